@@ -1,0 +1,186 @@
+/* libbns -- sampled batch normalisation for AMD MI355X (gfx950).
+ *
+ * Training-mode batch normalisation, forward and backward, in which the
+ * per-channel mean and variance are estimated from a sampled subset S of the
+ * activations ("Batch Normalization Sampling", Chen, Deng, Li et al.,
+ * arXiv 1810.10962).  Citations below are to that paper.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ * Layout     x, y, dy, dx are dense N x C x H x W tensors (channel planes of H*W
+ *            contiguous elements), element type given by bns_shape.dtype.  The
+ *            reduction axes are N, H, W, i.e. the paper's E_{0,1,2} / Var_{0,1,2}
+ *            on its N x H x W x C layout (Appendix A, notation).  Per-channel
+ *            vectors (gamma, beta, statistics, dgamma, dbeta) are float[C].
+ * Memory     Unless an argument is marked HOST it is a DEVICE pointer owned by
+ *            the caller, at least 16-byte aligned.  The library allocates and
+ *            frees nothing and keeps no state between calls except the tuning
+ *            overrides of bns_set_option.  `workspace` is caller-provided
+ *            device scratch of at least bns_workspace_bytes() bytes; its
+ *            contents need not be initialised and are undefined afterwards.
+ * Streams    `stream` is a hipStream_t passed as void* (NULL = the default
+ *            stream).  Work is enqueued on it and the call returns without
+ *            synchronising.  Calls that share a workspace must be ordered on
+ *            one stream.
+ * Aliasing   Outputs must not overlap inputs or each other (x is needed again
+ *            by the backward pass; dx is written while dy is read).
+ * Errors     Every call returns a bns_status.  Arguments are validated on the
+ *            host before anything is enqueued: BNS_EINVAL for NULL pointers,
+ *            non-positive extents, n_s outside [1, N] (Alg. 1), patch sizes
+ *            outside [1, H] x [1, W] (Alg. 2), VDN with n_s >= N, unknown
+ *            enums, misaligned pointers, overlapping buffers;
+ *            BNS_EUNSUPPORTED for extents beyond the limits listed at
+ *            bns_shape; BNS_EWORKSPACE when the workspace is too small;
+ *            BNS_EDEVICE when the HIP runtime reports a launch failure.
+ *            Nothing is thrown across the boundary.
+ * Determinism No floating-point atomics: per-channel sums are combined in a
+ *            fixed order, so results are bit-identical from run to run.
+ */
+#ifndef BNS_H
+#define BNS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BNS_OK = 0,
+    BNS_EINVAL = 1,
+    BNS_EUNSUPPORTED = 2,
+    BNS_EWORKSPACE = 3,
+    BNS_EDEVICE = 4
+} bns_status;
+
+/* Which activations feed the statistics. */
+typedef enum {
+    BNS_FULL = 0, /* all m = N*H*W points of a feature map (Eq. 2): plain BN                   */
+    BNS_NS = 1,   /* Naive Sampling: samples 0 .. n_s-1 (Alg. 1 with begin = 0)                */
+    BNS_BS = 2,   /* Batch Sampling: samples begin .. begin+n_s-1, begin = randint(0, N-n_s),
+                     one draw per (layer, epoch), shared by all channels (Alg. 1, Sec. 4.1)    */
+    BNS_FS = 3,   /* Feature Sampling: one patch_h x patch_w patch at (begin_h, begin_w) of
+                     every sample (Alg. 2); one location per layer, or one per channel         */
+    BNS_VDN = 4   /* Virtual Dataset Normalisation: the n_s virtual samples that the caller
+                     concatenated in front of the batch, samples 0 .. n_s-1 (Alg. 3)           */
+} bns_mode;
+
+typedef enum { BNS_F32 = 0, BNS_BF16 = 1 } bns_dtype; /* storage of x, y, dy, dx; arithmetic is fp32 */
+
+/* Tensor extents.  For VDN, N counts virtual + real samples (virtual first).
+ * Limits: N <= 65535, C <= 2^24, H*W < 2^31, N*H*W < 2^31, C*H*W < 2^31. */
+typedef struct {
+    int32_t N, C, H, W;
+    int32_t dtype; /* bns_dtype */
+} bns_shape;
+
+/* Sampling specification.  (seed, layer_id, epoch) select the random index: the paper
+ * refreshes indices once per epoch and draws them independently per layer (Sec. 4.1). */
+typedef struct {
+    int32_t mode;             /* bns_mode */
+    int32_t n_s;              /* NS/BS: samples kept; VDN: number of virtual samples; else ignored */
+    int32_t patch_h, patch_w; /* FS: patch extent; else ignored */
+    int32_t fs_per_channel;   /* FS: 0 = one patch location per layer (the paper's rule),
+                                 1 = an independent location for each channel */
+    uint32_t layer_id;
+    uint32_t epoch;
+} bns_spec;
+
+/* The location set S of one channel: the box [n0, n0+n_cnt) x [h0, h0+h_cnt) x [w0, w0+w_cnt). */
+typedef struct {
+    int32_t n0, n_cnt, h0, h_cnt, w0, w_cnt;
+} bns_box;
+
+const char* bns_status_string(bns_status s);
+
+/* Sampling index, computed on the host (Alg. 1-3; "randint" includes both ends).
+ * boxes: HOST array of shape->C entries, written.  A pure integer function of
+ * (shape, spec, seed): 64-bit SplitMix64-style mixing of seed, layer_id, epoch, the
+ * coordinate being drawn and (per-channel FS only) the channel; the top 32 bits are
+ * scaled to the number of outcomes.  No device is touched. */
+bns_status bns_sample_index(const bns_shape* shape, const bns_spec* spec, uint64_t seed,
+                            bns_box* boxes /* HOST, C entries */);
+
+/* The same index evaluated by the generator the kernels use, on the device.
+ * boxes: DEVICE array of shape->C entries, written on `stream`. */
+bns_status bns_sample_index_device(const bns_shape* shape, const bns_spec* spec, uint64_t seed,
+                                   bns_box* boxes /* DEVICE, C entries */, void* stream);
+
+/* Bytes of device scratch that bns_forward / bns_backward and their stages need. */
+size_t bns_workspace_bytes(const bns_shape* shape, const bns_spec* spec);
+
+/* Forward (Eq. 1 with the statistics of Eq. 3):
+ *   save_mean[c]   = E    = mean of x over S_c
+ *   save_invstd[c] = 1 / sqrt(Var + eps), Var = biased variance of x over S_c
+ *   y = gamma * (x - E) * invstd + beta                       for all N*H*W points
+ *   running_mean/var <- (1 - momentum) * running + momentum * (E | Var)     (Eq. 8; pass
+ *   momentum = 1 for its first-iteration branch); either may be NULL = not kept.
+ * in: x, gamma, beta.  out: y, save_mean, save_invstd.  in-out: running_*. */
+bns_status bns_forward(const bns_shape* shape, const bns_spec* spec, uint64_t seed,
+                       const void* x, const float* gamma, const float* beta,
+                       float eps, float momentum,
+                       void* y, float* save_mean, float* save_invstd,
+                       float* running_mean, float* running_var,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward (Eq. 5 with the modification of Eq. 6).  With g = dl/dy, r = save_invstd,
+ * x^ = (x - save_mean) * r and s = |S_c|:
+ *   dbeta[c]  = sum over all m points of g
+ *   dgamma[c] = sum over all m points of g * x^
+ *   dx_i = gamma r g_i                                            for x_i outside S
+ *   dx_i = gamma r (g_i - (dbeta + x^_i dgamma) / s)              for x_i in S
+ * (Eq. 6 after substituting dl/dE and dl/dVar of Eq. 5).  The index is re-derived from
+ * (spec, seed), which must equal the forward call's.
+ * in: x, dy, gamma, save_mean, save_invstd.  out: dx, dgamma, dbeta. */
+bns_status bns_backward(const bns_shape* shape, const bns_spec* spec, uint64_t seed,
+                        const void* x, const void* dy, const float* gamma,
+                        const float* save_mean, const float* save_invstd,
+                        void* dx, float* dgamma, float* dbeta,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* The stages that the two calls above are made of, for callers that want to place
+ * other work between them (and for per-kernel timing).  Same conventions.
+ *
+ * bns_forward_stats     Eq. 3 + Eq. 8: statistics of x over S and running averages.
+ * bns_forward_normalize Eq. 1: y from x and the saved statistics, all points.
+ * bns_backward_reduce   the two length-m sums of Eq. 5: dbeta and dgamma.
+ * bns_backward_dx       Eq. 6: dx from dy, (x on S), the statistics and dgamma, dbeta. */
+bns_status bns_forward_stats(const bns_shape* shape, const bns_spec* spec, uint64_t seed,
+                             const void* x, float eps, float momentum,
+                             float* save_mean, float* save_invstd,
+                             float* running_mean, float* running_var,
+                             void* workspace, size_t workspace_bytes, void* stream);
+bns_status bns_forward_normalize(const bns_shape* shape, const void* x,
+                                 const float* gamma, const float* beta,
+                                 const float* save_mean, const float* save_invstd,
+                                 void* y, void* stream);
+bns_status bns_backward_reduce(const bns_shape* shape, const void* x, const void* dy,
+                               const float* save_mean, const float* save_invstd,
+                               float* dgamma, float* dbeta,
+                               void* workspace, size_t workspace_bytes, void* stream);
+bns_status bns_backward_dx(const bns_shape* shape, const bns_spec* spec, uint64_t seed,
+                           const void* x, const void* dy, const float* gamma,
+                           const float* save_mean, const float* save_invstd,
+                           const float* dgamma, const float* dbeta,
+                           void* dx, void* stream);
+
+/* Plain device-to-device copy of `bytes` bytes (a multiple of 16) with 128-bit accesses:
+ * the "achievable bandwidth" yardstick that the benchmark reports beside the BN kernels,
+ * and the known-size kernel that hardware traffic counters are calibrated against. */
+bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* stream);
+
+/* Process-wide tuning overrides for benchmarking; value 0 restores the automatic choice.
+ *   "splits_stats"   blocks per channel in the statistics reduction      (1..64)
+ *   "splits_reduce"  blocks per channel in the backward reduction        (1..64)
+ *   "channel_group"  bns_forward / bns_backward walk the channels in groups of this many,
+ *                    running every stage on one group before the next, so that a group's
+ *                    second read of dy / x can be served from the last-level cache   (1..C)
+ * Returns BNS_EINVAL for an unknown name or a value out of range.  name: HOST string. */
+bns_status bns_set_option(const char* name, int32_t value);
+int32_t bns_get_option(const char* name); /* -1 for an unknown name */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BNS_H */

@@ -1,0 +1,297 @@
+// C ABI of libbns: argument validation and launch sequencing.  See include/bns.h for
+// the contract of every entry point.  No allocation, no synchronisation, no state
+// except the tuning overrides.
+#include <hip/hip_runtime.h>
+#include <string.h>
+
+#include <atomic>
+
+#include "../../include/bns.h"
+#include "bns_internal.hpp"
+
+using namespace bns;
+
+namespace {
+
+std::atomic<int32_t> g_splits_stats{0};
+std::atomic<int32_t> g_splits_reduce{0};
+std::atomic<int32_t> g_channel_group{0};
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline bool overlap(const void* a, size_t na, const void* b, size_t nb) {
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
+    return pa < pb + nb && pb < pa + na;
+}
+
+bns_status check_shape(const bns_shape* sh, Dims* d) {
+    if (!sh) return BNS_EINVAL;
+    if (sh->N <= 0 || sh->C <= 0 || sh->H <= 0 || sh->W <= 0) return BNS_EINVAL;
+    if (sh->dtype != BNS_F32 && sh->dtype != BNS_BF16) return BNS_EINVAL;
+    const int64_t hw = int64_t(sh->H) * sh->W;
+    const int64_t lim = int64_t(1) << 31;
+    if (sh->N > 65535 || sh->C > (1 << 24) || hw >= lim || hw * sh->N >= lim || hw * sh->C >= lim)
+        return BNS_EUNSUPPORTED;
+    d->N = sh->N;
+    d->C = sh->C;
+    d->H = sh->H;
+    d->W = sh->W;
+    d->HW = int32_t(hw);
+    d->dtype = sh->dtype;
+    if (sh->dtype == BNS_BF16 && hw % 8 == 0)
+        d->vec = 8;
+    else if (hw % 4 == 0)
+        d->vec = 4;
+    else
+        d->vec = 1;
+    return BNS_OK;
+}
+
+bns_status check_spec(const bns_shape* sh, const bns_spec* sp) {
+    if (!sp) return BNS_EINVAL;
+    switch (sp->mode) {
+        case BNS_FULL:
+            return BNS_OK;
+        case BNS_NS:
+        case BNS_BS:
+            return (sp->n_s >= 1 && sp->n_s <= sh->N) ? BNS_OK : BNS_EINVAL;   // n_s in (0, N], Alg. 1
+        case BNS_VDN:
+            return (sp->n_s >= 1 && sp->n_s < sh->N) ? BNS_OK : BNS_EINVAL;    // at least one real sample
+        case BNS_FS:
+            if (sp->fs_per_channel != 0 && sp->fs_per_channel != 1) return BNS_EINVAL;
+            return (sp->patch_h >= 1 && sp->patch_h <= sh->H && sp->patch_w >= 1 && sp->patch_w <= sh->W)
+                       ? BNS_OK
+                       : BNS_EINVAL;                                           // h_s in (0, H], w_s in (0, W], Alg. 2
+        default:
+            return BNS_EINVAL;
+    }
+}
+
+inline size_t elem_bytes(const Dims& d) { return d.dtype == BNS_F32 ? 4 : 2; }
+inline size_t tensor_bytes(const Dims& d) { return size_t(d.N) * d.C * d.HW * elem_bytes(d); }
+inline size_t workspace_need(const Dims& d) { return size_t(d.C) * kMaxSplits * sizeof(Partial); }
+
+inline bns_status dev(hipError_t e) { return e == hipSuccess ? BNS_OK : BNS_EDEVICE; }
+
+int stats_splits(const Dims& d, const IndexParams& ip, int cg) {
+    const int32_t o = g_splits_stats.load();
+    if (o > 0) return o;
+    const bns_box& b = ip.shared;
+    const bool planes = !ip.per_channel && b.h_cnt == d.H && b.w_cnt == d.W && d.vec > 1;
+    const uint64_t pts = uint64_t(b.n_cnt) * b.h_cnt * b.w_cnt;
+    return auto_splits(cg, uint32_t(planes ? pts / d.vec : pts / 4));
+}
+
+int reduce_splits(const Dims& d, int cg) {
+    const int32_t o = g_splits_reduce.load();
+    if (o > 0) return o;
+    return auto_splits(cg, uint32_t(uint64_t(d.N) * d.HW / d.vec));
+}
+
+int channel_group(const Dims& d) {
+    const int32_t o = g_channel_group.load();
+    if (o > 0 && o < d.C) return o;
+    return d.C;
+}
+
+// ---- stage bodies on a channel range (arguments already validated) ----------------
+bns_status stats_range(const Dims& d, const IndexParams& ip, const void* x, float eps, float momentum,
+                       float* save_mean, float* save_invstd, float* rm, float* rv, Partial* ws, int c0, int cg,
+                       hipStream_t st) {
+    const int splits = stats_splits(d, ip, cg);
+    if (launch_stats_partial(d, ip, x, ws, splits, c0, cg, st) != hipSuccess) return BNS_EDEVICE;
+    return dev(launch_stats_finalize(d, ip, x, ws, splits, c0, cg, eps, momentum, save_mean, save_invstd, rm, rv, st));
+}
+
+bns_status reduce_range(const Dims& d, const void* x, const void* dy, const float* save_mean,
+                        const float* save_invstd, float* dgamma, float* dbeta, Partial* ws, int c0, int cg,
+                        hipStream_t st) {
+    const int splits = reduce_splits(d, cg);
+    if (launch_reduce_partial(d, x, dy, save_mean, ws, splits, c0, cg, st) != hipSuccess) return BNS_EDEVICE;
+    return dev(launch_reduce_finalize(d, ws, splits, c0, cg, save_invstd, dgamma, dbeta, st));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* bns_status_string(bns_status s) {
+    switch (s) {
+        case BNS_OK: return "BNS_OK";
+        case BNS_EINVAL: return "BNS_EINVAL: invalid argument";
+        case BNS_EUNSUPPORTED: return "BNS_EUNSUPPORTED: extent beyond the supported limits";
+        case BNS_EWORKSPACE: return "BNS_EWORKSPACE: workspace too small";
+        case BNS_EDEVICE: return "BNS_EDEVICE: HIP launch failed";
+        default: return "unknown bns_status";
+    }
+}
+
+bns_status bns_sample_index(const bns_shape* shape, const bns_spec* spec, uint64_t seed, bns_box* boxes) {
+    Dims d;
+    bns_status s = check_shape(shape, &d);
+    if (s != BNS_OK) return s;
+    if ((s = check_spec(shape, spec)) != BNS_OK) return s;
+    if (!boxes) return BNS_EINVAL;
+    const IndexParams ip = make_index_params(*shape, *spec, seed);
+    for (int c = 0; c < d.C; ++c) boxes[c] = box_of_channel(ip, c);
+    return BNS_OK;
+}
+
+bns_status bns_sample_index_device(const bns_shape* shape, const bns_spec* spec, uint64_t seed, bns_box* boxes,
+                                   void* stream) {
+    Dims d;
+    bns_status s = check_shape(shape, &d);
+    if (s != BNS_OK) return s;
+    if ((s = check_spec(shape, spec)) != BNS_OK) return s;
+    if (!boxes) return BNS_EINVAL;
+    const IndexParams ip = make_index_params(*shape, *spec, seed);
+    return dev(launch_index_boxes(ip, d.C, boxes, static_cast<hipStream_t>(stream)));
+}
+
+size_t bns_workspace_bytes(const bns_shape* shape, const bns_spec* spec) {
+    (void)spec;
+    Dims d;
+    if (check_shape(shape, &d) != BNS_OK) return 0;
+    return workspace_need(d);
+}
+
+bns_status bns_forward_stats(const bns_shape* shape, const bns_spec* spec, uint64_t seed, const void* x, float eps,
+                             float momentum, float* save_mean, float* save_invstd, float* running_mean,
+                             float* running_var, void* workspace, size_t workspace_bytes, void* stream) {
+    Dims d;
+    bns_status s = check_shape(shape, &d);
+    if (s != BNS_OK) return s;
+    if ((s = check_spec(shape, spec)) != BNS_OK) return s;
+    if (!x || !save_mean || !save_invstd || !workspace) return BNS_EINVAL;
+    if (!aligned16(x) || !aligned16(workspace)) return BNS_EINVAL;
+    if (!(eps >= 0.f) || !(momentum >= 0.f && momentum <= 1.f)) return BNS_EINVAL;
+    if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
+    const IndexParams ip = make_index_params(*shape, *spec, seed);
+    return stats_range(d, ip, x, eps, momentum, save_mean, save_invstd, running_mean, running_var,
+                       static_cast<Partial*>(workspace), 0, d.C, static_cast<hipStream_t>(stream));
+}
+
+bns_status bns_forward_normalize(const bns_shape* shape, const void* x, const float* gamma, const float* beta,
+                                 const float* save_mean, const float* save_invstd, void* y, void* stream) {
+    Dims d;
+    bns_status s = check_shape(shape, &d);
+    if (s != BNS_OK) return s;
+    if (!x || !gamma || !beta || !save_mean || !save_invstd || !y) return BNS_EINVAL;
+    if (!aligned16(x) || !aligned16(y)) return BNS_EINVAL;
+    if (overlap(x, tensor_bytes(d), y, tensor_bytes(d))) return BNS_EINVAL;
+    return dev(launch_normalize(d, x, gamma, beta, save_mean, save_invstd, y, 0, d.C, static_cast<hipStream_t>(stream)));
+}
+
+bns_status bns_forward(const bns_shape* shape, const bns_spec* spec, uint64_t seed, const void* x,
+                       const float* gamma, const float* beta, float eps, float momentum, void* y, float* save_mean,
+                       float* save_invstd, float* running_mean, float* running_var, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+    Dims d;
+    bns_status s = check_shape(shape, &d);
+    if (s != BNS_OK) return s;
+    if ((s = check_spec(shape, spec)) != BNS_OK) return s;
+    if (!x || !gamma || !beta || !y || !save_mean || !save_invstd || !workspace) return BNS_EINVAL;
+    if (!aligned16(x) || !aligned16(y) || !aligned16(workspace)) return BNS_EINVAL;
+    if (overlap(x, tensor_bytes(d), y, tensor_bytes(d))) return BNS_EINVAL;
+    if (!(eps >= 0.f) || !(momentum >= 0.f && momentum <= 1.f)) return BNS_EINVAL;
+    if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
+    const IndexParams ip = make_index_params(*shape, *spec, seed);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Partial* ws = static_cast<Partial*>(workspace);
+    const int G = channel_group(d);
+    for (int c0 = 0; c0 < d.C; c0 += G) {
+        const int cg = (d.C - c0 < G) ? d.C - c0 : G;
+        s = stats_range(d, ip, x, eps, momentum, save_mean, save_invstd, running_mean, running_var, ws, c0, cg, st);
+        if (s != BNS_OK) return s;
+        s = dev(launch_normalize(d, x, gamma, beta, save_mean, save_invstd, y, c0, cg, st));
+        if (s != BNS_OK) return s;
+    }
+    return BNS_OK;
+}
+
+bns_status bns_backward_reduce(const bns_shape* shape, const void* x, const void* dy, const float* save_mean,
+                               const float* save_invstd, float* dgamma, float* dbeta, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+    Dims d;
+    bns_status s = check_shape(shape, &d);
+    if (s != BNS_OK) return s;
+    if (!x || !dy || !save_mean || !save_invstd || !dgamma || !dbeta || !workspace) return BNS_EINVAL;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(workspace)) return BNS_EINVAL;
+    if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
+    return reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, static_cast<Partial*>(workspace), 0, d.C,
+                        static_cast<hipStream_t>(stream));
+}
+
+bns_status bns_backward_dx(const bns_shape* shape, const bns_spec* spec, uint64_t seed, const void* x,
+                           const void* dy, const float* gamma, const float* save_mean, const float* save_invstd,
+                           const float* dgamma, const float* dbeta, void* dx, void* stream) {
+    Dims d;
+    bns_status s = check_shape(shape, &d);
+    if (s != BNS_OK) return s;
+    if ((s = check_spec(shape, spec)) != BNS_OK) return s;
+    if (!x || !dy || !gamma || !save_mean || !save_invstd || !dgamma || !dbeta || !dx) return BNS_EINVAL;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx)) return BNS_EINVAL;
+    const size_t tb = tensor_bytes(d);
+    if (overlap(dx, tb, x, tb) || overlap(dx, tb, dy, tb)) return BNS_EINVAL;
+    const IndexParams ip = make_index_params(*shape, *spec, seed);
+    return dev(launch_dx(d, ip, x, dy, gamma, save_mean, save_invstd, dgamma, dbeta, dx, 0, d.C,
+                         static_cast<hipStream_t>(stream)));
+}
+
+bns_status bns_backward(const bns_shape* shape, const bns_spec* spec, uint64_t seed, const void* x, const void* dy,
+                        const float* gamma, const float* save_mean, const float* save_invstd, void* dx,
+                        float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes, void* stream) {
+    Dims d;
+    bns_status s = check_shape(shape, &d);
+    if (s != BNS_OK) return s;
+    if ((s = check_spec(shape, spec)) != BNS_OK) return s;
+    if (!x || !dy || !gamma || !save_mean || !save_invstd || !dx || !dgamma || !dbeta || !workspace)
+        return BNS_EINVAL;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || !aligned16(workspace)) return BNS_EINVAL;
+    const size_t tb = tensor_bytes(d);
+    if (overlap(dx, tb, x, tb) || overlap(dx, tb, dy, tb)) return BNS_EINVAL;
+    if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
+    const IndexParams ip = make_index_params(*shape, *spec, seed);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Partial* ws = static_cast<Partial*>(workspace);
+    const int G = channel_group(d);
+    for (int c0 = 0; c0 < d.C; c0 += G) {
+        const int cg = (d.C - c0 < G) ? d.C - c0 : G;
+        s = reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, ws, c0, cg, st);
+        if (s != BNS_OK) return s;
+        s = dev(launch_dx(d, ip, x, dy, gamma, save_mean, save_invstd, dgamma, dbeta, dx, c0, cg, st));
+        if (s != BNS_OK) return s;
+    }
+    return BNS_OK;
+}
+
+bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src || (bytes & 15u) || !aligned16(dst) || !aligned16(src)) return BNS_EINVAL;
+    if ((bytes / 16 + 1023) / 1024 >= (size_t(1) << 31)) return BNS_EUNSUPPORTED;
+    if (overlap(dst, bytes, src, bytes)) return BNS_EINVAL;
+    return dev(launch_copy(dst, src, bytes, static_cast<hipStream_t>(stream)));
+}
+
+bns_status bns_set_option(const char* name, int32_t value) {
+    if (!name || value < 0) return BNS_EINVAL;
+    if (!strcmp(name, "splits_stats") || !strcmp(name, "splits_reduce")) {
+        if (value > kMaxSplits) return BNS_EINVAL;
+        (name[7] == 's' ? g_splits_stats : g_splits_reduce).store(value);
+        return BNS_OK;
+    }
+    if (!strcmp(name, "channel_group")) {
+        g_channel_group.store(value);
+        return BNS_OK;
+    }
+    return BNS_EINVAL;
+}
+
+int32_t bns_get_option(const char* name) {
+    if (!name) return -1;
+    if (!strcmp(name, "splits_stats")) return g_splits_stats.load();
+    if (!strcmp(name, "splits_reduce")) return g_splits_reduce.load();
+    if (!strcmp(name, "channel_group")) return g_channel_group.load();
+    return -1;
+}
+
+}  // extern "C"

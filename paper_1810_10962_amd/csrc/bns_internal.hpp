@@ -1,0 +1,53 @@
+// Host-side launch interface between the C ABI (bns_api.hip) and the kernels
+// (bns_kernels.hip).  Every launcher works on the channel range [c0, c0 + cg).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "bns_index.hpp"
+
+namespace bns {
+
+constexpr int kMaxSplits = 64;  // upper bound on blocks that share one channel's reduction
+
+struct Dims {
+    int32_t N, C, H, W;
+    int32_t HW;     // H * W
+    int32_t dtype;  // bns_dtype
+    int32_t vec;    // elements per memory access: largest of {8 (bf16 only), 4, 1} dividing HW
+};
+
+// One (sum, sum) pair per channel and split.
+struct Partial {
+    float a, b;
+};
+
+// Forward statistics (Eq. 3): partial sums of (x - pivot) and (x - pivot)^2 over S.
+hipError_t launch_stats_partial(const Dims& d, const IndexParams& ip, const void* x, Partial* partial,
+                                int splits, int c0, int cg, hipStream_t st);
+// Fixed-order combine, mean / inv-std, running averages (Eq. 8).
+hipError_t launch_stats_finalize(const Dims& d, const IndexParams& ip, const void* x, const Partial* partial,
+                                 int splits, int c0, int cg, float eps, float momentum,
+                                 float* save_mean, float* save_invstd, float* running_mean,
+                                 float* running_var, hipStream_t st);
+// Eq. 1 over every element.
+hipError_t launch_normalize(const Dims& d, const void* x, const float* gamma, const float* beta,
+                            const float* mean, const float* invstd, void* y, int c0, int cg, hipStream_t st);
+// Backward sums of Eq. 5 over all m points: partial sums of dy and dy * (x - mean).
+hipError_t launch_reduce_partial(const Dims& d, const void* x, const void* dy, const float* mean,
+                                 Partial* partial, int splits, int c0, int cg, hipStream_t st);
+hipError_t launch_reduce_finalize(const Dims& d, const Partial* partial, int splits, int c0, int cg,
+                                  const float* invstd, float* dgamma, float* dbeta, hipStream_t st);
+// Eq. 6 over every element.
+hipError_t launch_dx(const Dims& d, const IndexParams& ip, const void* x, const void* dy, const float* gamma,
+                     const float* mean, const float* invstd, const float* dgamma, const float* dbeta,
+                     void* dx, int c0, int cg, hipStream_t st);
+
+hipError_t launch_index_boxes(const IndexParams& ip, int C, bns_box* boxes, hipStream_t st);
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+
+// Blocks per channel for a reduction over `vectors_per_channel` memory accesses.
+int auto_splits(int cg, uint32_t vectors_per_channel);
+
+}  // namespace bns

@@ -1,0 +1,505 @@
+// HIP kernels of libbns for gfx950 (wave64).  All of them are bound by HBM traffic:
+// a few flops per element moved, so no matrix cores; the work is to keep every access
+// 128 bits wide and coalesced, to touch only the bytes the method needs, and to keep
+// enough loads in flight.
+//
+// Data layout: N x C x H x W.  A channel is N planes of HW contiguous elements, one per
+// sample, (C * HW) elements apart.  Within one sample the planes of consecutive channels
+// are adjacent, so a channel range [c0, c0 + cg) of one sample is ONE contiguous run of
+// cg * HW elements: the element-wise kernels walk that run with flat 128-bit accesses and
+// recover the channel of an access with one multiply-shift division.
+#include <hip/hip_runtime.h>
+
+#include "bns_device.hpp"
+#include "bns_internal.hpp"
+
+namespace bns {
+
+// ===========================================================================
+// Forward statistics over the location set S (Eq. 3)
+// ===========================================================================
+// Sums are taken of (x - pivot), pivot = the first sampled element of the channel, so
+// that Var = E[d^2] - E[d]^2 does not cancel when |mean| >> std.
+
+// S made of whole planes (FULL, NS, BS, VDN) with HW a multiple of V.
+// grid.x = cg * splits; block (c, k) reduces vectors [k * per_block, (k + 1) * per_block)
+// of the n_cnt * HW / V vectors of channel c.
+template <typename T, int V>
+__global__ __launch_bounds__(kBlock) void stats_partial_planes_kernel(
+    const T* __restrict__ x, Partial* __restrict__ partial, IndexParams ip, int C, int HW,
+    FastDiv hwv_div, int c0, int splits, uint32_t per_block) {
+    __shared__ float lds[2 * (kBlock / kWave)];
+    const int cl = blockIdx.x / splits;
+    const int k = blockIdx.x - cl * splits;
+    const int c = c0 + cl;
+    const bns_box b = ip.shared;                                   // planes: never per-channel
+    const uint32_t hwv = hwv_div.d;
+    const uint32_t tot = uint32_t(b.n_cnt) * hwv;
+    const uint32_t j0 = uint32_t(k) * per_block;
+    const uint32_t j1 = min(j0 + per_block, tot);
+    const size_t nstride = size_t(C) * HW;
+    const T* base = x + (size_t(b.n0) * C + c) * HW;                // plane (n0, c)
+    const float pivot = load_scalar<T>(base);
+
+    float s1[2] = {0.f, 0.f}, s2[2] = {0.f, 0.f};
+    uint32_t j = j0 + threadIdx.x;
+    for (; j + 3u * kBlock < j1; j += 4u * kBlock) {
+        Vec<T, V> v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t ju = j + u * kBlock;
+            const uint32_t n = fdiv(ju, hwv_div);
+            v[u].load(base + n * nstride + size_t(ju - n * hwv) * V);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+                const float dlt = v[u].f[i] - pivot;
+                s1[u & 1] += dlt;
+                s2[u & 1] = fmaf(dlt, dlt, s2[u & 1]);
+            }
+    }
+    for (; j < j1; j += kBlock) {
+        const uint32_t n = fdiv(j, hwv_div);
+        Vec<T, V> v;
+        v.load(base + n * nstride + size_t(j - n * hwv) * V);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const float dlt = v.f[i] - pivot;
+            s1[0] += dlt;
+            s2[0] = fmaf(dlt, dlt, s2[0]);
+        }
+    }
+    float a = s1[0] + s1[1], q = s2[0] + s2[1];
+    block_sum2(a, q, lds);
+    if (threadIdx.x == 0) partial[size_t(c) * splits + k] = Partial{a, q};
+}
+
+// S a rectangular patch of every sampled plane (FS), or planes whose size is not a
+// multiple of the vector width.  Scalar accesses: patch rows are short and unaligned.
+// Element j of the n_cnt * h_cnt * w_cnt sampled points -> (n, ph, pw) by two divisions.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void stats_partial_patch_kernel(
+    const T* __restrict__ x, Partial* __restrict__ partial, IndexParams ip, int C, int W, int HW,
+    FastDiv patch_div, FastDiv pw_div, int c0, int splits, uint32_t per_block) {
+    __shared__ float lds[2 * (kBlock / kWave)];
+    const int cl = blockIdx.x / splits;
+    const int k = blockIdx.x - cl * splits;
+    const int c = c0 + cl;
+    const bns_box b = box_of_channel(ip, c);
+    const uint32_t tot = uint32_t(b.n_cnt) * patch_div.d;
+    const uint32_t j0 = uint32_t(k) * per_block;
+    const uint32_t j1 = min(j0 + per_block, tot);
+    const size_t nstride = size_t(C) * HW;
+    const T* base = x + (size_t(b.n0) * C + c) * HW + size_t(b.h0) * W + b.w0;   // first sampled element
+    const float pivot = load_scalar<T>(base);
+
+    float s1 = 0.f, s2 = 0.f;
+    for (uint32_t j = j0 + threadIdx.x; j < j1; j += kBlock) {
+        const uint32_t n = fdiv(j, patch_div);
+        const uint32_t r = j - n * patch_div.d;
+        const uint32_t ph = fdiv(r, pw_div);
+        const uint32_t pw = r - ph * pw_div.d;
+        const float dlt = load_scalar<T>(base + n * nstride + size_t(ph) * W + pw) - pivot;
+        s1 += dlt;
+        s2 = fmaf(dlt, dlt, s2);
+    }
+    block_sum2(s1, s2, lds);
+    if (threadIdx.x == 0) partial[size_t(c) * splits + k] = Partial{s1, s2};
+}
+
+// One thread per channel: add the splits in index order (fp64), then Eq. 3 and Eq. 8.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void stats_finalize_kernel(
+    const T* __restrict__ x, const Partial* __restrict__ partial, IndexParams ip, int C, int W, int HW,
+    int splits, int c0, int cg, float eps, float momentum, float* __restrict__ save_mean,
+    float* __restrict__ save_invstd, float* __restrict__ running_mean, float* __restrict__ running_var) {
+    const int cl = blockIdx.x * kBlock + threadIdx.x;
+    if (cl >= cg) return;
+    const int c = c0 + cl;
+    const bns_box b = box_of_channel(ip, c);
+    const double s = double(b.n_cnt) * double(b.h_cnt) * double(b.w_cnt);
+    const double pivot = load_scalar<T>(x + (size_t(b.n0) * C + c) * HW + size_t(b.h0) * W + b.w0);
+    double s1 = 0.0, s2 = 0.0;
+    for (int k = 0; k < splits; ++k) {
+        const Partial p = partial[size_t(c) * splits + k];
+        s1 += double(p.a);
+        s2 += double(p.b);
+    }
+    const double m1 = s1 / s;
+    const double mean = pivot + m1;
+    double var = s2 / s - m1 * m1;
+    if (var < 0.0) var = 0.0;
+    save_mean[c] = float(mean);
+    save_invstd[c] = float(1.0 / sqrt(var + double(eps)));
+    const double a = double(momentum);
+    if (running_mean) running_mean[c] = float((1.0 - a) * double(running_mean[c]) + a * mean);
+    if (running_var) running_var[c] = float((1.0 - a) * double(running_var[c]) + a * var);
+}
+
+// ===========================================================================
+// Forward normalise + affine over every element (Eq. 1)
+// ===========================================================================
+// grid = (ceil(cg * HW / V / (kBlock * U)), N).  Block (bx, n) handles kBlock * U
+// consecutive vectors of the contiguous run [c0, c0 + cg) x HW of sample n.
+template <typename T, int V, int U>
+__global__ __launch_bounds__(kBlock) void normalize_kernel(
+    const T* __restrict__ x, T* __restrict__ y, const float* __restrict__ gamma,
+    const float* __restrict__ beta, const float* __restrict__ mean, const float* __restrict__ invstd,
+    int C, int HW, FastDiv hwv_div, int c0, uint32_t run_vectors) {
+    const size_t run0 = (size_t(blockIdx.y) * C + c0) * HW;
+    const T* xr = x + run0;
+    T* yr = y + run0;
+    const uint32_t v0 = blockIdx.x * uint32_t(kBlock * U) + threadIdx.x;
+
+    Vec<T, V> v[U];
+    float mu[U], sc[U], sh[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t vi = v0 + u * kBlock;
+        if (vi < run_vectors) v[u].load(xr + size_t(vi) * V);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t vi = v0 + u * kBlock;
+        if (vi < run_vectors) {
+            const int c = c0 + int(fdiv(vi, hwv_div));
+            mu[u] = mean[c];
+            sc[u] = gamma[c] * invstd[c];
+            sh[u] = beta[c];
+        }
+    }
+    // (x - mean) first: exact when x is close to the mean, where folding the mean into the
+    // shift (x * sc + (beta - mean * sc)) would cancel.
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t vi = v0 + u * kBlock;
+        if (vi < run_vectors) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) v[u].f[i] = fmaf(v[u].f[i] - mu[u], sc[u], sh[u]);
+            v[u].store(yr + size_t(vi) * V);
+        }
+    }
+}
+
+// ===========================================================================
+// Backward reductions over all m points (Eq. 5): sum dy, sum dy * (x - mean)
+// ===========================================================================
+// grid.x = cg * splits, block (c, k) as in stats_partial_planes_kernel with S = everything.
+template <typename T, int V>
+__global__ __launch_bounds__(kBlock) void reduce_partial_kernel(
+    const T* __restrict__ x, const T* __restrict__ dy, const float* __restrict__ mean,
+    Partial* __restrict__ partial, int C, int HW, FastDiv hwv_div, int c0, int splits, uint32_t per_block,
+    uint32_t tot) {
+    __shared__ float lds[2 * (kBlock / kWave)];
+    const int cl = blockIdx.x / splits;
+    const int k = blockIdx.x - cl * splits;
+    const int c = c0 + cl;
+    const uint32_t hwv = hwv_div.d;
+    const uint32_t j0 = uint32_t(k) * per_block;
+    const uint32_t j1 = min(j0 + per_block, tot);
+    const size_t nstride = size_t(C) * HW;
+    const size_t cbase = size_t(c) * HW;
+    const float mu = mean[c];
+
+    float s1[2] = {0.f, 0.f}, s2[2] = {0.f, 0.f};
+    uint32_t j = j0 + threadIdx.x;
+    for (; j + 1u * kBlock < j1; j += 2u * kBlock) {
+        Vec<T, V> g[2], v[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint32_t ju = j + u * kBlock;
+            const uint32_t n = fdiv(ju, hwv_div);
+            const size_t off = cbase + n * nstride + size_t(ju - n * hwv) * V;
+            g[u].load(dy + off);
+            v[u].load(x + off);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+                s1[u] += g[u].f[i];
+                s2[u] = fmaf(g[u].f[i], v[u].f[i] - mu, s2[u]);
+            }
+    }
+    for (; j < j1; j += kBlock) {
+        const uint32_t n = fdiv(j, hwv_div);
+        const size_t off = cbase + n * nstride + size_t(j - n * hwv) * V;
+        Vec<T, V> g, v;
+        g.load(dy + off);
+        v.load(x + off);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            s1[0] += g.f[i];
+            s2[0] = fmaf(g.f[i], v.f[i] - mu, s2[0]);
+        }
+    }
+    float a = s1[0] + s1[1], q = s2[0] + s2[1];
+    block_sum2(a, q, lds);
+    if (threadIdx.x == 0) partial[size_t(c) * splits + k] = Partial{a, q};
+}
+
+__global__ __launch_bounds__(kBlock) void reduce_finalize_kernel(
+    const Partial* __restrict__ partial, int splits, int c0, int cg, const float* __restrict__ invstd,
+    float* __restrict__ dgamma, float* __restrict__ dbeta) {
+    const int cl = blockIdx.x * kBlock + threadIdx.x;
+    if (cl >= cg) return;
+    const int c = c0 + cl;
+    double s1 = 0.0, s2 = 0.0;
+    for (int k = 0; k < splits; ++k) {
+        const Partial p = partial[size_t(c) * splits + k];
+        s1 += double(p.a);
+        s2 += double(p.b);
+    }
+    dbeta[c] = float(s1);
+    dgamma[c] = float(s2 * double(invstd[c]));
+}
+
+// ===========================================================================
+// Backward dx over every element (Eq. 6)
+// ===========================================================================
+// Same walk as normalize_kernel.  dx = a * dy everywhere (a = gamma * invstd); the
+// 1/s terms of Eq. 6 are subtracted only where the element lies in S, and x is loaded
+// only by accesses that intersect S.
+template <typename T, int V, int U>
+__global__ __launch_bounds__(kBlock) void dx_kernel(
+    const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx, const float* __restrict__ gamma,
+    const float* __restrict__ mean, const float* __restrict__ invstd, const float* __restrict__ dgamma,
+    const float* __restrict__ dbeta, IndexParams ip, int C, int W, int HW, FastDiv hwv_div, FastDiv w_div,
+    int c0, uint32_t run_vectors, float inv_s) {
+    const int n = blockIdx.y;
+    const size_t run0 = (size_t(n) * C + c0) * HW;
+    const T* xr = x + run0;
+    const T* gr = dy + run0;
+    T* dr = dx + run0;
+    const uint32_t v0 = blockIdx.x * uint32_t(kBlock * U) + threadIdx.x;
+    const uint32_t hwv = hwv_div.d;
+
+    Vec<T, V> g[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t vi = v0 + u * kBlock;
+        if (vi < run_vectors) g[u].load(gr + size_t(vi) * V);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t vi = v0 + u * kBlock;
+        if (vi >= run_vectors) continue;
+        const uint32_t cl = fdiv(vi, hwv_div);
+        const int c = c0 + int(cl);
+        const uint32_t e0 = (vi - cl * hwv) * V;                  // first element, within its plane
+        const bns_box b = box_of_channel(ip, c);
+        const float r = invstd[c];
+        const float a = gamma[c] * r;
+        // rows [h0, h0 + h_cnt) of the plane are the elements [h0 * W, (h0 + h_cnt) * W)
+        const bool touches = n >= b.n0 && n < b.n0 + b.n_cnt && e0 + V > uint32_t(b.h0) * W &&
+                             e0 < uint32_t(b.h0 + b.h_cnt) * W;
+        if (touches) {
+            Vec<T, V> xv;
+            xv.load(xr + size_t(vi) * V);
+            const float mu = mean[c];
+            const float k1 = a * inv_s * dbeta[c];
+            const float k2 = a * inv_s * dgamma[c] * r;
+            uint32_t h = fdiv(e0, w_div);
+            uint32_t w = e0 - h * uint32_t(W);
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+                const bool in = h >= uint32_t(b.h0) && h < uint32_t(b.h0 + b.h_cnt) &&
+                                w >= uint32_t(b.w0) && w < uint32_t(b.w0 + b.w_cnt);
+                const float corr = in ? fmaf(k2, xv.f[i] - mu, k1) : 0.f;
+                g[u].f[i] = fmaf(a, g[u].f[i], -corr);
+                if (++w == uint32_t(W)) {
+                    w = 0;
+                    ++h;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < V; ++i) g[u].f[i] *= a;
+        }
+        g[u].store(dr + size_t(vi) * V);
+    }
+}
+
+// ===========================================================================
+// Utilities
+// ===========================================================================
+__global__ __launch_bounds__(kBlock) void index_boxes_kernel(IndexParams ip, int C, bns_box* __restrict__ boxes) {
+    const int c = blockIdx.x * kBlock + threadIdx.x;
+    if (c < C) boxes[c] = box_of_channel(ip, c);
+}
+
+__global__ __launch_bounds__(kBlock) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                      size_t n16) {
+    const size_t i0 = size_t(blockIdx.x) * (kBlock * 4) + threadIdx.x;
+    if (i0 + 3 * kBlock < n16) {
+        const uint4 a = src[i0], b = src[i0 + kBlock], c = src[i0 + 2 * kBlock], d = src[i0 + 3 * kBlock];
+        dst[i0] = a;
+        dst[i0 + kBlock] = b;
+        dst[i0 + 2 * kBlock] = c;
+        dst[i0 + 3 * kBlock] = d;
+    } else {
+        for (size_t i = i0; i < n16; i += kBlock) dst[i] = src[i];
+    }
+}
+
+// ===========================================================================
+// Launchers
+// ===========================================================================
+namespace {
+
+inline uint32_t ceil_div(uint32_t a, uint32_t b) { return (a + b - 1) / b; }
+
+// Calls f(T tag, integral_constant<V>) for the storage type and vector width of `d`.
+template <int V>
+struct VecTag {
+    static constexpr int value = V;
+};
+
+template <typename F>
+hipError_t dispatch(const Dims& d, F&& f) {
+    if (d.dtype == BNS_F32) {
+        if (d.vec == 4) return f(float(), VecTag<4>());
+        return f(float(), VecTag<1>());
+    }
+    if (d.vec == 8) return f(bf16_t(), VecTag<8>());
+    if (d.vec == 4) return f(bf16_t(), VecTag<4>());
+    return f(bf16_t(), VecTag<1>());
+}
+
+}  // namespace
+
+int auto_splits(int cg, uint32_t vectors_per_channel) {
+    // Aim for >= 2048 blocks (8 per CU on 256 CUs) but keep >= 4 accesses per thread.
+    uint32_t want = ceil_div(2048u, uint32_t(cg));
+    uint32_t cap = vectors_per_channel / (4u * kBlock);
+    if (cap < 1u) cap = 1u;
+    uint32_t s = want < cap ? want : cap;
+    if (s < 1u) s = 1u;
+    if (s > uint32_t(kMaxSplits)) s = kMaxSplits;
+    return int(s);
+}
+
+hipError_t launch_stats_partial(const Dims& d, const IndexParams& ip, const void* x, Partial* partial,
+                                int splits, int c0, int cg, hipStream_t st) {
+    const bns_box& b = ip.shared;
+    const bool planes = !ip.per_channel && b.h_cnt == d.H && b.w_cnt == d.W && d.vec > 1;
+    const dim3 grid(uint32_t(cg) * uint32_t(splits));
+    if (planes) {
+        return dispatch(d, [&](auto t, auto vt) {
+            using T = decltype(t);
+            constexpr int V = decltype(vt)::value;
+            const uint32_t hwv = uint32_t(d.HW / V);
+            const uint32_t tot = uint32_t(b.n_cnt) * hwv;
+            const uint32_t per_block = ceil_div(tot, uint32_t(splits));
+            hipLaunchKernelGGL((stats_partial_planes_kernel<T, V>), grid, dim3(kBlock), 0, st,
+                               static_cast<const T*>(x), partial, ip, d.C, d.HW, make_fastdiv(hwv), c0, splits,
+                               per_block);
+            return hipGetLastError();
+        });
+    }
+    const uint32_t patch = uint32_t(b.h_cnt) * uint32_t(b.w_cnt);
+    const uint32_t tot = uint32_t(b.n_cnt) * patch;
+    const uint32_t per_block = ceil_div(tot, uint32_t(splits));
+    if (d.dtype == BNS_F32)
+        hipLaunchKernelGGL((stats_partial_patch_kernel<float>), grid, dim3(kBlock), 0, st,
+                           static_cast<const float*>(x), partial, ip, d.C, d.W, d.HW, make_fastdiv(patch),
+                           make_fastdiv(uint32_t(b.w_cnt)), c0, splits, per_block);
+    else
+        hipLaunchKernelGGL((stats_partial_patch_kernel<bf16_t>), grid, dim3(kBlock), 0, st,
+                           static_cast<const bf16_t*>(x), partial, ip, d.C, d.W, d.HW, make_fastdiv(patch),
+                           make_fastdiv(uint32_t(b.w_cnt)), c0, splits, per_block);
+    return hipGetLastError();
+}
+
+hipError_t launch_stats_finalize(const Dims& d, const IndexParams& ip, const void* x, const Partial* partial,
+                                 int splits, int c0, int cg, float eps, float momentum, float* save_mean,
+                                 float* save_invstd, float* running_mean, float* running_var, hipStream_t st) {
+    const dim3 grid(ceil_div(uint32_t(cg), kBlock));
+    if (d.dtype == BNS_F32)
+        hipLaunchKernelGGL((stats_finalize_kernel<float>), grid, dim3(kBlock), 0, st,
+                           static_cast<const float*>(x), partial, ip, d.C, d.W, d.HW, splits, c0, cg, eps, momentum,
+                           save_mean, save_invstd, running_mean, running_var);
+    else
+        hipLaunchKernelGGL((stats_finalize_kernel<bf16_t>), grid, dim3(kBlock), 0, st,
+                           static_cast<const bf16_t*>(x), partial, ip, d.C, d.W, d.HW, splits, c0, cg, eps, momentum,
+                           save_mean, save_invstd, running_mean, running_var);
+    return hipGetLastError();
+}
+
+hipError_t launch_normalize(const Dims& d, const void* x, const float* gamma, const float* beta,
+                            const float* mean, const float* invstd, void* y, int c0, int cg, hipStream_t st) {
+    return dispatch(d, [&](auto t, auto vt) {
+        using T = decltype(t);
+        constexpr int V = decltype(vt)::value;
+        constexpr int U = 4;
+        const uint32_t hwv = uint32_t(d.HW / V);
+        const uint32_t run_vectors = uint32_t(cg) * hwv;
+        const dim3 grid(ceil_div(run_vectors, kBlock * U), uint32_t(d.N));
+        hipLaunchKernelGGL((normalize_kernel<T, V, U>), grid, dim3(kBlock), 0, st, static_cast<const T*>(x),
+                           static_cast<T*>(y), gamma, beta, mean, invstd, d.C, d.HW, make_fastdiv(hwv), c0,
+                           run_vectors);
+        return hipGetLastError();
+    });
+}
+
+hipError_t launch_reduce_partial(const Dims& d, const void* x, const void* dy, const float* mean,
+                                 Partial* partial, int splits, int c0, int cg, hipStream_t st) {
+    return dispatch(d, [&](auto t, auto vt) {
+        using T = decltype(t);
+        constexpr int V = decltype(vt)::value;
+        const uint32_t hwv = uint32_t(d.HW / V);
+        const uint32_t tot = uint32_t(d.N) * hwv;
+        const uint32_t per_block = ceil_div(tot, uint32_t(splits));
+        const dim3 grid(uint32_t(cg) * uint32_t(splits));
+        hipLaunchKernelGGL((reduce_partial_kernel<T, V>), grid, dim3(kBlock), 0, st, static_cast<const T*>(x),
+                           static_cast<const T*>(dy), mean, partial, d.C, d.HW, make_fastdiv(hwv), c0, splits,
+                           per_block, tot);
+        return hipGetLastError();
+    });
+}
+
+hipError_t launch_reduce_finalize(const Dims& d, const Partial* partial, int splits, int c0, int cg,
+                                  const float* invstd, float* dgamma, float* dbeta, hipStream_t st) {
+    (void)d;
+    hipLaunchKernelGGL(reduce_finalize_kernel, dim3(ceil_div(uint32_t(cg), kBlock)), dim3(kBlock), 0, st, partial,
+                       splits, c0, cg, invstd, dgamma, dbeta);
+    return hipGetLastError();
+}
+
+hipError_t launch_dx(const Dims& d, const IndexParams& ip, const void* x, const void* dy, const float* gamma,
+                     const float* mean, const float* invstd, const float* dgamma, const float* dbeta, void* dx,
+                     int c0, int cg, hipStream_t st) {
+    const bns_box& b = ip.shared;
+    const double s = double(b.n_cnt) * double(b.h_cnt) * double(b.w_cnt);
+    const float inv_s = float(1.0 / s);
+    return dispatch(d, [&](auto t, auto vt) {
+        using T = decltype(t);
+        constexpr int V = decltype(vt)::value;
+        constexpr int U = 4;
+        const uint32_t hwv = uint32_t(d.HW / V);
+        const uint32_t run_vectors = uint32_t(cg) * hwv;
+        const dim3 grid(ceil_div(run_vectors, kBlock * U), uint32_t(d.N));
+        hipLaunchKernelGGL((dx_kernel<T, V, U>), grid, dim3(kBlock), 0, st, static_cast<const T*>(x),
+                           static_cast<const T*>(dy), static_cast<T*>(dx), gamma, mean, invstd, dgamma, dbeta, ip,
+                           d.C, d.W, d.HW, make_fastdiv(hwv), make_fastdiv(uint32_t(d.W)), c0, run_vectors, inv_s);
+        return hipGetLastError();
+    });
+}
+
+hipError_t launch_index_boxes(const IndexParams& ip, int C, bns_box* boxes, hipStream_t st) {
+    hipLaunchKernelGGL(index_boxes_kernel, dim3(ceil_div(uint32_t(C), kBlock)), dim3(kBlock), 0, st, ip, C, boxes);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    const size_t blocks = (n16 + kBlock * 4 - 1) / (kBlock * 4);
+    hipLaunchKernelGGL(copy_kernel, dim3(uint32_t(blocks)), dim3(kBlock), 0, st, static_cast<const uint4*>(src),
+                       static_cast<uint4*>(dst), n16);
+    return hipGetLastError();
+}
+
+}  // namespace bns

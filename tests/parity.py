@@ -1,0 +1,70 @@
+"""Shared helpers of the GPU parity tests: oracle reference for a workload and the error metric."""
+import numpy as np
+
+from oracle import bns_oracle as oracle
+
+# Tolerances stated for the build: fp32 1e-5, bf16 1e-2 (relative; see scaled_err).
+TOL_F32 = 1e-5
+TOL_BF16 = 1e-2
+
+
+def oracle_boxes(wl, C=None):
+    return oracle.sample_index(wl.N, wl.C if C is None else C, wl.H, wl.W, wl.mode, n_s=wl.n_s, patch_h=wl.patch_h,
+                               patch_w=wl.patch_w, fs_per_channel=wl.fs_per_channel, seed=wl.sampling_seed,
+                               layer_id=wl.layer_id, epoch=wl.epoch)
+
+
+def oracle_reference(wl, inp, channels=None):
+    """Oracle forward + backward.  ``channels``: list of channel ids to evaluate (all by default);
+    the returned tensors then hold only those channels, in that order."""
+    boxes = oracle_boxes(wl)
+    if channels is not None:
+        ch = np.asarray(channels)
+        boxes = boxes[ch]
+        sel = lambda a: a[:, ch] if a.ndim == 4 else a[ch]
+        inp = {k: sel(v) for k, v in inp.items()}
+    f = oracle.forward(inp["x"], inp["gamma"], inp["beta"], boxes, wl.eps, wl.momentum,
+                       inp["running_mean"], inp["running_var"])
+    b = oracle.backward(inp["x"], inp["dy"], inp["gamma"], f["mean"], f["var"], boxes, wl.eps)
+    return dict(y=f["y"], save_mean=f["mean"], save_invstd=f["invstd"], running_mean=f["running_mean"],
+                running_var=f["running_var"], dx=b["dx"], dgamma=b["dgamma"], dbeta=b["dbeta"])
+
+
+def scaled_err(got, ref, floor=0.0):
+    """max_i |got_i - ref_i| / (|ref_i| + max(RMS(ref), floor)).
+
+    A purely element-wise relative error is undefined where y, dx or dbeta cross zero; adding the
+    tensor's RMS to the denominator keeps it a relative measure at the tensor's own scale.
+    ``floor`` is the RMS of the terms the output is a difference of, for outputs that cancel."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    rms = max(np.sqrt(np.mean(ref ** 2)), floor)
+    return float(np.max(np.abs(got - ref) / (np.abs(ref) + rms + 1e-300)))
+
+
+def direct_term_rms(inp, ref, channels=None):
+    """RMS of gamma * invstd * dy, the first term of both branches of Eq. 6.
+
+    dx is that term minus the 1/s corrections.  For s of a few points the two nearly cancel
+    (with s = m = 2 exactly, up to eps), and fp32 rounding of the terms then dominates the
+    difference, so dx is measured against the larger of its own RMS and this one.  For the
+    benchmark shapes (s in the thousands) the two are equal to within 1/s."""
+    ch = slice(None) if channels is None else np.asarray(channels)
+    a = (np.asarray(inp["gamma"], dtype=np.float64)[ch] * ref["save_invstd"])[None, :, None, None]
+    return float(np.sqrt(np.mean((a * inp["dy"][:, ch].astype(np.float64)) ** 2)))
+
+
+def assert_parity(res, ref, wl, channels=None, what="", inp=None):
+    tol_t = TOL_F32 if wl.dtype == "f32" else TOL_BF16
+    errs = {}
+    for k, r in ref.items():
+        g = res[k]
+        if channels is not None:
+            g = g[:, channels] if g.ndim == 4 else g[channels]
+        assert g.shape == r.shape, (k, g.shape, r.shape)
+        assert np.isfinite(g).all(), f"{what} {k}: non-finite output"
+        tol = tol_t if k in ("y", "dx") else TOL_F32          # per-channel vectors are fp32 in every mode
+        floor = direct_term_rms(inp, ref, channels) if (k == "dx" and inp is not None) else 0.0
+        errs[k] = scaled_err(g, r, floor)
+        assert errs[k] <= tol, f"{what} {k}: scaled error {errs[k]:.3e} > {tol:g}"
+    return errs

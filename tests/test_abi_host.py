@@ -1,0 +1,139 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+include/bns.h declares, generates the same sampling index as the oracle bit for bit, and
+rejects bad arguments before anything is enqueued."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+from oracle import bns_oracle as o
+from paper_1810_10962_amd import bns
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    bns.load()
+    names = bns.declared_symbols()
+    assert {"bns_forward", "bns_backward", "bns_sample_index", "bns_workspace_bytes"} <= set(names)
+    assert bns.missing_symbols() == []
+    assert "BNS_OK" in bns.bns_status_string(0)
+    for code in range(1, 5):
+        assert bns.bns_status_string(code).startswith("BNS_E")
+
+
+def _oracle_boxes(N, C_, H, W, mode, seed, **kw):
+    return o.sample_index(N, C_, H, W, mode, seed=seed, **kw)
+
+
+def test_host_index_is_bit_identical_to_the_oracle():
+    rng = np.random.default_rng(0)
+    checked = 0
+    for _ in range(3000):
+        N, H, W = (int(v) for v in rng.integers(1, 70, 3))
+        C_ = int(rng.integers(1, 5))
+        seed = int(rng.integers(0, 2 ** 63)) * 2 + int(rng.integers(0, 2))
+        layer, epoch = int(rng.integers(0, 2 ** 32)), int(rng.integers(0, 2 ** 32))
+        mode = int(rng.integers(0, 5))
+        n_s = int(rng.integers(1, N + 1))
+        if mode == o.VDN and N == 1:
+            continue
+        if mode == o.VDN:
+            n_s = int(rng.integers(1, N))
+        ph, pw = int(rng.integers(1, H + 1)), int(rng.integers(1, W + 1))
+        pc = int(rng.integers(0, 2))
+        shape = bns.make_shape(N, C_, H, W)
+        spec = bns.make_spec(mode, n_s, ph, pw, pc, layer, epoch)
+        got = bns.bns_sample_index(shape, spec, seed)
+        ref = _oracle_boxes(N, C_, H, W, mode, seed, n_s=n_s, patch_h=ph, patch_w=pw, fs_per_channel=pc,
+                            layer_id=layer, epoch=epoch)
+        assert (got == ref).all(), (N, C_, H, W, mode, seed, layer, epoch, got, ref)
+        checked += 1
+    assert checked > 2500
+
+
+def test_host_index_many_channels_and_large_extents():
+    # per-channel FS over many channels, and extents near the documented limits
+    shape = bns.make_shape(3, 4096, 60, 30)
+    spec = bns.make_spec(bns.BNS_FS, 0, 17, 9, 1, 77, 5)
+    got = bns.bns_sample_index(shape, spec, 2 ** 64 - 1)
+    ref = _oracle_boxes(3, 4096, 60, 30, o.FS, 2 ** 64 - 1, patch_h=17, patch_w=9, fs_per_channel=1,
+                        layer_id=77, epoch=5)
+    assert (got == ref).all() and len({tuple(r) for r in got}) > 500
+    for epoch in range(20):
+        shape = bns.make_shape(1, 1, 60000, 30000)
+        spec = bns.make_spec(bns.BNS_FS, 0, 1, 1, 0, 2 ** 32 - 1, epoch)
+        got = bns.bns_sample_index(shape, spec, 2 ** 63)
+        ref = _oracle_boxes(1, 1, 60000, 30000, o.FS, 2 ** 63, patch_h=1, patch_w=1, layer_id=2 ** 32 - 1, epoch=epoch)
+        assert (got == ref).all()
+    shape = bns.make_shape(65535, 2, 1, 1)
+    got = bns.bns_sample_index(shape, bns.make_spec(bns.BNS_BS, 1, layer_id=1), 42)
+    ref = _oracle_boxes(65535, 2, 1, 1, o.BS, 42, n_s=1, layer_id=1)
+    assert (got == ref).all()
+
+
+def _expect(status, fn, *args):
+    with pytest.raises(bns.BnsError) as e:
+        fn(*args)
+    assert e.value.status == status
+
+
+def test_invalid_shapes_and_specs_are_rejected():
+    ok_shape = bns.make_shape(8, 4, 6, 6)
+    bs = lambda n: bns.make_spec(bns.BNS_BS, n)
+    for bad in [bns.make_shape(0, 4, 6, 6), bns.make_shape(8, -1, 6, 6), bns.make_shape(8, 4, 0, 6),
+                bns.make_shape(8, 4, 6, 6, dtype=7)]:
+        _expect(bns.BNS_EINVAL, bns.bns_sample_index, bad, bs(2), 0)
+    for bad in [bns.make_shape(70000, 4, 6, 6), bns.make_shape(2, 4, 50000, 50000),
+                bns.make_shape(2, 2 ** 25, 1, 1)]:
+        _expect(bns.BNS_EUNSUPPORTED, bns.bns_sample_index, bad, bs(2), 0)
+    for bad in [bs(0), bs(9), bs(-3), bns.make_spec(bns.BNS_NS, 0), bns.make_spec(bns.BNS_VDN, 8),
+                bns.make_spec(bns.BNS_VDN, 0), bns.make_spec(bns.BNS_FS, 0, 0, 3), bns.make_spec(bns.BNS_FS, 0, 7, 3),
+                bns.make_spec(bns.BNS_FS, 0, 3, 7), bns.make_spec(bns.BNS_FS, 0, 3, 3, fs_per_channel=2),
+                bns.make_spec(9), bns.make_spec(-1)]:
+        _expect(bns.BNS_EINVAL, bns.bns_sample_index, ok_shape, bad, 0)
+    assert bns.bns_workspace_bytes(bns.make_shape(0, 4, 6, 6), bs(2)) == 0
+    assert bns.bns_workspace_bytes(ok_shape, bs(2)) >= 4 * 2 * 4
+
+
+def test_null_misaligned_overlapping_and_small_workspace_are_rejected_without_a_gpu():
+    """Validation runs before any launch, so fake (never dereferenced) addresses suffice."""
+    lib = bns.load()
+    shape, spec = bns.make_shape(8, 4, 6, 6), bns.make_spec(bns.BNS_BS, 2)
+    need = bns.bns_workspace_bytes(shape, spec)
+    tb = 8 * 4 * 36 * 4
+    P = lambda a: C.c_void_p(a)
+    x, y, dy, dx, ws = 0x10000, 0x20000, 0x30000, 0x40000, 0x50000
+    v = 0x60000                                                   # per-channel vectors
+
+    def fwd(x=x, y=y, ws=ws, wsb=need, eps=1e-5, mom=0.1, gamma=v, sm=v + 256):
+        return lib.bns_forward(C.byref(shape), C.byref(spec), 1, P(x), P(gamma), P(v + 128), C.c_float(eps),
+                               C.c_float(mom), P(y), P(sm), P(v + 384), None, None, P(ws), wsb, None)
+
+    def bwd(x=x, dy=dy, dx=dx, ws=ws, wsb=need):
+        return lib.bns_backward(C.byref(shape), C.byref(spec), 1, P(x), P(dy), P(v), P(v + 128), P(v + 256),
+                                P(dx), P(v + 384), P(v + 512), P(ws), wsb, None)
+
+    assert fwd(x=0) == bns.BNS_EINVAL and fwd(y=0) == bns.BNS_EINVAL and fwd(ws=0) == bns.BNS_EINVAL
+    assert fwd(gamma=0) == bns.BNS_EINVAL and fwd(sm=0) == bns.BNS_EINVAL
+    assert fwd(x=x + 4) == bns.BNS_EINVAL and fwd(y=y + 8) == bns.BNS_EINVAL          # misaligned
+    assert fwd(y=x) == bns.BNS_EINVAL and fwd(y=x + tb - 16) == bns.BNS_EINVAL        # overlap
+    assert fwd(wsb=need - 1) == bns.BNS_EWORKSPACE
+    assert fwd(eps=-1.0) == bns.BNS_EINVAL and fwd(mom=1.5) == bns.BNS_EINVAL
+    assert fwd(eps=float("nan")) == bns.BNS_EINVAL
+    assert bwd(x=0) == bns.BNS_EINVAL and bwd(dy=0) == bns.BNS_EINVAL and bwd(dx=0) == bns.BNS_EINVAL
+    assert bwd(dx=dy) == bns.BNS_EINVAL and bwd(dx=x + 16) == bns.BNS_EINVAL
+    assert bwd(wsb=0) == bns.BNS_EWORKSPACE
+    assert lib.bns_forward(None, C.byref(spec), 1, P(x), P(v), P(v), 0.0, 0.0, P(y), P(v), P(v), None, None,
+                           P(ws), need, None) == bns.BNS_EINVAL
+    assert lib.bns_copy_reference(P(x), P(x + 8), 64, None) == bns.BNS_EINVAL
+    assert lib.bns_copy_reference(P(x), P(y), 60, None) == bns.BNS_EINVAL
+    assert lib.bns_copy_reference(P(x), P(x + 32), 64, None) == bns.BNS_EINVAL
+
+
+def test_options():
+    assert bns.bns_get_option("splits_stats") == 0 and bns.bns_get_option("nonsense") == -1
+    bns.bns_set_option("splits_reduce", 8)
+    assert bns.bns_get_option("splits_reduce") == 8 and bns.bns_get_option("splits_stats") == 0
+    bns.bns_set_option("splits_reduce", 0)
+    _expect(bns.BNS_EINVAL, bns.bns_set_option, "splits_stats", 65)
+    _expect(bns.BNS_EINVAL, bns.bns_set_option, "nonsense", 1)
+    _expect(bns.BNS_EINVAL, bns.bns_set_option, "channel_group", -1)
