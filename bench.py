@@ -1,0 +1,282 @@
+#!/usr/bin/env python3
+"""Benchmark of libbns on one MI355X: sampled batch normalisation, forward + backward.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload imagenet_bs] [--quick]
+
+A step is one bns_forward + bns_backward over one synthetic batch that is already
+resident in HBM.  The workload is the shape the headline metric is quoted on,
+NCHW 64x256x56x56 fp32 with Batch Sampling 8/64; the other sampling modes, full BN and
+the bf16 variants of the same tensor are timed after it and reported under "variants".
+Buffers rotate between steps so that no step finds its inputs in the last-level cache.
+
+Prints ONE JSON line.  `value` is the effective bandwidth: the bytes the method has to
+move (see algorithmic_bytes) divided by the measured time per step.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published peak
+METRIC = "BN fwd+bwd effective HBM GB/s (% peak) and speedup vs full BN, 64x256x56x56"
+
+# HBM traffic of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+# scaled by what the same counters read for bns_copy_reference of known size; bytes per launch.
+# Filled from profiles/ (see there for the commands); None where no counter run exists.
+MEASURED_TRAFFIC = {
+    ("imagenet_bs", "dx"): 436892054,           # profiles/imagenet_bs_f32_hbm_traffic.md
+    ("imagenet_bs", "normalize"): 411166831,
+    ("imagenet_bs", "reduce"): 411101108,
+}
+
+
+def sampling_ratio(wl, boxes) -> float:
+    b = boxes[0]
+    return float(b[1]) * float(b[3]) * float(b[5]) / float(wl.N * wl.H * wl.W)
+
+
+def algorithmic_bytes(wl, r: float) -> dict:
+    """Bytes each stage has to move, per step (e = element size).
+
+    statistics  : read x on S only                      r e E
+    normalise   : read x, write y                       2 e E
+    bwd reduce  : read dy and x, all m points           2 e E
+    dx          : read dy, write dx, read x on S    (2 + r) e E
+    Per-channel vectors and the partial-sum workspace are O(C) and left out.
+    """
+    e = 4 if wl.dtype == "f32" else 2
+    E = wl.elements
+    st = dict(stats=r * e * E, normalize=2 * e * E, reduce=2 * e * E, dx=(2 + r) * e * E)
+    st["fwd+bwd"] = sum(st.values())
+    return st
+
+
+class DeviceSet:
+    """`nset` rotating buffer sets for one workload plus the shared per-channel tensors."""
+
+    def __init__(self, wl, inputs, nset, torch, bns):
+        self.wl = wl
+        self.bufs = [bns.Buffers(wl, inputs)]
+        for _ in range(nset - 1):
+            b = bns.Buffers.__new__(bns.Buffers)
+            b.__dict__.update(self.bufs[0].__dict__)
+            for name in ("x", "dy"):
+                setattr(b, name, getattr(self.bufs[0], name).clone())
+            for name in ("y", "dx"):
+                setattr(b, name, torch.empty_like(self.bufs[0].x))
+            self.bufs.append(b)
+        self.i = 0
+
+    def next(self):
+        b = self.bufs[self.i % len(self.bufs)]
+        self.i += 1
+        return b
+
+
+def time_steps(ds, steps, warmup, torch):
+    for _ in range(warmup):
+        b = ds.next()
+        b.forward()
+        b.backward()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        b = ds.next()
+        b.forward()
+        b.backward()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def time_stages(ds, steps, torch, bns):
+    """Average duration of every stage, HIP events on the stream the kernels run on."""
+    wl = ds.wl
+    names = ["stats", "normalize", "reduce", "dx"]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
+    for s in range(steps):
+        b = ds.next()
+        e = evs[s]
+        e[0].record()
+        bns.bns_forward_stats(b.shape, b.spec, b.seed, b.x, wl.eps, wl.momentum, b.save_mean, b.save_invstd,
+                              b.running_mean, b.running_var, b.workspace)
+        e[1].record()
+        bns.bns_forward_normalize(b.shape, b.x, b.gamma, b.beta, b.save_mean, b.save_invstd, b.y)
+        e[2].record()
+        bns.bns_backward_reduce(b.shape, b.x, b.dy, b.save_mean, b.save_invstd, b.dgamma, b.dbeta, b.workspace)
+        e[3].record()
+        bns.bns_backward_dx(b.shape, b.spec, b.seed, b.x, b.dy, b.gamma, b.save_mean, b.save_invstd, b.dgamma,
+                            b.dbeta, b.dx)
+        e[4].record()
+    torch.cuda.synchronize()
+    out = {}
+    for k, name in enumerate(names):
+        out[name] = float(np.mean([evs[s][k].elapsed_time(evs[s][k + 1]) for s in range(steps)])) * 1e-3
+    return out
+
+
+def time_copy(ds, steps, torch, bns):
+    for _ in range(3):
+        b = ds.next()
+        bns.bns_copy_reference(b.y, b.x)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, z in evs:
+        b = ds.next()
+        a.record()
+        bns.bns_copy_reference(b.y, b.x)
+        z.record()
+    torch.cuda.synchronize()
+    return float(np.mean([a.elapsed_time(z) for a, z in evs])) * 1e-3
+
+
+def cpu_baseline(wl, inputs, res, budget_s=12.0):
+    """The fp64 oracle, as it stands, timed on this host on a bounded sample of channels.
+
+    Channels are independent, so the sample is whole channels of the same tensor; it is also
+    compared with what the GPU produced for them."""
+    from oracle import bns_oracle as oracle
+
+    boxes = oracle.sample_index(wl.N, wl.C, wl.H, wl.W, wl.mode, n_s=wl.n_s, patch_h=wl.patch_h, patch_w=wl.patch_w,
+                                fs_per_channel=wl.fs_per_channel, seed=wl.sampling_seed, layer_id=wl.layer_id,
+                                epoch=wl.epoch)
+    tol = {"f32": 1e-5, "bf16": 1e-2}[wl.dtype]
+    done, spent, worst = 0, 0.0, {}
+    order = list(range(0, wl.C, 8)) + [c for c in range(wl.C) if c % 8]
+    while done < len(order) and spent < budget_s:
+        ch = np.asarray(order[done:done + 4])
+        x, dy = inputs["x"][:, ch], inputs["dy"][:, ch]
+        t0 = time.perf_counter()
+        f = oracle.forward(x, inputs["gamma"][ch], inputs["beta"][ch], boxes[ch], wl.eps, wl.momentum,
+                           inputs["running_mean"][ch], inputs["running_var"][ch])
+        b = oracle.backward(x, dy, inputs["gamma"][ch], f["mean"], f["var"], boxes[ch], wl.eps)
+        spent += time.perf_counter() - t0
+        ref = dict(y=f["y"], dx=b["dx"], save_mean=f["mean"], save_invstd=f["invstd"], dgamma=b["dgamma"],
+                   dbeta=b["dbeta"])
+        for k, rv in ref.items():
+            g = res[k][:, ch] if res[k].ndim == 4 else res[k][ch]
+            err = float(np.max(np.abs(g - rv) / (np.abs(rv) + np.sqrt(np.mean(rv ** 2)))))
+            worst[k] = max(worst.get(k, 0.0), err)
+            assert err <= (tol if k in ("y", "dx") else 1e-5), f"GPU result differs from the oracle: {k} {err:.3e}"
+        done += len(ch)
+    r = sampling_ratio(wl, boxes)
+    bytes_per_channel = algorithmic_bytes(wl, r)["fwd+bwd"] / wl.C
+    return dict(value=round(bytes_per_channel * done / spent / 1e9, 4), unit="GB/s", cores=1, kind="oracle",
+                sample=f"{done} of {wl.C} channels of the same tensor, oracle forward+backward in fp64 (numpy, "
+                       f"one thread), {spent:.1f} s", elements_per_s=round(wl.elements / wl.C * done / spent, 1),
+                max_scaled_error_vs_gpu={k: float(f"{v:.3e}") for k, v in worst.items()})
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="imagenet_bs")
+    ap.add_argument("--quick", action="store_true", help="primary workload only, no variants, no CPU baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (sampled BN keeps its statistics local to a GPU; "
+              "see DESIGN.md, 'More than one GPU'); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_1810_10962_amd import bns, workloads
+
+    bns.load()                                            # raises if libbns.so is missing: no fallback
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    K, W = args.steps, args.warmup
+
+    wl = workloads.WORKLOADS[args.workload]
+    inputs = workloads.make_inputs(wl)
+    tensor_bytes = wl.elements * (4 if wl.dtype == "f32" else 2)
+    nset = max(2, min(8, int(np.ceil(1.5e9 / (4 * tensor_bytes)))))       # rotate over >= 1.5 GB
+    ds = DeviceSet(wl, inputs, nset, torch, bns)
+    boxes = bns.bns_sample_index(ds.bufs[0].shape, ds.bufs[0].spec, wl.sampling_seed)
+    r = sampling_ratio(wl, boxes)
+    alg = algorithmic_bytes(wl, r)
+
+    sec = time_steps(ds, K, W, torch)
+    stages = time_stages(ds, K, torch, bns)
+    copy_s = time_copy(ds, min(K, 50), torch, bns)
+
+    # dominant kernel = the longest single-kernel stage (statistics and reduce stages also
+    # contain a one-block finalize kernel, so their event pair covers two launches)
+    dom = max(("normalize", "dx", "reduce"), key=lambda k: stages[k])
+    kernel_name = {"normalize": "normalize_kernel", "dx": "dx_kernel", "reduce": "reduce_partial_kernel"}[dom]
+    achieved = alg[dom] / stages[dom] / 1e9
+    roofline = dict(bound="hbm", kernel=kernel_name, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=MEASURED_TRAFFIC.get((wl.name, dom)),
+                    algorithmic_bytes_per_launch=int(alg[dom]), avg_launch_us=round(stages[dom] * 1e6, 2),
+                    timing="HIP events on the launch stream around the stage, mean over the timed steps")
+
+    out = {
+        "metric": METRIC, "value": round(alg["fwd+bwd"] / sec / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": K,
+        "warmup": W, "ms_per_step": round(sec * 1e3, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if wl.dtype == "f32" else "bf16 storage, f32 arithmetic",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: NCHW {wl.N}x{wl.C}x{wl.H}x{wl.W} {wl.dtype}, {wl.label()} "
+                               f"(sampling ratio {r:.4f}), forward+backward, eps={wl.eps}, momentum={wl.momentum}",
+                   "buffer_sets_rotated": nset},
+        "pct_of_hbm_peak": round(100 * alg["fwd+bwd"] / sec / 1e9 / HBM_PEAK_GBS, 2),
+        "elements_per_s": round(wl.elements / sec, 1),
+        "algorithmic_bytes_per_step": int(alg["fwd+bwd"]),
+        "stages_us": {k: round(v * 1e6, 2) for k, v in stages.items()},
+        "stages_GBs": {k: round(alg[k] / stages[k] / 1e9, 1) for k in stages},
+        "copy_reference": {"us": round(copy_s * 1e6, 2), "GBs": round(2 * tensor_bytes / copy_s / 1e9, 1)},
+        "roofline": roofline,
+    }
+
+    if not args.quick:
+        ds.bufs[0].forward()
+        ds.bufs[0].backward()
+        res = ds.bufs[0].results()
+        out["cpu_baseline"] = cpu_baseline(wl, inputs, res)
+        del ds
+        torch.cuda.empty_cache()
+        variants = {}
+        base = wl.name.split("_")[0]
+        for name in [f"{base}_bs", f"{base}_fs", f"{base}_full", f"{base}_bs_bf16", f"{base}_fs_bf16",
+                     f"{base}_full_bf16"]:
+            if name not in workloads.WORKLOADS:
+                continue
+            v = workloads.WORKLOADS[name]
+            vin = inputs
+            if v.dtype == "bf16":
+                vin = dict(inputs)
+                vin["x"] = workloads.round_to_bf16(inputs["x"])
+                vin["dy"] = workloads.round_to_bf16(inputs["dy"])
+            vb = v.elements * (4 if v.dtype == "f32" else 2)
+            vds = DeviceSet(v, vin, max(2, min(8, int(np.ceil(1.5e9 / (4 * vb))))), torch, bns)
+            vr = sampling_ratio(v, bns.bns_sample_index(vds.bufs[0].shape, vds.bufs[0].spec, v.sampling_seed))
+            vsec = time_steps(vds, K, W, torch)
+            va = algorithmic_bytes(v, vr)["fwd+bwd"]
+            variants[name] = dict(label=v.label(), dtype=v.dtype, ratio=round(vr, 4), us_per_step=round(vsec * 1e6, 2),
+                                  effective_GBs=round(va / vsec / 1e9, 1),
+                                  pct_of_hbm_peak=round(100 * va / vsec / 1e9 / HBM_PEAK_GBS, 2),
+                                  elements_per_s=round(v.elements / vsec, 1))
+            del vds
+            torch.cuda.empty_cache()
+        for name, v in variants.items():
+            full = variants.get(name.replace("_bs", "_full").replace("_fs", "_full"))
+            if full:
+                v["speedup_vs_full_bn"] = round(full["us_per_step"] / v["us_per_step"], 4)
+        out["variants"] = variants
+        if wl.name in variants and "speedup_vs_full_bn" in variants[wl.name]:
+            out["speedup_vs_full_bn"] = variants[wl.name]["speedup_vs_full_bn"]
+        out["paper_context"] = ("paper reports up to 2x BN-layer speedup and up to 20% end-to-end (TensorFlow, "
+                                "Titan Xp / V100, Sec. 5.2, Table 3); no kernel-level bandwidth is published")
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

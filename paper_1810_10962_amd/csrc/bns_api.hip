@@ -283,6 +283,24 @@ bns_status bns_set_option(const char* name, int32_t value) {
         g_channel_group.store(value);
         return BNS_OK;
     }
+    // value 0 = automatic; non-temporal masks are given as mask + 1 so that 0 keeps that meaning
+    struct {
+        const char* n;
+        int* p;
+        int hi, bias;
+    } tun[] = {
+        {"norm_unroll", &g_tuning.norm_unroll, 4, 0},     {"norm_nt", &g_tuning.norm_nt, 4, 1},
+        {"dx_unroll", &g_tuning.dx_unroll, 4, 0},         {"dx_nt", &g_tuning.dx_nt, 4, 1},
+        {"reduce_unroll", &g_tuning.reduce_unroll, 4, 0}, {"reduce_nt", &g_tuning.reduce_nt, 2, 1},
+        {"reduce_split_major", &g_tuning.reduce_split_major, 1, 0},
+        {"reduce_align", &g_tuning.reduce_align, 1, 0},
+    };
+    for (auto& t : tun)
+        if (!strcmp(name, t.n)) {
+            if (value > t.hi || (value == 3 && t.hi == 4 && t.bias == 0)) return BNS_EINVAL;
+            *t.p = value - t.bias;
+            return BNS_OK;
+        }
     return BNS_EINVAL;
 }
 

@@ -18,6 +18,22 @@ struct Dims {
     int32_t vec;    // elements per memory access: largest of {8 (bf16 only), 4, 1} dividing HW
 };
 
+// Launch-shape choices; 0 = the default for the storage type (see tuned()).  The benchmark
+// can override them through bns_set_option.  Defaults come from sweeps on MI355X at
+// 64x256x56x56: one 128-bit access per thread and non-temporal loads and stores stream
+// fastest (streamed data is not re-read, so keeping it out of L2 avoids write-backs of
+// lines nobody will hit).
+struct Tuning {
+    int norm_unroll = 0, norm_nt = -1;      // accesses per thread; bit 0: non-temporal loads, bit 1: stores
+    int dx_unroll = 0, dx_nt = -1;
+    int reduce_unroll = 0, reduce_nt = -1;
+    int reduce_split_major = 0;             // block order of the backward reduction
+    int reduce_align = 0;                   // round a block's range up to whole planes
+};
+extern Tuning g_tuning;
+inline int tuned(int v, int dflt) { return v > 0 ? v : dflt; }
+inline int tuned_nt(int v, int dflt) { return v >= 0 ? v : dflt; }
+
 // One (sum, sum) pair per channel and split.
 struct Partial {
     float a, b;

@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kBlock) void stats_finalize_kernel(
 // ===========================================================================
 // grid = (ceil(cg * HW / V / (kBlock * U)), N).  Block (bx, n) handles kBlock * U
 // consecutive vectors of the contiguous run [c0, c0 + cg) x HW of sample n.
-template <typename T, int V, int U>
+template <typename T, int V, int U, int NT>
 __global__ __launch_bounds__(kBlock) void normalize_kernel(
     const T* __restrict__ x, T* __restrict__ y, const float* __restrict__ gamma,
     const float* __restrict__ beta, const float* __restrict__ mean, const float* __restrict__ invstd,
@@ -158,7 +158,9 @@ __global__ __launch_bounds__(kBlock) void normalize_kernel(
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint32_t vi = v0 + u * kBlock;
-        if (vi < run_vectors) v[u].load(xr + size_t(vi) * V);
+        if (vi < run_vectors) {
+            if (NT & 1) v[u].load_nt(xr + size_t(vi) * V); else v[u].load(xr + size_t(vi) * V);
+        }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -178,7 +180,7 @@ __global__ __launch_bounds__(kBlock) void normalize_kernel(
         if (vi < run_vectors) {
 #pragma unroll
             for (int i = 0; i < V; ++i) v[u].f[i] = fmaf(v[u].f[i] - mu[u], sc[u], sh[u]);
-            v[u].store(yr + size_t(vi) * V);
+            if (NT & 2) v[u].store_nt(yr + size_t(vi) * V); else v[u].store(yr + size_t(vi) * V);
         }
     }
 }
@@ -187,14 +189,20 @@ __global__ __launch_bounds__(kBlock) void normalize_kernel(
 // Backward reductions over all m points (Eq. 5): sum dy, sum dy * (x - mean)
 // ===========================================================================
 // grid.x = cg * splits, block (c, k) as in stats_partial_planes_kernel with S = everything.
-template <typename T, int V>
+template <typename T, int V, int U, int NT>
 __global__ __launch_bounds__(kBlock) void reduce_partial_kernel(
     const T* __restrict__ x, const T* __restrict__ dy, const float* __restrict__ mean,
-    Partial* __restrict__ partial, int C, int HW, FastDiv hwv_div, int c0, int splits, uint32_t per_block,
-    uint32_t tot) {
+    Partial* __restrict__ partial, int C, int HW, FastDiv hwv_div, int c0, int cg, int splits, uint32_t per_block,
+    uint32_t tot, int split_major) {
     __shared__ float lds[2 * (kBlock / kWave)];
-    const int cl = blockIdx.x / splits;
-    const int k = blockIdx.x - cl * splits;
+    int cl, k;
+    if (split_major) {            // consecutive blocks: consecutive channels of the same sample range
+        k = blockIdx.x / cg;
+        cl = blockIdx.x - k * cg;
+    } else {                      // consecutive blocks: consecutive ranges of the same channel
+        cl = blockIdx.x / splits;
+        k = blockIdx.x - cl * splits;
+    }
     const int c = c0 + cl;
     const uint32_t hwv = hwv_div.d;
     const uint32_t j0 = uint32_t(k) * per_block;
@@ -203,20 +211,27 @@ __global__ __launch_bounds__(kBlock) void reduce_partial_kernel(
     const size_t cbase = size_t(c) * HW;
     const float mu = mean[c];
 
-    float s1[2] = {0.f, 0.f}, s2[2] = {0.f, 0.f};
-    uint32_t j = j0 + threadIdx.x;
-    for (; j + 1u * kBlock < j1; j += 2u * kBlock) {
-        Vec<T, V> g[2], v[2];
+    float s1[U], s2[U];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < U; ++u) s1[u] = s2[u] = 0.f;
+    uint32_t j = j0 + threadIdx.x;
+    for (; j + uint32_t(U - 1) * kBlock < j1; j += uint32_t(U) * kBlock) {
+        Vec<T, V> g[U], v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
             const uint32_t ju = j + u * kBlock;
             const uint32_t n = fdiv(ju, hwv_div);
             const size_t off = cbase + n * nstride + size_t(ju - n * hwv) * V;
-            g[u].load(dy + off);
-            v[u].load(x + off);
+            if (NT & 1) {
+                g[u].load_nt(dy + off);
+                v[u].load_nt(x + off);
+            } else {
+                g[u].load(dy + off);
+                v[u].load(x + off);
+            }
         }
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int i = 0; i < V; ++i) {
                 s1[u] += g[u].f[i];
@@ -235,7 +250,12 @@ __global__ __launch_bounds__(kBlock) void reduce_partial_kernel(
             s2[0] = fmaf(g.f[i], v.f[i] - mu, s2[0]);
         }
     }
-    float a = s1[0] + s1[1], q = s2[0] + s2[1];
+    float a = s1[0], q = s2[0];
+#pragma unroll
+    for (int u = 1; u < U; ++u) {
+        a += s1[u];
+        q += s2[u];
+    }
     block_sum2(a, q, lds);
     if (threadIdx.x == 0) partial[size_t(c) * splits + k] = Partial{a, q};
 }
@@ -262,7 +282,7 @@ __global__ __launch_bounds__(kBlock) void reduce_finalize_kernel(
 // Same walk as normalize_kernel.  dx = a * dy everywhere (a = gamma * invstd); the
 // 1/s terms of Eq. 6 are subtracted only where the element lies in S, and x is loaded
 // only by accesses that intersect S.
-template <typename T, int V, int U>
+template <typename T, int V, int U, int NT>
 __global__ __launch_bounds__(kBlock) void dx_kernel(
     const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx, const float* __restrict__ gamma,
     const float* __restrict__ mean, const float* __restrict__ invstd, const float* __restrict__ dgamma,
@@ -280,7 +300,9 @@ __global__ __launch_bounds__(kBlock) void dx_kernel(
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint32_t vi = v0 + u * kBlock;
-        if (vi < run_vectors) g[u].load(gr + size_t(vi) * V);
+        if (vi < run_vectors) {
+            if (NT & 1) g[u].load_nt(gr + size_t(vi) * V); else g[u].load(gr + size_t(vi) * V);
+        }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -297,7 +319,7 @@ __global__ __launch_bounds__(kBlock) void dx_kernel(
                              e0 < uint32_t(b.h0 + b.h_cnt) * W;
         if (touches) {
             Vec<T, V> xv;
-            xv.load(xr + size_t(vi) * V);
+            if (NT & 1) xv.load_nt(xr + size_t(vi) * V); else xv.load(xr + size_t(vi) * V);
             const float mu = mean[c];
             const float k1 = a * inv_s * dbeta[c];
             const float k2 = a * inv_s * dgamma[c] * r;
@@ -318,7 +340,7 @@ __global__ __launch_bounds__(kBlock) void dx_kernel(
 #pragma unroll
             for (int i = 0; i < V; ++i) g[u].f[i] *= a;
         }
-        g[u].store(dr + size_t(vi) * V);
+        if (NT & 2) g[u].store_nt(dr + size_t(vi) * V); else g[u].store(dr + size_t(vi) * V);
     }
 }
 
@@ -357,6 +379,30 @@ struct VecTag {
     static constexpr int value = V;
 };
 
+template <int I>
+struct IC {
+    static constexpr int value = I;
+};
+
+// Calls f(IC<U>, IC<NT>) for an unroll factor in {1, 2, 4} and a non-temporal mask in 0..3.
+template <typename F>
+hipError_t dispatch_unroll_nt(int U, int NT, F&& f) {
+    switch ((U == 1 ? 0 : U == 2 ? 1 : 2) * 4 + (NT & 3)) {
+        case 0: return f(IC<1>(), IC<0>());
+        case 1: return f(IC<1>(), IC<1>());
+        case 2: return f(IC<1>(), IC<2>());
+        case 3: return f(IC<1>(), IC<3>());
+        case 4: return f(IC<2>(), IC<0>());
+        case 5: return f(IC<2>(), IC<1>());
+        case 6: return f(IC<2>(), IC<2>());
+        case 7: return f(IC<2>(), IC<3>());
+        case 8: return f(IC<4>(), IC<0>());
+        case 9: return f(IC<4>(), IC<1>());
+        case 10: return f(IC<4>(), IC<2>());
+        default: return f(IC<4>(), IC<3>());
+    }
+}
+
 template <typename F>
 hipError_t dispatch(const Dims& d, F&& f) {
     if (d.dtype == BNS_F32) {
@@ -369,6 +415,8 @@ hipError_t dispatch(const Dims& d, F&& f) {
 }
 
 }  // namespace
+
+Tuning g_tuning;
 
 int auto_splits(int cg, uint32_t vectors_per_channel) {
     // Aim for >= 2048 blocks (8 per CU on 256 CUs) but keep >= 4 accesses per thread.
@@ -433,14 +481,17 @@ hipError_t launch_normalize(const Dims& d, const void* x, const float* gamma, co
     return dispatch(d, [&](auto t, auto vt) {
         using T = decltype(t);
         constexpr int V = decltype(vt)::value;
-        constexpr int U = 4;
-        const uint32_t hwv = uint32_t(d.HW / V);
-        const uint32_t run_vectors = uint32_t(cg) * hwv;
-        const dim3 grid(ceil_div(run_vectors, kBlock * U), uint32_t(d.N));
-        hipLaunchKernelGGL((normalize_kernel<T, V, U>), grid, dim3(kBlock), 0, st, static_cast<const T*>(x),
-                           static_cast<T*>(y), gamma, beta, mean, invstd, d.C, d.HW, make_fastdiv(hwv), c0,
-                           run_vectors);
-        return hipGetLastError();
+        return dispatch_unroll_nt(tuned(g_tuning.norm_unroll, d.dtype == BNS_F32 ? 1 : 2), tuned_nt(g_tuning.norm_nt, 3), [&](auto ut, auto nt) {
+            constexpr int U = decltype(ut)::value;
+            constexpr int NT = decltype(nt)::value;
+            const uint32_t hwv = uint32_t(d.HW / V);
+            const uint32_t run_vectors = uint32_t(cg) * hwv;
+            const dim3 grid(ceil_div(run_vectors, kBlock * U), uint32_t(d.N));
+            hipLaunchKernelGGL((normalize_kernel<T, V, U, NT>), grid, dim3(kBlock), 0, st, static_cast<const T*>(x),
+                               static_cast<T*>(y), gamma, beta, mean, invstd, d.C, d.HW, make_fastdiv(hwv), c0,
+                               run_vectors);
+            return hipGetLastError();
+        });
     });
 }
 
@@ -449,14 +500,19 @@ hipError_t launch_reduce_partial(const Dims& d, const void* x, const void* dy, c
     return dispatch(d, [&](auto t, auto vt) {
         using T = decltype(t);
         constexpr int V = decltype(vt)::value;
-        const uint32_t hwv = uint32_t(d.HW / V);
-        const uint32_t tot = uint32_t(d.N) * hwv;
-        const uint32_t per_block = ceil_div(tot, uint32_t(splits));
-        const dim3 grid(uint32_t(cg) * uint32_t(splits));
-        hipLaunchKernelGGL((reduce_partial_kernel<T, V>), grid, dim3(kBlock), 0, st, static_cast<const T*>(x),
-                           static_cast<const T*>(dy), mean, partial, d.C, d.HW, make_fastdiv(hwv), c0, splits,
-                           per_block, tot);
-        return hipGetLastError();
+        return dispatch_unroll_nt(tuned(g_tuning.reduce_unroll, 2), tuned_nt(g_tuning.reduce_nt, 1) & 1, [&](auto ut, auto nt) {
+            constexpr int U = decltype(ut)::value;
+            constexpr int NT = decltype(nt)::value;
+            const uint32_t hwv = uint32_t(d.HW / V);
+            const uint32_t tot = uint32_t(d.N) * hwv;
+            uint32_t per_block = ceil_div(tot, uint32_t(splits));
+            if (g_tuning.reduce_align && per_block > hwv) per_block = ceil_div(per_block, hwv) * hwv;   // whole planes
+            const dim3 grid(uint32_t(cg) * uint32_t(splits));
+            hipLaunchKernelGGL((reduce_partial_kernel<T, V, U, NT>), grid, dim3(kBlock), 0, st,
+                               static_cast<const T*>(x), static_cast<const T*>(dy), mean, partial, d.C, d.HW,
+                               make_fastdiv(hwv), c0, cg, splits, per_block, tot, g_tuning.reduce_split_major);
+            return hipGetLastError();
+        });
     });
 }
 
@@ -477,14 +533,18 @@ hipError_t launch_dx(const Dims& d, const IndexParams& ip, const void* x, const 
     return dispatch(d, [&](auto t, auto vt) {
         using T = decltype(t);
         constexpr int V = decltype(vt)::value;
-        constexpr int U = 4;
-        const uint32_t hwv = uint32_t(d.HW / V);
-        const uint32_t run_vectors = uint32_t(cg) * hwv;
-        const dim3 grid(ceil_div(run_vectors, kBlock * U), uint32_t(d.N));
-        hipLaunchKernelGGL((dx_kernel<T, V, U>), grid, dim3(kBlock), 0, st, static_cast<const T*>(x),
-                           static_cast<const T*>(dy), static_cast<T*>(dx), gamma, mean, invstd, dgamma, dbeta, ip,
-                           d.C, d.W, d.HW, make_fastdiv(hwv), make_fastdiv(uint32_t(d.W)), c0, run_vectors, inv_s);
-        return hipGetLastError();
+        return dispatch_unroll_nt(tuned(g_tuning.dx_unroll, d.dtype == BNS_F32 ? 1 : 2), tuned_nt(g_tuning.dx_nt, 3), [&](auto ut, auto nt) {
+            constexpr int U = decltype(ut)::value;
+            constexpr int NT = decltype(nt)::value;
+            const uint32_t hwv = uint32_t(d.HW / V);
+            const uint32_t run_vectors = uint32_t(cg) * hwv;
+            const dim3 grid(ceil_div(run_vectors, kBlock * U), uint32_t(d.N));
+            hipLaunchKernelGGL((dx_kernel<T, V, U, NT>), grid, dim3(kBlock), 0, st, static_cast<const T*>(x),
+                               static_cast<const T*>(dy), static_cast<T*>(dx), gamma, mean, invstd, dgamma, dbeta,
+                               ip, d.C, d.W, d.HW, make_fastdiv(hwv), make_fastdiv(uint32_t(d.W)), c0, run_vectors,
+                               inv_s);
+            return hipGetLastError();
+        });
     });
 }
 
