@@ -33,7 +33,7 @@ __device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv& f) {
 
 // ---------------------------------------------------------------------------
 // Storage types.  bf16 is handled as raw 16-bit patterns: widening is a shift,
-// narrowing rounds to nearest, ties to even (NaN stays NaN).
+// narrowing is the hardware conversion (round to nearest, ties to even; NaN stays NaN).
 // ---------------------------------------------------------------------------
 struct bf16_t {
     uint16_t bits;
@@ -41,11 +41,14 @@ struct bf16_t {
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
-__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;   // quiet NaN
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+// Two floats -> two bf16 packed in one dword (lo in bits 0..15): v_cvt_pk_bf16_f32 on gfx950.
+typedef __bf16 bf16x2_native __attribute__((ext_vector_type(2)));
+typedef float f32x2_native __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    const f32x2_native v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_native));
 }
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) { return pack_bf16x2(f, 0.f) & 0xFFFFu; }
 
 // Vec<T, V>: V consecutive elements of storage type T, moved with one access of
 // V * sizeof(T) bytes and exposed as V floats.
@@ -102,8 +105,8 @@ struct Vec<bf16_t, 4> {
     }
     __device__ __forceinline__ u2 pack() const {
         u2 v;
-        v.x = f32_to_bf16(f[0]) | (f32_to_bf16(f[1]) << 16);
-        v.y = f32_to_bf16(f[2]) | (f32_to_bf16(f[3]) << 16);
+        v.x = pack_bf16x2(f[0], f[1]);
+        v.y = pack_bf16x2(f[2], f[3]);
         return v;
     }
     __device__ __forceinline__ void load(const bf16_t* p) { unpack(*reinterpret_cast<const u2*>(p)); }
@@ -128,10 +131,10 @@ struct Vec<bf16_t, 8> {
     }
     __device__ __forceinline__ u4 pack() const {
         u4 v;
-        v.x = f32_to_bf16(f[0]) | (f32_to_bf16(f[1]) << 16);
-        v.y = f32_to_bf16(f[2]) | (f32_to_bf16(f[3]) << 16);
-        v.z = f32_to_bf16(f[4]) | (f32_to_bf16(f[5]) << 16);
-        v.w = f32_to_bf16(f[6]) | (f32_to_bf16(f[7]) << 16);
+        v.x = pack_bf16x2(f[0], f[1]);
+        v.y = pack_bf16x2(f[2], f[3]);
+        v.z = pack_bf16x2(f[4], f[5]);
+        v.w = pack_bf16x2(f[6], f[7]);
         return v;
     }
     __device__ __forceinline__ void load(const bf16_t* p) { unpack(*reinterpret_cast<const u4*>(p)); }
@@ -157,6 +160,13 @@ __device__ __forceinline__ float load_scalar<bf16_t>(const bf16_t* p) { return b
 // LDS, then the first wave adds the four in index order.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+// fp64 butterfly over the wave (fixed pattern): used by the finalize kernels, one wave per channel.
+__device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
     for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
     return v;

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kBlock) void stats_partial_planes_kernel(
         for (int u = 0; u < 4; ++u) {
             const uint32_t ju = j + u * kBlock;
             const uint32_t n = fdiv(ju, hwv_div);
-            v[u].load(base + n * nstride + size_t(ju - n * hwv) * V);
+            v[u].load_nt(base + n * nstride + size_t(ju - n * hwv) * V);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u)
@@ -95,13 +95,23 @@ __global__ __launch_bounds__(kBlock) void stats_partial_patch_kernel(
     const T* base = x + (size_t(b.n0) * C + c) * HW + size_t(b.h0) * W + b.w0;   // first sampled element
     const float pivot = load_scalar<T>(base);
 
-    float s1 = 0.f, s2 = 0.f;
-    for (uint32_t j = j0 + threadIdx.x; j < j1; j += kBlock) {
+    auto at = [&](uint32_t j) {
         const uint32_t n = fdiv(j, patch_div);
         const uint32_t r = j - n * patch_div.d;
         const uint32_t ph = fdiv(r, pw_div);
         const uint32_t pw = r - ph * pw_div.d;
-        const float dlt = load_scalar<T>(base + n * nstride + size_t(ph) * W + pw) - pivot;
+        return load_scalar<T>(base + n * nstride + size_t(ph) * W + pw);
+    };
+    float s1 = 0.f, s2 = 0.f;
+    uint32_t j = j0 + threadIdx.x;
+    for (; j + 3u * kBlock < j1; j += 4u * kBlock) {        // four independent loads in flight
+        const float v0 = at(j), v1 = at(j + kBlock), v2 = at(j + 2u * kBlock), v3 = at(j + 3u * kBlock);
+        const float d0 = v0 - pivot, d1 = v1 - pivot, d2 = v2 - pivot, d3 = v3 - pivot;
+        s1 += (d0 + d1) + (d2 + d3);
+        s2 = fmaf(d0, d0, fmaf(d1, d1, fmaf(d2, d2, fmaf(d3, d3, s2))));
+    }
+    for (; j < j1; j += kBlock) {
+        const float dlt = at(j) - pivot;
         s1 += dlt;
         s2 = fmaf(dlt, dlt, s2);
     }
@@ -109,24 +119,35 @@ __global__ __launch_bounds__(kBlock) void stats_partial_patch_kernel(
     if (threadIdx.x == 0) partial[size_t(c) * splits + k] = Partial{s1, s2};
 }
 
-// One thread per channel: add the splits in index order (fp64), then Eq. 3 and Eq. 8.
+// One wave per channel: lane k holds split k, fp64 butterfly (a fixed pattern, so the
+// rounding order never changes), then lane 0 applies Eq. 3 and Eq. 8.  splits <= 64.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void stats_finalize_kernel(
     const T* __restrict__ x, const Partial* __restrict__ partial, IndexParams ip, int C, int W, int HW,
     int splits, int c0, int cg, float eps, float momentum, float* __restrict__ save_mean,
     float* __restrict__ save_invstd, float* __restrict__ running_mean, float* __restrict__ running_var) {
-    const int cl = blockIdx.x * kBlock + threadIdx.x;
-    if (cl >= cg) return;
+    const int lane = threadIdx.x % kWave;
+    const int cl = blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    if (cl >= cg) return;                                           // whole wave leaves together
     const int c = c0 + cl;
-    const bns_box b = box_of_channel(ip, c);
-    const double s = double(b.n_cnt) * double(b.h_cnt) * double(b.w_cnt);
-    const double pivot = load_scalar<T>(x + (size_t(b.n0) * C + c) * HW + size_t(b.h0) * W + b.w0);
     double s1 = 0.0, s2 = 0.0;
-    for (int k = 0; k < splits; ++k) {
-        const Partial p = partial[size_t(c) * splits + k];
-        s1 += double(p.a);
-        s2 += double(p.b);
+    if (lane < splits) {
+        const Partial p = partial[size_t(c) * splits + lane];
+        s1 = double(p.a);
+        s2 = double(p.b);
     }
+    // loads that lane 0 needs, issued before the shuffles
+    const bns_box b = box_of_channel(ip, c);
+    double pivot = 0.0, rm = 0.0, rv = 0.0;
+    if (lane == 0) {
+        pivot = load_scalar<T>(x + (size_t(b.n0) * C + c) * HW + size_t(b.h0) * W + b.w0);
+        if (running_mean) rm = double(running_mean[c]);
+        if (running_var) rv = double(running_var[c]);
+    }
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    if (lane != 0) return;
+    const double s = double(b.n_cnt) * double(b.h_cnt) * double(b.w_cnt);
     const double m1 = s1 / s;
     const double mean = pivot + m1;
     double var = s2 / s - m1 * m1;
@@ -134,8 +155,8 @@ __global__ __launch_bounds__(kBlock) void stats_finalize_kernel(
     save_mean[c] = float(mean);
     save_invstd[c] = float(1.0 / sqrt(var + double(eps)));
     const double a = double(momentum);
-    if (running_mean) running_mean[c] = float((1.0 - a) * double(running_mean[c]) + a * mean);
-    if (running_var) running_var[c] = float((1.0 - a) * double(running_var[c]) + a * var);
+    if (running_mean) running_mean[c] = float((1.0 - a) * rm + a * mean);
+    if (running_var) running_var[c] = float((1.0 - a) * rv + a * var);
 }
 
 // ===========================================================================
@@ -263,17 +284,22 @@ __global__ __launch_bounds__(kBlock) void reduce_partial_kernel(
 __global__ __launch_bounds__(kBlock) void reduce_finalize_kernel(
     const Partial* __restrict__ partial, int splits, int c0, int cg, const float* __restrict__ invstd,
     float* __restrict__ dgamma, float* __restrict__ dbeta) {
-    const int cl = blockIdx.x * kBlock + threadIdx.x;
+    const int lane = threadIdx.x % kWave;
+    const int cl = blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
     if (cl >= cg) return;
     const int c = c0 + cl;
     double s1 = 0.0, s2 = 0.0;
-    for (int k = 0; k < splits; ++k) {
-        const Partial p = partial[size_t(c) * splits + k];
-        s1 += double(p.a);
-        s2 += double(p.b);
+    if (lane < splits) {
+        const Partial p = partial[size_t(c) * splits + lane];
+        s1 = double(p.a);
+        s2 = double(p.b);
     }
+    const float r = lane == 0 ? invstd[c] : 0.f;
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    if (lane != 0) return;
     dbeta[c] = float(s1);
-    dgamma[c] = float(s2 * double(invstd[c]));
+    dgamma[c] = float(s2 * double(r));
 }
 
 // ===========================================================================
@@ -464,7 +490,7 @@ hipError_t launch_stats_partial(const Dims& d, const IndexParams& ip, const void
 hipError_t launch_stats_finalize(const Dims& d, const IndexParams& ip, const void* x, const Partial* partial,
                                  int splits, int c0, int cg, float eps, float momentum, float* save_mean,
                                  float* save_invstd, float* running_mean, float* running_var, hipStream_t st) {
-    const dim3 grid(ceil_div(uint32_t(cg), kBlock));
+    const dim3 grid(ceil_div(uint32_t(cg), kBlock / kWave));
     if (d.dtype == BNS_F32)
         hipLaunchKernelGGL((stats_finalize_kernel<float>), grid, dim3(kBlock), 0, st,
                            static_cast<const float*>(x), partial, ip, d.C, d.W, d.HW, splits, c0, cg, eps, momentum,
@@ -519,7 +545,7 @@ hipError_t launch_reduce_partial(const Dims& d, const void* x, const void* dy, c
 hipError_t launch_reduce_finalize(const Dims& d, const Partial* partial, int splits, int c0, int cg,
                                   const float* invstd, float* dgamma, float* dbeta, hipStream_t st) {
     (void)d;
-    hipLaunchKernelGGL(reduce_finalize_kernel, dim3(ceil_div(uint32_t(cg), kBlock)), dim3(kBlock), 0, st, partial,
+    hipLaunchKernelGGL(reduce_finalize_kernel, dim3(ceil_div(uint32_t(cg), kBlock / kWave)), dim3(kBlock), 0, st, partial,
                        splits, c0, cg, invstd, dgamma, dbeta);
     return hipGetLastError();
 }

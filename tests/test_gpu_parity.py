@@ -265,6 +265,23 @@ def test_running_statistics_over_iterations_and_null_running_buffers():
     assert torch.equal(before, buf.running_mean)
 
 
+def test_bf16_stores_round_to_nearest_even():
+    """The bf16 path does the same fp32 arithmetic as the fp32 path on the same (bf16-representable)
+    inputs, so its outputs must be the fp32 outputs rounded to nearest-even: bit-equal almost
+    everywhere, and never more than one bf16 step apart (the statistics are summed in a different
+    order, which can move an fp32 result across a rounding boundary)."""
+    wl16 = workloads.WORKLOADS["cifar_fs"].replace(N=8, dtype="bf16")
+    inp = workloads.make_inputs(wl16)
+    r16 = bns.run_workload(wl16, inp)
+    r32 = bns.run_workload(wl16.replace(dtype="f32"), inp)
+    for k in ("y", "dx"):
+        want = torch.from_numpy(r32[k]).to(torch.bfloat16).view(torch.int16).numpy().astype(np.int32)
+        got = torch.from_numpy(r16[k]).to(torch.bfloat16).view(torch.int16).numpy().astype(np.int32)
+        diff = np.abs(want - got)
+        assert diff.max() <= 1, k
+        assert (diff == 0).mean() > 0.999, (k, (diff == 0).mean())
+
+
 def test_copy_reference():
     src = torch.arange(0, 1 << 20, dtype=torch.int32, device="cuda:0")
     for n in (4, 1024, 4096 + 4, 1 << 20):
