@@ -69,7 +69,8 @@ bns_status check_spec(const bns_shape* sh, const bns_spec* sp) {
 
 inline size_t elem_bytes(const Dims& d) { return d.dtype == BNS_F32 ? 4 : 2; }
 inline size_t tensor_bytes(const Dims& d) { return size_t(d.N) * d.C * d.HW * elem_bytes(d); }
-inline size_t workspace_need(const Dims& d) { return size_t(d.C) * kMaxSplits * sizeof(Partial); }
+inline size_t partial_bytes(const Dims& d) { return (size_t(d.C) * kMaxSplits * sizeof(Partial) + 255) & ~size_t(255); }
+inline size_t workspace_need(const Dims& d) { return partial_bytes(d) + kSlotBytes; }
 
 inline bns_status dev(hipError_t e) { return e == hipSuccess ? BNS_OK : BNS_EDEVICE; }
 
@@ -198,6 +199,22 @@ bns_status bns_forward(const bns_shape* shape, const bns_spec* spec, uint64_t se
     const IndexParams ip = make_index_params(*shape, *spec, seed);
     hipStream_t st = static_cast<hipStream_t>(stream);
     Partial* ws = static_cast<Partial*>(workspace);
+    if (g_tuning.path != 1) {
+        FusedIo io;
+        io.x = x;
+        io.out = y;
+        io.gamma = gamma;
+        io.beta = beta;
+        io.save_mean = save_mean;
+        io.save_invstd = save_invstd;
+        io.running_mean = running_mean;
+        io.running_var = running_var;
+        const hipError_t fe = launch_fused(d, ip, false, io, eps, momentum,
+                                           static_cast<char*>(workspace) + partial_bytes(d), kSlotBytes, 0, d.C, st);
+        if (fe == hipSuccess) return BNS_OK;
+        if (fe != hipErrorNotSupported) return BNS_EDEVICE;
+        if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
+    }
     const int G = channel_group(d);
     for (int c0 = 0; c0 < d.C; c0 += G) {
         const int cg = (d.C - c0 < G) ? d.C - c0 : G;
@@ -254,6 +271,22 @@ bns_status bns_backward(const bns_shape* shape, const bns_spec* spec, uint64_t s
     const IndexParams ip = make_index_params(*shape, *spec, seed);
     hipStream_t st = static_cast<hipStream_t>(stream);
     Partial* ws = static_cast<Partial*>(workspace);
+    if (g_tuning.path != 1) {
+        FusedIo io;
+        io.x = x;
+        io.dy = dy;
+        io.out = dx;
+        io.gamma = gamma;
+        io.save_mean = const_cast<float*>(save_mean);
+        io.save_invstd = const_cast<float*>(save_invstd);
+        io.dgamma = dgamma;
+        io.dbeta = dbeta;
+        const hipError_t fe = launch_fused(d, ip, true, io, 0.f, 0.f, static_cast<char*>(workspace) + partial_bytes(d),
+                                           kSlotBytes, 0, d.C, st);
+        if (fe == hipSuccess) return BNS_OK;
+        if (fe != hipErrorNotSupported) return BNS_EDEVICE;
+        if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
+    }
     const int G = channel_group(d);
     for (int c0 = 0; c0 < d.C; c0 += G) {
         const int cg = (d.C - c0 < G) ? d.C - c0 : G;
@@ -294,10 +327,13 @@ bns_status bns_set_option(const char* name, int32_t value) {
         {"reduce_unroll", &g_tuning.reduce_unroll, 4, 0}, {"reduce_nt", &g_tuning.reduce_nt, 2, 1},
         {"reduce_split_major", &g_tuning.reduce_split_major, 1, 0},
         {"reduce_align", &g_tuning.reduce_align, 1, 0},
+        {"path", &g_tuning.path, 2, 0},
+        {"fused_variant", &g_tuning.fused_variant, 7, 0},
+        {"fused_coop", &g_tuning.fused_coop, 1, 0},
     };
     for (auto& t : tun)
         if (!strcmp(name, t.n)) {
-            if (value > t.hi || (value == 3 && t.hi == 4 && t.bias == 0)) return BNS_EINVAL;
+            if (value > t.hi || (value == 3 && t.hi == 4 && t.bias == 0 && t.n[0] != 'f')) return BNS_EINVAL;
             *t.p = value - t.bias;
             return BNS_OK;
         }

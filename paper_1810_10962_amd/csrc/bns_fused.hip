@@ -1,0 +1,636 @@
+// Fused single-launch kernels: a channel stays on chip between its reduction and its
+// element-wise pass.
+//
+// The paper counts the cost of BN in reductions over m points followed by a second pass
+// over the same data (Sec. 3.1, Fig. 1c/d).  On MI355X a channel of a typical layer
+// (0.1 - 1 MB) fits in the vector registers of one or a few compute units (512 KB each),
+// so the second pass need not touch HBM again:
+//
+//   forward : read x once, keep it in registers, statistics over S (Eq. 3), normalise
+//             (Eq. 1), write y                               ->  2e bytes per element
+//   backward: read dy (kept in registers) and x once, sums over all m (Eq. 5), then
+//             dx (Eq. 6) re-reading x only on S              ->  (3 + r)e bytes per element
+//
+// A *team* of T blocks owns one channel at a time; each member keeps 1/T of the channel's
+// vectors in registers (KMAX 16-byte vectors per thread).  Members exchange their partial
+// sums through stamped slots in the workspace (an all-gather): each slot word is a 64-bit
+// value {payload float, 32-bit stamp} written and polled with relaxed agent-scope atomics,
+// so payload and stamp always arrive together and no slot has to be cleared beforehand.
+// Every member adds the T partials in member order, so all members get bit-identical
+// statistics, and results do not depend on timing.
+//
+// The grid is launched cooperatively (all blocks co-resident), which is what makes waiting
+// on a team-mate safe.  The wait is bounded: if a team-mate's slot never arrives, the sums
+// become NaN and the kernel still runs to completion.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+
+#include "bns_device.hpp"
+#include "bns_internal.hpp"
+
+namespace bns {
+
+namespace {
+
+// ---------------------------------------------------------------------------------------
+// RawVec<T, V>: V storage elements as they sit in memory (kept packed in registers).
+// ---------------------------------------------------------------------------------------
+template <typename T, int V>
+struct RawVec;
+
+template <>
+struct RawVec<float, 1> {
+    typedef float raw_t;
+    static __device__ __forceinline__ raw_t ld(const float* p) { return __builtin_nontemporal_load(p); }
+    static __device__ __forceinline__ void st(float* p, raw_t r) { __builtin_nontemporal_store(r, p); }
+    static __device__ __forceinline__ void unpack(raw_t r, float* f) { f[0] = r; }
+    static __device__ __forceinline__ raw_t pack(const float* f) { return f[0]; }
+};
+template <>
+struct RawVec<float, 4> {
+    typedef float raw_t __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ raw_t ld(const float* p) {
+        return __builtin_nontemporal_load(reinterpret_cast<const raw_t*>(p));
+    }
+    static __device__ __forceinline__ void st(float* p, raw_t r) {
+        __builtin_nontemporal_store(r, reinterpret_cast<raw_t*>(p));
+    }
+    static __device__ __forceinline__ void unpack(raw_t r, float* f) {
+        f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w;
+    }
+    static __device__ __forceinline__ raw_t pack(const float* f) { return raw_t{f[0], f[1], f[2], f[3]}; }
+};
+template <>
+struct RawVec<bf16_t, 1> {
+    typedef uint16_t raw_t;
+    static __device__ __forceinline__ raw_t ld(const bf16_t* p) { return p->bits; }
+    static __device__ __forceinline__ void st(bf16_t* p, raw_t r) { p->bits = r; }
+    static __device__ __forceinline__ void unpack(raw_t r, float* f) { f[0] = bf16_to_f32(r); }
+    static __device__ __forceinline__ raw_t pack(const float* f) { return uint16_t(f32_to_bf16(f[0])); }
+};
+template <>
+struct RawVec<bf16_t, 4> {
+    typedef uint32_t raw_t __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ raw_t ld(const bf16_t* p) {
+        return __builtin_nontemporal_load(reinterpret_cast<const raw_t*>(p));
+    }
+    static __device__ __forceinline__ void st(bf16_t* p, raw_t r) {
+        __builtin_nontemporal_store(r, reinterpret_cast<raw_t*>(p));
+    }
+    static __device__ __forceinline__ void unpack(raw_t r, float* f) {
+        f[0] = bf16_to_f32(r.x & 0xFFFFu); f[1] = __uint_as_float(r.x & 0xFFFF0000u);
+        f[2] = bf16_to_f32(r.y & 0xFFFFu); f[3] = __uint_as_float(r.y & 0xFFFF0000u);
+    }
+    static __device__ __forceinline__ raw_t pack(const float* f) {
+        return raw_t{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3])};
+    }
+};
+template <>
+struct RawVec<bf16_t, 8> {
+    typedef uint32_t raw_t __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ raw_t ld(const bf16_t* p) {
+        return __builtin_nontemporal_load(reinterpret_cast<const raw_t*>(p));
+    }
+    static __device__ __forceinline__ void st(bf16_t* p, raw_t r) {
+        __builtin_nontemporal_store(r, reinterpret_cast<raw_t*>(p));
+    }
+    static __device__ __forceinline__ void unpack(raw_t r, float* f) {
+        f[0] = bf16_to_f32(r.x & 0xFFFFu); f[1] = __uint_as_float(r.x & 0xFFFF0000u);
+        f[2] = bf16_to_f32(r.y & 0xFFFFu); f[3] = __uint_as_float(r.y & 0xFFFF0000u);
+        f[4] = bf16_to_f32(r.z & 0xFFFFu); f[5] = __uint_as_float(r.z & 0xFFFF0000u);
+        f[6] = bf16_to_f32(r.w & 0xFFFFu); f[7] = __uint_as_float(r.w & 0xFFFF0000u);
+    }
+    static __device__ __forceinline__ raw_t pack(const float* f) {
+        return raw_t{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
+                     pack_bf16x2(f[6], f[7])};
+    }
+};
+
+constexpr int kMaxTeam = 1024;            // members of a team (T)
+constexpr uint32_t kSpinLimit = 1u << 21; // polls before a missing team-mate is given up on
+
+struct FusedArgs {
+    const void* x;
+    const void* dy;   // backward only
+    void* out;        // forward: y; backward: dx
+    const float* gamma;
+    const float* beta;
+    float* save_mean;     // forward: written; backward: read
+    float* save_invstd;
+    float* running_mean;
+    float* running_var;
+    float* dgamma;
+    float* dbeta;
+    unsigned long long* slots;  // [2][gridDim.x][2] words of {payload, stamp}
+    IndexParams ip;
+    FastDiv hwv_div, w_div;
+    int32_t C, W, HW;
+    int32_t c0, cg;
+    int32_t T, num_teams;
+    uint32_t per;   // vectors per team member
+    uint32_t tot;   // vectors per channel: N * HW / V
+    uint32_t stamp0;
+    float eps, momentum, inv_s;
+    double s;       // |S| per channel
+};
+
+// Block-wide sum of (a, b) over NT threads; result returned to every thread.
+template <int NT>
+__device__ __forceinline__ void block_allsum2(float& a, float& b, float* red) {
+    a = wave_sum(a);
+    b = wave_sum(b);
+    constexpr int nw = NT / kWave;
+    if (nw > 1) {
+        const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+        __syncthreads();                       // red[] may still be read from the previous use
+        if (lane == 0) {
+            red[wave] = a;
+            red[nw + wave] = b;
+        }
+        __syncthreads();
+        float sa = red[0], sb = red[nw];
+#pragma unroll
+        for (int w = 1; w < nw; ++w) {
+            sa += red[w];
+            sb += red[nw + w];
+        }
+        a = sa;
+        b = sb;
+    }
+}
+
+// All-gather of one (a, b) pair per team member, summed in member order in fp64.
+// Returns the team totals to every thread of the block.
+template <int NT>
+__device__ __forceinline__ void team_allsum2(const FusedArgs& A, int team_first_block, int j, uint32_t it,
+                                             float a, float b, double& ta, double& tb, float* team_lds,
+                                             double* bc) {
+    if (A.T == 1) {
+        ta = double(a);
+        tb = double(b);
+        return;
+    }
+    const uint32_t stamp = A.stamp0 + it;
+    unsigned long long* base = A.slots + size_t(it & 1u) * gridDim.x * 2;
+    if (threadIdx.x == 0) {
+        unsigned long long* mine = base + size_t(team_first_block + j) * 2;
+        __hip_atomic_store(mine, (static_cast<unsigned long long>(stamp) << 32) | __float_as_uint(a),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(mine + 1, (static_cast<unsigned long long>(stamp) << 32) | __float_as_uint(b),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    for (int t = threadIdx.x; t < A.T; t += NT) {
+        unsigned long long* theirs = base + size_t(team_first_block + t) * 2;
+        float pa = __builtin_nanf(""), pb = __builtin_nanf("");
+        for (uint32_t spin = 0; spin < kSpinLimit; ++spin) {
+            const unsigned long long wa = __hip_atomic_load(theirs, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned long long wb = __hip_atomic_load(theirs + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (uint32_t(wa >> 32) == stamp && uint32_t(wb >> 32) == stamp) {
+                pa = __uint_as_float(uint32_t(wa));
+                pb = __uint_as_float(uint32_t(wb));
+                break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+        }
+        team_lds[t] = pa;
+        team_lds[kMaxTeam + t] = pb;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double sa = 0.0, sb = 0.0;
+        for (int t = 0; t < A.T; ++t) {
+            sa += double(team_lds[t]);
+            sb += double(team_lds[kMaxTeam + t]);
+        }
+        bc[0] = sa;
+        bc[1] = sb;
+    }
+    __syncthreads();
+    ta = bc[0];
+    tb = bc[1];
+}
+
+// Returns v unchanged but opaque to the optimiser.  Each phase of a fused kernel derives its
+// addresses from its own opaque copy of the thread's first vector index, so that the compiler
+// recomputes them (a few integer operations) instead of keeping KMAX 64-bit addresses alive
+// across phases next to the KMAX data vectors.
+__device__ __forceinline__ uint32_t opaque(uint32_t v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
+// Same for a data vector: stops the compiler from keeping the unpacked (wider) form of a packed
+// bf16 vector alive from the reduction phase to the element-wise phase.
+template <typename R>
+__device__ __forceinline__ void opaque_raw(R& r) {
+    asm volatile("" : "+v"(r));
+}
+template <>
+__device__ __forceinline__ void opaque_raw<uint16_t>(uint16_t& r) {
+    uint32_t t = r;
+    asm volatile("" : "+v"(t));
+    r = uint16_t(t);
+}
+
+// Is element (h, w) of sample n inside the box?  Whole-vector shortcuts are taken by the callers.
+__device__ __forceinline__ bool in_hw(const bns_box& b, uint32_t h, uint32_t w) {
+    return h >= uint32_t(b.h0) && h < uint32_t(b.h0 + b.h_cnt) && w >= uint32_t(b.w0) && w < uint32_t(b.w0 + b.w_cnt);
+}
+
+// ---------------------------------------------------------------------------------------
+// Forward: Eq. 3 + Eq. 8 + Eq. 1 with x read once
+// ---------------------------------------------------------------------------------------
+template <typename T, int V, int KMAX, int NT>
+__global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
+    typedef RawVec<T, V> RV;
+    __shared__ float red[2 * (NT / kWave)];
+    __shared__ float team_lds[2 * kMaxTeam];
+    __shared__ double bc[2];
+    const int team = blockIdx.x / A.T;
+    if (team >= A.num_teams) return;                       // blocks beyond the last whole team
+    const int j = blockIdx.x - team * A.T;
+    const uint32_t hwv = A.hwv_div.d;
+    const uint32_t beg = uint32_t(j) * A.per;
+    const uint32_t end = min(beg + A.per, A.tot);
+    const size_t nstride = size_t(A.C) * A.HW;
+    const T* x = static_cast<const T*>(A.x);
+    T* y = static_cast<T*>(A.out);
+
+    uint32_t it = 0;
+    for (int cl = team; cl < A.cg; cl += A.num_teams, ++it) {
+        const int c = A.c0 + cl;
+        const bns_box b = box_of_channel(A.ip, c);
+        const T* xc = x + size_t(c) * A.HW;
+        T* yc = y + size_t(c) * A.HW;
+        const float pivot = load_scalar<T>(xc + size_t(b.n0) * nstride + size_t(b.h0) * A.W + b.w0);
+        const bool full_hw = b.h_cnt * b.w_cnt == A.HW;
+
+        typename RV::raw_t v[KMAX];
+        const uint32_t ia = opaque(beg + threadIdx.x);
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+            const uint32_t i = ia + uint32_t(k) * NT;
+            if (i < end) {
+                const uint32_t n = fdiv(i, A.hwv_div);
+                v[k] = RV::ld(xc + n * nstride + size_t(i - n * hwv) * V);
+            }
+        }
+        float s1 = 0.f, s2 = 0.f;
+        const uint32_t ib = opaque(beg + threadIdx.x);
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+            const uint32_t i = ib + uint32_t(k) * NT;
+            if (i < end) {
+                const uint32_t n = fdiv(i, A.hwv_div);
+                if (n >= uint32_t(b.n0) && n < uint32_t(b.n0 + b.n_cnt)) {
+                    float f[V];
+                    RV::unpack(v[k], f);
+                    if (full_hw) {
+#pragma unroll
+                        for (int e = 0; e < V; ++e) {
+                            const float d = f[e] - pivot;
+                            s1 += d;
+                            s2 = fmaf(d, d, s2);
+                        }
+                    } else {
+                        const uint32_t e0 = (i - n * hwv) * V;
+                        if (e0 + V > uint32_t(b.h0) * A.W && e0 < uint32_t(b.h0 + b.h_cnt) * A.W) {
+                            uint32_t h = fdiv(e0, A.w_div);
+                            uint32_t w = e0 - h * uint32_t(A.W);
+#pragma unroll
+                            for (int e = 0; e < V; ++e) {
+                                if (in_hw(b, h, w)) {
+                                    const float d = f[e] - pivot;
+                                    s1 += d;
+                                    s2 = fmaf(d, d, s2);
+                                }
+                                if (++w == uint32_t(A.W)) {
+                                    w = 0;
+                                    ++h;
+                                }
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        block_allsum2<NT>(s1, s2, red);
+        double t1, t2;
+        team_allsum2<NT>(A, team * A.T, j, it, s1, s2, t1, t2, team_lds, bc);
+
+        // Eq. 3 (every thread computes the same values from the same totals)
+        const double m1 = t1 / A.s;
+        const double mean = double(pivot) + m1;
+        double var = t2 / A.s - m1 * m1;
+        if (!(var >= 0.0)) var = (var != var) ? var : 0.0;      // clamp rounding; keep NaN visible
+        const float mu = float(mean);
+        const float r = float(1.0 / sqrt(var + double(A.eps)));
+        if (j == 0 && threadIdx.x == 0) {
+            A.save_mean[c] = mu;
+            A.save_invstd[c] = r;
+            const double al = double(A.momentum);
+            if (A.running_mean) A.running_mean[c] = float((1.0 - al) * double(A.running_mean[c]) + al * mean);
+            if (A.running_var) A.running_var[c] = float((1.0 - al) * double(A.running_var[c]) + al * var);
+        }
+        const float sc = A.gamma[c] * r;
+        const float sh = A.beta[c];
+        const uint32_t ic = opaque(beg + threadIdx.x);
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+            const uint32_t i = ic + uint32_t(k) * NT;
+            if (i < end) {
+                const uint32_t n = fdiv(i, A.hwv_div);
+                float f[V];
+                opaque_raw(v[k]);
+                RV::unpack(v[k], f);
+#pragma unroll
+                for (int e = 0; e < V; ++e) f[e] = fmaf(f[e] - mu, sc, sh);
+                RV::st(yc + n * nstride + size_t(i - n * hwv) * V, RV::pack(f));
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Backward: Eq. 5 sums + Eq. 6 with dy read once
+// ---------------------------------------------------------------------------------------
+template <typename T, int V, int KMAX, int NT>
+__global__ __launch_bounds__(NT) void fused_backward_kernel(FusedArgs A) {
+    typedef RawVec<T, V> RV;
+    __shared__ float red[2 * (NT / kWave)];
+    __shared__ float team_lds[2 * kMaxTeam];
+    __shared__ double bc[2];
+    const int team = blockIdx.x / A.T;
+    if (team >= A.num_teams) return;
+    const int j = blockIdx.x - team * A.T;
+    const uint32_t hwv = A.hwv_div.d;
+    const uint32_t beg = uint32_t(j) * A.per;
+    const uint32_t end = min(beg + A.per, A.tot);
+    const size_t nstride = size_t(A.C) * A.HW;
+    const T* x = static_cast<const T*>(A.x);
+    const T* dy = static_cast<const T*>(A.dy);
+    T* dx = static_cast<T*>(A.out);
+
+    uint32_t it = 0;
+    for (int cl = team; cl < A.cg; cl += A.num_teams, ++it) {
+        const int c = A.c0 + cl;
+        const bns_box b = box_of_channel(A.ip, c);
+        const T* xc = x + size_t(c) * A.HW;
+        const T* gc = dy + size_t(c) * A.HW;
+        T* dc = dx + size_t(c) * A.HW;
+        const float mu = A.save_mean[c];
+        const float r = A.save_invstd[c];
+        const float ga = A.gamma[c];
+
+        typename RV::raw_t g[KMAX];
+        const uint32_t ia = opaque(beg + threadIdx.x);
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+            const uint32_t i = ia + uint32_t(k) * NT;
+            if (i < end) {
+                const uint32_t n = fdiv(i, A.hwv_div);
+                g[k] = RV::ld(gc + n * nstride + size_t(i - n * hwv) * V);
+            }
+        }
+        float s1 = 0.f, s2 = 0.f;
+        constexpr int XB = (KMAX >= 50 || V == 8) ? 2 : 4;        // x vectors in flight per thread (register budget)
+        const uint32_t ib = opaque(beg + threadIdx.x);
+#pragma unroll
+        for (int k0 = 0; k0 < KMAX; k0 += XB) {
+            typename RV::raw_t xv[XB];
+#pragma unroll
+            for (int u = 0; u < XB; ++u) {
+                const uint32_t i = ib + uint32_t(k0 + u) * NT;
+                if (k0 + u < KMAX && i < end) {
+                    const uint32_t n = fdiv(i, A.hwv_div);
+                    xv[u] = RV::ld(xc + n * nstride + size_t(i - n * hwv) * V);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < XB; ++u) {
+                const uint32_t i = ib + uint32_t(k0 + u) * NT;
+                if (k0 + u < KMAX && i < end) {
+                    float fg[V], fx[V];
+                    RV::unpack(g[k0 + u < KMAX ? k0 + u : 0], fg);
+                    RV::unpack(xv[u], fx);
+#pragma unroll
+                    for (int e = 0; e < V; ++e) {
+                        s1 += fg[e];
+                        s2 = fmaf(fg[e], fx[e] - mu, s2);
+                    }
+                }
+            }
+        }
+        block_allsum2<NT>(s1, s2, red);
+        double t1, t2;
+        team_allsum2<NT>(A, team * A.T, j, it, s1, s2, t1, t2, team_lds, bc);
+
+        const float dbeta = float(t1);
+        const float dgamma = float(t2 * double(r));
+        if (j == 0 && threadIdx.x == 0) {
+            A.dbeta[c] = dbeta;
+            A.dgamma[c] = dgamma;
+        }
+        const float a = ga * r;
+        const float k1 = a * A.inv_s * dbeta;
+        const float k2 = a * A.inv_s * dgamma * r;
+        const uint32_t ic = opaque(beg + threadIdx.x);
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+            const uint32_t i = ic + uint32_t(k) * NT;
+            if (i < end) {
+                const uint32_t n = fdiv(i, A.hwv_div);
+                const uint32_t off = i - n * hwv;
+                const uint32_t e0 = off * V;
+                float f[V];
+                opaque_raw(g[k]);
+                RV::unpack(g[k], f);
+                const bool touches = n >= uint32_t(b.n0) && n < uint32_t(b.n0 + b.n_cnt) &&
+                                     e0 + V > uint32_t(b.h0) * A.W && e0 < uint32_t(b.h0 + b.h_cnt) * A.W;
+                if (touches) {
+                    float fx[V];
+                    RV::unpack(RV::ld(xc + n * nstride + size_t(off) * V), fx);
+                    uint32_t h = fdiv(e0, A.w_div);
+                    uint32_t w = e0 - h * uint32_t(A.W);
+#pragma unroll
+                    for (int e = 0; e < V; ++e) {
+                        const float corr = in_hw(b, h, w) ? fmaf(k2, fx[e] - mu, k1) : 0.f;
+                        f[e] = fmaf(a, f[e], -corr);
+                        if (++w == uint32_t(A.W)) {
+                            w = 0;
+                            ++h;
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < V; ++e) f[e] *= a;
+                }
+                RV::st(dc + n * nstride + size_t(off) * V, RV::pack(f));
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Host side: choice of block size, registers per thread and team size
+// ---------------------------------------------------------------------------------------
+struct Variant {
+    int nt, kmax;
+};
+// (threads per block, 16-byte vectors per thread).  Registers grow with kmax, so small
+// channels take small variants and several blocks share a compute unit.
+constexpr Variant kVariants[] = {{64, 1}, {128, 2}, {256, 4}, {512, 8}, {512, 16}, {512, 32}, {512, 50}};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
+template <typename T, int V>
+const void* kernel_ptr(bool backward, int variant) {
+#define BNS_CASE(I, NT_, K_)                                                                        \
+    case I:                                                                                         \
+        return backward ? reinterpret_cast<const void*>(&fused_backward_kernel<T, V, K_, NT_>)      \
+                        : reinterpret_cast<const void*>(&fused_forward_kernel<T, V, K_, NT_>);
+    switch (variant) {
+        BNS_CASE(0, 64, 1)
+        BNS_CASE(1, 128, 2)
+        BNS_CASE(2, 256, 4)
+        BNS_CASE(3, 512, 8)
+        BNS_CASE(4, 512, 16)
+        BNS_CASE(5, 512, 32)
+        BNS_CASE(6, 512, 50)
+    }
+#undef BNS_CASE
+    return nullptr;
+}
+
+const void* kernel_for(const Dims& d, bool backward, int variant) {
+    if (d.dtype == BNS_F32) return d.vec == 4 ? kernel_ptr<float, 4>(backward, variant) : kernel_ptr<float, 1>(backward, variant);
+    if (d.vec == 8) return kernel_ptr<bf16_t, 8>(backward, variant);
+    if (d.vec == 4) return kernel_ptr<bf16_t, 4>(backward, variant);
+    return kernel_ptr<bf16_t, 1>(backward, variant);
+}
+
+struct DeviceInfo {
+    int cus = 0;
+    int coop = 0;
+    int blocks_per_cu[2][5][kNumVariants];  // [backward][type/vec combo][variant], 0 = not queried yet
+};
+DeviceInfo g_dev[16];
+
+int combo_index(const Dims& d) {
+    if (d.dtype == BNS_F32) return d.vec == 4 ? 0 : 1;
+    return d.vec == 8 ? 2 : d.vec == 4 ? 3 : 4;
+}
+
+std::atomic<uint32_t> g_stamp{1};
+
+}  // namespace
+
+// Plans and launches one fused pass over channels [c0, c0 + cg).  Returns hipErrorNotSupported
+// when the channel does not fit on chip (the caller then takes the streaming kernels).
+hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, const FusedIo& io, float eps,
+                        float momentum, void* slots, size_t slot_bytes, int c0, int cg, hipStream_t st) {
+    int devid = 0;
+    hipError_t e = hipGetDevice(&devid);
+    if (e != hipSuccess) return e;
+    if (devid < 0 || devid >= 16) return hipErrorNotSupported;
+    DeviceInfo& di = g_dev[devid];
+    if (di.cus == 0) {
+        int cus = 0, coop = 0;
+        if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, devid)) != hipSuccess) return e;
+        if ((e = hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, devid)) != hipSuccess) return e;
+        di.coop = coop;
+        di.cus = cus;
+    }
+    if (!di.coop || di.cus <= 0) return hipErrorNotSupported;
+
+    const uint32_t hwv = uint32_t(d.HW / d.vec);
+    const uint32_t tot = uint32_t(d.N) * hwv;
+    const int combo = combo_index(d);
+
+    // Every variant moves the same bytes, so what differs is the number of rounds (each round
+    // ends in a team exchange) and the team size.  Take the fewest rounds; among those the
+    // smallest variant (most threads per compute unit) whose teams stay small, else the
+    // smallest team.  With fewer channels than blocks a team is widened so every block has work.
+    int best = -1, bestT = 0, best_blocks = 0;
+    long best_key = -1;
+    for (int v = 0; v < kNumVariants; ++v) {
+        if (g_tuning.fused_variant > 0 && v != g_tuning.fused_variant - 1) continue;
+        const Variant& va = kVariants[v];
+        int& bpc = di.blocks_per_cu[backward ? 1 : 0][combo][v];
+        if (bpc == 0) {
+            int nb = 0;
+            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel_for(d, backward, v), va.nt, 0);
+            if (e != hipSuccess) return e;
+            bpc = nb > 0 ? nb : -1;
+        }
+        if (bpc < 0) continue;
+        const int blocks = di.cus * bpc;
+        const uint32_t cap = uint32_t(va.nt) * uint32_t(va.kmax);           // vectors one block can hold
+        long T = long((tot + cap - 1) / cap);                               // members needed for one channel
+        if (T > blocks || T > kMaxTeam) continue;
+        if (long(cg) * T < blocks) {
+            long Tw = blocks / cg;
+            if (Tw > kMaxTeam) Tw = kMaxTeam;
+            if (Tw > T) T = Tw;
+        }
+        const long teams = blocks / T < cg ? blocks / T : cg;
+        const long rounds = (cg + teams - 1) / teams;
+        const long key = rounds * 100000 + (T == 1 ? 0 : T <= 64 ? 1 : T) * 8 + v;   // smaller is better
+        if (best < 0 || key < best_key) {
+            best = v;
+            bestT = int(T);
+            best_blocks = blocks;
+            best_key = key;
+        }
+    }
+    if (best < 0) return hipErrorNotSupported;
+    // Measured on MI355X: with every channel in flight at once (one round) the fused kernels beat
+    // the streaming kernels at every size tried; with several rounds all teams alternate between
+    // a read-only and a write-only phase in step and lose more bandwidth than the saved bytes buy.
+    if (best_key >= 200000 && g_tuning.path != 2) return hipErrorNotSupported;
+
+    FusedArgs A;
+    A.x = io.x;
+    A.dy = io.dy;
+    A.out = io.out;
+    A.gamma = io.gamma;
+    A.beta = io.beta;
+    A.save_mean = io.save_mean;
+    A.save_invstd = io.save_invstd;
+    A.running_mean = io.running_mean;
+    A.running_var = io.running_var;
+    A.dgamma = io.dgamma;
+    A.dbeta = io.dbeta;
+    A.slots = static_cast<unsigned long long*>(slots);
+    A.ip = ip;
+    A.hwv_div = make_fastdiv(hwv);
+    A.w_div = make_fastdiv(uint32_t(d.W));
+    A.C = d.C;
+    A.W = d.W;
+    A.HW = d.HW;
+    A.c0 = c0;
+    A.cg = cg;
+    A.T = bestT;
+    A.num_teams = best_blocks / bestT;
+    if (A.num_teams > cg) A.num_teams = cg;
+    A.per = (tot + uint32_t(bestT) - 1) / uint32_t(bestT);
+    A.tot = tot;
+    const uint32_t rounds = uint32_t((cg + A.num_teams - 1) / A.num_teams);
+    A.stamp0 = g_stamp.fetch_add(rounds + 1);
+    A.eps = eps;
+    A.momentum = momentum;
+    const bns_box& b = ip.shared;
+    A.s = double(b.n_cnt) * double(b.h_cnt) * double(b.w_cnt);
+    A.inv_s = float(1.0 / A.s);
+
+    const int grid = A.num_teams * bestT;
+    if (size_t(grid) * 2 * 2 * sizeof(unsigned long long) > slot_bytes) return hipErrorNotSupported;
+    if (uint64_t(A.per) > uint64_t(kVariants[best].nt) * kVariants[best].kmax) return hipErrorNotSupported;
+    void* params[] = {&A};
+    if (g_tuning.fused_coop)
+        return hipLaunchCooperativeKernel(kernel_for(d, backward, best), dim3(grid), dim3(kVariants[best].nt), params,
+                                          0, st);
+    return hipLaunchKernel(kernel_for(d, backward, best), dim3(grid), dim3(kVariants[best].nt), params, 0, st);
+}
+
+}  // namespace bns

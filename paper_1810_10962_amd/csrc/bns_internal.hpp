@@ -29,6 +29,10 @@ struct Tuning {
     int reduce_unroll = 0, reduce_nt = -1;
     int reduce_split_major = 0;             // block order of the backward reduction
     int reduce_align = 0;                   // round a block's range up to whole planes
+    int path = 0;                           // 0: fused kernels when a channel fits on chip, else streaming;
+                                            // 1: streaming kernels only; 2: fused only (error if it cannot)
+    int fused_variant = 0;                  // 1..7 forces a (block size, registers) variant of the fused kernels
+    int fused_coop = 0;                     // 1: launch the fused kernels with hipLaunchCooperativeKernel
 };
 extern Tuning g_tuning;
 inline int tuned(int v, int dflt) { return v > 0 ? v : dflt; }
@@ -59,6 +63,25 @@ hipError_t launch_reduce_finalize(const Dims& d, const Partial* partial, int spl
 hipError_t launch_dx(const Dims& d, const IndexParams& ip, const void* x, const void* dy, const float* gamma,
                      const float* mean, const float* invstd, const float* dgamma, const float* dbeta,
                      void* dx, int c0, int cg, hipStream_t st);
+
+// Fused single-launch passes (bns_fused.hip).  Pointers a pass does not use are null.
+struct FusedIo {
+    const void* x = nullptr;
+    const void* dy = nullptr;
+    void* out = nullptr;
+    const float* gamma = nullptr;
+    const float* beta = nullptr;
+    float* save_mean = nullptr;
+    float* save_invstd = nullptr;
+    float* running_mean = nullptr;
+    float* running_var = nullptr;
+    float* dgamma = nullptr;
+    float* dbeta = nullptr;
+};
+constexpr size_t kSlotBytes = 256 * 1024;   // stamped exchange slots of the fused kernels
+// hipErrorNotSupported: the channel does not fit on chip (take the streaming kernels instead).
+hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, const FusedIo& io, float eps,
+                        float momentum, void* slots, size_t slot_bytes, int c0, int cg, hipStream_t st);
 
 hipError_t launch_index_boxes(const IndexParams& ip, int C, bns_box* boxes, hipStream_t st);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
