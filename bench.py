@@ -264,6 +264,16 @@ def main():
                                   effective_GBs=round(va / vsec / 1e9, 1),
                                   pct_of_hbm_peak=round(100 * va / vsec / 1e9 / HBM_PEAK_GBS, 2),
                                   elements_per_s=round(v.elements / vsec, 1))
+            # the two kernel families side by side: streaming (several kernels, HBM re-read) and
+            # fused (one launch per direction, channel kept on chip); `us_per_step` above is the default
+            for label, path in (("streaming_us", 1), ("fused_us", 2)):
+                bns.bns_set_option("path", path)
+                try:
+                    variants[name][label] = round(time_steps(vds, max(K // 2, 10), max(W // 2, 5), torch) * 1e6, 2)
+                except bns.BnsError:
+                    variants[name][label] = None
+                finally:
+                    bns.bns_set_option("path", 0)
             del vds
             torch.cuda.empty_cache()
         for name, v in variants.items():
@@ -273,6 +283,20 @@ def main():
         out["variants"] = variants
         if wl.name in variants and "speedup_vs_full_bn" in variants[wl.name]:
             out["speedup_vs_full_bn"] = variants[wl.name]["speedup_vs_full_bn"]
+        others = {}
+        for name in ("tiny_bs", "cifar_fs", "vdn", "micro_a_fs", "micro_a_full", "micro_b_fs", "micro_b_full"):
+            v = workloads.WORKLOADS[name]
+            vin = workloads.make_inputs(v)
+            vb = v.elements * 4
+            vds = DeviceSet(v, vin, max(2, min(8, int(np.ceil(1.5e9 / (4 * vb))))), torch, bns)
+            vr = sampling_ratio(v, bns.bns_sample_index(vds.bufs[0].shape, vds.bufs[0].spec, v.sampling_seed))
+            vsec = time_steps(vds, K, W, torch)
+            va = algorithmic_bytes(v, vr)["fwd+bwd"]
+            others[name] = dict(shape="x".join(map(str, v.shape)), label=v.label(), us_per_step=round(vsec * 1e6, 2),
+                                effective_GBs=round(va / vsec / 1e9, 1), elements_per_s=round(v.elements / vsec, 1))
+            del vds
+            torch.cuda.empty_cache()
+        out["other_configs"] = others
         out["paper_context"] = ("paper reports up to 2x BN-layer speedup and up to 20% end-to-end (TensorFlow, "
                                 "Titan Xp / V100, Sec. 5.2, Table 3); no kernel-level bandwidth is published")
     print(json.dumps(out))

@@ -165,6 +165,46 @@ bns_status bns_backward_dx(const bns_shape* shape, const bns_spec* spec, uint64_
                            const float* dgamma, const float* dbeta,
                            void* dx, void* stream);
 
+/* "VDN + sampling" (Sec. 4.2 step 3, Eq. 4).  The tensor holds n_v virtual samples in front of
+ * N - n_v real ones (Alg. 3).  `spec` (mode FULL, NS, BS or FS) is the sampling strategy applied to
+ * the REAL samples, exactly as Alg. 1 / Alg. 2 on a batch of N - n_v samples shifted by n_v.  With
+ * x_v the virtual set and x_s the sampled real set, each statistic by Eq. 3 on its own set,
+ *   E   = mix_beta * E[x_v]   + (1 - mix_beta) * E[x_s]
+ *   Var = mix_beta * Var[x_v] + (1 - mix_beta) * Var[x_s]           (the paper uses mix_beta = 0.5)
+ * save_mean / save_invstd hold the blended E and 1/sqrt(Var + eps); save_mean_parts (float[2*C])
+ * holds E[x_v] for every channel, then E[x_s] for every channel: the backward pass centres the
+ * variance terms on them.  Everything else as bns_forward.
+ * Errors as bns_forward, plus BNS_EINVAL for n_v outside [1, N-1], mix_beta outside [0, 1],
+ * mode VDN, or a spec that is invalid for N - n_v samples. */
+bns_status bns_sample_index_mixed(const bns_shape* shape, const bns_spec* spec, uint64_t seed, int32_t n_v,
+                                  bns_box* boxes /* HOST, C entries: the sampled REAL set */);
+bns_status bns_forward_mixed(const bns_shape* shape, const bns_spec* spec, uint64_t seed,
+                             int32_t n_v, float mix_beta,
+                             const void* x, const float* gamma, const float* beta,
+                             float eps, float momentum,
+                             void* y, float* save_mean, float* save_invstd, float* save_mean_parts,
+                             float* running_mean, float* running_var,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward of bns_forward_mixed.  The paper prints none for Eq. 4; by the chain rule, in the form
+ * of Eq. 5 / Eq. 6, with g = dl/dy, r = save_invstd, x^ = (x - E) r and dbeta, dgamma the sums over
+ * all points as in bns_backward:
+ *   dx_i = gamma r g_i - gamma r w (dbeta + r dgamma (x_i - E_set))
+ * with (w, E_set) = (mix_beta / s_v, E[x_v]) on the virtual set, ((1 - mix_beta) / s_s, E[x_s]) on
+ * the sampled real set, and w = 0 elsewhere. */
+bns_status bns_backward_mixed(const bns_shape* shape, const bns_spec* spec, uint64_t seed,
+                              int32_t n_v, float mix_beta,
+                              const void* x, const void* dy, const float* gamma,
+                              const float* save_mean, const float* save_invstd, const float* save_mean_parts,
+                              void* dx, float* dgamma, float* dbeta,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* Inference-mode normalisation (App. D): the statistics are the recorded moving averages of Eq. 8,
+ *   y = gamma * (x - running_mean) / sqrt(running_var + eps) + beta        for all points.
+ * in: x, gamma, beta, running_mean, running_var.  out: y. */
+bns_status bns_inference(const bns_shape* shape, const void* x, const float* gamma, const float* beta,
+                         const float* running_mean, const float* running_var, float eps, void* y, void* stream);
+
 /* Plain device-to-device copy of `bytes` bytes (a multiple of 16) with 128-bit accesses:
  * the "achievable bandwidth" yardstick that the benchmark reports beside the BN kernels,
  * and the known-size kernel that hardware traffic counters are calibrated against. */

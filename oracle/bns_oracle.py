@@ -15,7 +15,8 @@ What it follows, in the paper's notation:
 * Alg. 3  Virtual Dataset Normalisation: statistics from samples 0 .. n_v - 1
 * Eq. 5   BN backward, three partial derivatives
 * Eq. 6   sampled backward: the 1/s mean and variance terms only on x_i in S
-* Eq. 8   moving average, alpha weights the new value
+* Eq. 4   VDN combined with a sampling strategy: blended E and Var (backward derived, see there)
+* Eq. 8   moving average, alpha weights the new value; App. D: validation uses it in Eq. 1
 
 The paper stores activations as N x H x W x C; here tensors are N x C x H x W
 (the reduction is over the same three axes: samples, height, width).
@@ -173,6 +174,18 @@ def forward(x, gamma, beta, boxes, eps: float, momentum: float = 0.1,
     return out
 
 
+def inference(x, gamma, beta, moving_mean, moving_var, eps: float):
+    """Validation-time normalisation (Appendix D): E and Var of Eq. 1 are replaced by the
+    recorded moving averages of Eq. 8."""
+    x = np.asarray(x)
+    N, C, H, W = x.shape
+    y = np.empty((N, C, H, W), dtype=np.float64)
+    for k in range(C):
+        x_hat = (x[:, k].astype(np.float64) - float(moving_mean[k])) / math.sqrt(float(moving_var[k]) + eps)
+        y[:, k] = float(gamma[k]) * x_hat + float(beta[k])
+    return y
+
+
 # --------------------------------------------------------------------------
 # Backward: Eq. 5 with the Eq. 6 modification
 # --------------------------------------------------------------------------
@@ -207,6 +220,90 @@ def backward(x, dy, gamma, mean, var, boxes, eps: float):
         d[S] += dl_dE * (1.0 / s) + dl_dVar * (2.0 * (xk[S] - E) / s)     # x_i in S
         dx[:, k] = d
         dgamma[k] = (g * x_hat).sum()
+        dbeta[k] = g.sum()
+    return dict(dx=dx, dgamma=dgamma, dbeta=dbeta)
+
+
+# --------------------------------------------------------------------------
+# VDN combined with a sampling strategy: Eq. 4
+# --------------------------------------------------------------------------
+def sample_index_mixed(N: int, C: int, H: int, W: int, mode: int, n_v: int, *, n_s: int = 0,
+                       patch_h: int = 0, patch_w: int = 0, fs_per_channel: int = 0,
+                       seed: int = 0, layer_id: int = 0, epoch: int = 0):
+    """Location sets for "VDN + sampling" (Section 4.2, step 3; Eq. 4).
+
+    The batch holds n_v virtual samples in front of N - n_v real ones (Alg. 3).  Returns
+    (boxes_v, boxes_s): x_v = the virtual samples 0 .. n_v-1, x_s = the real samples
+    sampled by ``mode`` exactly as in Alg. 1 / Alg. 2 applied to the real part of the batch
+    (sample indices shifted by n_v).
+    """
+    real = sample_index(N - n_v, C, H, W, mode, n_s=n_s, patch_h=patch_h, patch_w=patch_w,
+                        fs_per_channel=fs_per_channel, seed=seed, layer_id=layer_id, epoch=epoch)
+    boxes_s = real.copy()
+    boxes_s[:, 0] += n_v
+    boxes_v = np.tile(np.array([[0, n_v, 0, H, 0, W]], dtype=np.int64), (C, 1))
+    return boxes_v, boxes_s
+
+
+def forward_mixed(x, gamma, beta, boxes_v, boxes_s, mix_beta: float, eps: float, momentum: float = 0.1,
+                  running_mean=None, running_var=None):
+    """Eq. 4: X = beta_mix * X[x_v] + (1 - beta_mix) * X[x_s] for X in {E, Var}, each X[.] by Eq. 3
+    on its own set (Var[x_v] about E[x_v], Var[x_s] about E[x_s]); then Eq. 1 on every point."""
+    x = np.asarray(x)
+    N, C, H, W = x.shape
+    y = np.empty((N, C, H, W), dtype=np.float64)
+    E, Var, E_v, E_s = (np.empty(C) for _ in range(4))
+    for k in range(C):
+        xk = x[:, k].astype(np.float64)
+        x_v = xk[subset_mask(N, H, W, boxes_v[k])]
+        x_s = xk[subset_mask(N, H, W, boxes_s[k])]
+        E_v[k] = x_v.sum() / x_v.size
+        E_s[k] = x_s.sum() / x_s.size
+        Var_v = ((x_v - E_v[k]) ** 2).sum() / x_v.size
+        Var_s = ((x_s - E_s[k]) ** 2).sum() / x_s.size
+        E[k] = mix_beta * E_v[k] + (1.0 - mix_beta) * E_s[k]            # Eq. 4, X = E
+        Var[k] = mix_beta * Var_v + (1.0 - mix_beta) * Var_s            # Eq. 4, X = Var
+        y[:, k] = float(gamma[k]) * (xk - E[k]) / math.sqrt(Var[k] + eps) + float(beta[k])
+    out = dict(y=y, mean=E, var=Var, invstd=1.0 / np.sqrt(Var + eps), mean_v=E_v, mean_s=E_s)
+    if running_mean is not None:
+        a = float(momentum)
+        out["running_mean"] = a * E + (1.0 - a) * np.asarray(running_mean, dtype=np.float64)
+        out["running_var"] = a * Var + (1.0 - a) * np.asarray(running_var, dtype=np.float64)
+    return out
+
+
+def backward_mixed(x, dy, gamma, mean, var, mean_v, mean_s, boxes_v, boxes_s, mix_beta: float, eps: float):
+    """Backward of ``forward_mixed``.  The paper prints no backward for Eq. 4; this is the chain
+    rule in the form of Eq. 5 / Eq. 6: dl/dx^, dl/dE and dl/dVar exactly as in Eq. 5 (with the
+    blended E and Var), and
+
+        dl/dx_i = dl/dx^_i / sqrt(Var + eps) + dl/dE * dE/dx_i + dl/dVar * dVar/dx_i
+
+    where, from Eq. 4 and Eq. 3, dE/dx_i = beta_mix / s_v and dVar/dx_i = beta_mix 2 (x_i - E_v) / s_v
+    for x_i in the virtual set, (1 - beta_mix) / s_s and (1 - beta_mix) 2 (x_i - E_s) / s_s for x_i in
+    the sampled real set, and zero elsewhere (the second branch of Eq. 6)."""
+    x = np.asarray(x)
+    dy = np.asarray(dy)
+    N, C, H, W = x.shape
+    dx = np.empty((N, C, H, W), dtype=np.float64)
+    dgamma = np.empty(C)
+    dbeta = np.empty(C)
+    for k in range(C):
+        xk = x[:, k].astype(np.float64)
+        g = dy[:, k].astype(np.float64)
+        E, V = float(mean[k]), float(var[k])
+        r = 1.0 / math.sqrt(V + eps)
+        dl_dxhat = g * float(gamma[k])
+        dl_dE = (dl_dxhat * (-r)).sum()
+        dl_dVar = (dl_dxhat * (xk - E) * (-0.5) * (V + eps) ** (-1.5)).sum()
+        d = dl_dxhat * r
+        for box, weight, centre in ((boxes_v[k], mix_beta, float(mean_v[k])),
+                                    (boxes_s[k], 1.0 - mix_beta, float(mean_s[k]))):
+            S = subset_mask(N, H, W, box)
+            s = subset_size(box)
+            d[S] += dl_dE * (weight / s) + dl_dVar * (weight * 2.0 * (xk[S] - centre) / s)
+        dx[:, k] = d
+        dgamma[k] = (g * (xk - E) * r).sum()
         dbeta[k] = g.sum()
     return dict(dx=dx, dgamma=dgamma, dbeta=dbeta)
 

@@ -59,6 +59,12 @@ _PROTOS = {
     "bns_forward_normalize": (C.c_int, [_SHP, _P, _P, _P, _P, _P, _P, _P]),
     "bns_backward_reduce": (C.c_int, [_SHP, _P, _P, _P, _P, _P, _P, _P, C.c_size_t, _P]),
     "bns_backward_dx": (C.c_int, [_SHP, _SPC, C.c_uint64, _P, _P, _P, _P, _P, _P, _P, _P, _P]),
+    "bns_sample_index_mixed": (C.c_int, [_SHP, _SPC, C.c_uint64, C.c_int32, C.POINTER(bns_box)]),
+    "bns_forward_mixed": (C.c_int, [_SHP, _SPC, C.c_uint64, C.c_int32, C.c_float, _P, _P, _P, C.c_float, C.c_float,
+                                    _P, _P, _P, _P, _P, _P, _P, C.c_size_t, _P]),
+    "bns_backward_mixed": (C.c_int, [_SHP, _SPC, C.c_uint64, C.c_int32, C.c_float, _P, _P, _P, _P, _P, _P,
+                                     _P, _P, _P, _P, C.c_size_t, _P]),
+    "bns_inference": (C.c_int, [_SHP, _P, _P, _P, _P, _P, C.c_float, _P, _P]),
     "bns_copy_reference": (C.c_int, [_P, _P, C.c_size_t, _P]),
     "bns_set_option": (C.c_int, [C.c_char_p, C.c_int32]),
     "bns_get_option": (C.c_int32, [C.c_char_p]),
@@ -201,6 +207,40 @@ def bns_backward_dx(shape, spec, seed, x, dy, gamma, save_mean, save_invstd, dga
                                   _stream(x)), "bns_backward_dx")
 
 
+def bns_sample_index_mixed(shape: bns_shape, spec: bns_spec, seed: int, n_v: int) -> np.ndarray:
+    """Host index of the sampled real set for "VDN + sampling": int32 array [C, 6]."""
+    lib = load()
+    n = max(int(shape.C), 0)
+    arr = (bns_box * max(n, 1))()
+    _check(lib.bns_sample_index_mixed(C.byref(shape), C.byref(spec), C.c_uint64(seed), C.c_int32(n_v), arr),
+           "bns_sample_index_mixed")
+    return _boxes_to_numpy(arr, n)
+
+
+def bns_forward_mixed(shape, spec, seed, n_v, mix_beta, x, gamma, beta, eps, momentum, y, save_mean, save_invstd,
+                      save_mean_parts, running_mean, running_var, workspace):
+    _check(load().bns_forward_mixed(C.byref(shape), C.byref(spec), C.c_uint64(seed), C.c_int32(n_v),
+                                    C.c_float(mix_beta), _ptr(x), _ptr(gamma), _ptr(beta), C.c_float(eps),
+                                    C.c_float(momentum), _ptr(y), _ptr(save_mean), _ptr(save_invstd),
+                                    _ptr(save_mean_parts), _ptr(running_mean), _ptr(running_var), _ptr(workspace),
+                                    C.c_size_t(workspace.numel() * workspace.element_size()), _stream(x)),
+           "bns_forward_mixed")
+
+
+def bns_backward_mixed(shape, spec, seed, n_v, mix_beta, x, dy, gamma, save_mean, save_invstd, save_mean_parts,
+                       dx, dgamma, dbeta, workspace):
+    _check(load().bns_backward_mixed(C.byref(shape), C.byref(spec), C.c_uint64(seed), C.c_int32(n_v),
+                                     C.c_float(mix_beta), _ptr(x), _ptr(dy), _ptr(gamma), _ptr(save_mean),
+                                     _ptr(save_invstd), _ptr(save_mean_parts), _ptr(dx), _ptr(dgamma), _ptr(dbeta),
+                                     _ptr(workspace), C.c_size_t(workspace.numel() * workspace.element_size()),
+                                     _stream(x)), "bns_backward_mixed")
+
+
+def bns_inference(shape, x, gamma, beta, running_mean, running_var, eps, y):
+    _check(load().bns_inference(C.byref(shape), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(running_mean),
+                                _ptr(running_var), C.c_float(eps), _ptr(y), _stream(x)), "bns_inference")
+
+
 def bns_copy_reference(dst, src):
     nbytes = src.numel() * src.element_size()
     _check(load().bns_copy_reference(_ptr(dst), _ptr(src), C.c_size_t(nbytes), _stream(src)), "bns_copy_reference")
@@ -244,12 +284,24 @@ class Buffers:
         self.dbeta = torch.empty(wl.C, **f32)
         self.workspace = torch.empty(max(bns_workspace_bytes(self.shape, self.spec), 16), dtype=torch.uint8,
                                      device=dev)
+        self.n_v = getattr(wl, "n_v", 0) if wl.mode != BNS_VDN else 0
+        self.save_mean_parts = torch.empty(2 * wl.C, **f32) if self.n_v else None
 
     def forward(self):
+        if self.n_v:
+            bns_forward_mixed(self.shape, self.spec, self.seed, self.n_v, self.wl.mix_beta, self.x, self.gamma,
+                              self.beta, self.wl.eps, self.wl.momentum, self.y, self.save_mean, self.save_invstd,
+                              self.save_mean_parts, self.running_mean, self.running_var, self.workspace)
+            return
         bns_forward(self.shape, self.spec, self.seed, self.x, self.gamma, self.beta, self.wl.eps, self.wl.momentum,
                     self.y, self.save_mean, self.save_invstd, self.running_mean, self.running_var, self.workspace)
 
     def backward(self):
+        if self.n_v:
+            bns_backward_mixed(self.shape, self.spec, self.seed, self.n_v, self.wl.mix_beta, self.x, self.dy,
+                               self.gamma, self.save_mean, self.save_invstd, self.save_mean_parts, self.dx,
+                               self.dgamma, self.dbeta, self.workspace)
+            return
         bns_backward(self.shape, self.spec, self.seed, self.x, self.dy, self.gamma, self.save_mean,
                      self.save_invstd, self.dx, self.dgamma, self.dbeta, self.workspace)
 
@@ -260,7 +312,9 @@ class Buffers:
         return dict(y=host(self.y), dx=host(self.dx), save_mean=host(self.save_mean),
                     save_invstd=host(self.save_invstd), running_mean=host(self.running_mean),
                     running_var=host(self.running_var), dgamma=host(self.dgamma), dbeta=host(self.dbeta),
-                    boxes=bns_sample_index(self.shape, self.spec, self.seed))
+                    boxes=(bns_sample_index_mixed(self.shape, self.spec, self.seed, self.n_v) if self.n_v
+                           else bns_sample_index(self.shape, self.spec, self.seed)),
+                    **({"save_mean_parts": host(self.save_mean_parts)} if self.n_v else {}))
 
 
 def run_workload(wl, inputs, device="cuda:0"):

@@ -70,7 +70,7 @@ bns_status check_spec(const bns_shape* sh, const bns_spec* sp) {
 inline size_t elem_bytes(const Dims& d) { return d.dtype == BNS_F32 ? 4 : 2; }
 inline size_t tensor_bytes(const Dims& d) { return size_t(d.N) * d.C * d.HW * elem_bytes(d); }
 inline size_t partial_bytes(const Dims& d) { return (size_t(d.C) * kMaxSplits * sizeof(Partial) + 255) & ~size_t(255); }
-inline size_t workspace_need(const Dims& d) { return partial_bytes(d) + kSlotBytes; }
+inline size_t workspace_need(const Dims& d) { return 2 * partial_bytes(d) + kSlotBytes; }   // [sums S][sums V][slots]
 
 inline bns_status dev(hipError_t e) { return e == hipSuccess ? BNS_OK : BNS_EDEVICE; }
 
@@ -183,6 +183,19 @@ bns_status bns_forward_normalize(const bns_shape* shape, const void* x, const fl
     return dev(launch_normalize(d, x, gamma, beta, save_mean, save_invstd, y, 0, d.C, static_cast<hipStream_t>(stream)));
 }
 
+bns_status bns_inference(const bns_shape* shape, const void* x, const float* gamma, const float* beta,
+                         const float* running_mean, const float* running_var, float eps, void* y, void* stream) {
+    Dims d;
+    bns_status s = check_shape(shape, &d);
+    if (s != BNS_OK) return s;
+    if (!x || !gamma || !beta || !running_mean || !running_var || !y) return BNS_EINVAL;
+    if (!aligned16(x) || !aligned16(y)) return BNS_EINVAL;
+    if (!(eps >= 0.f)) return BNS_EINVAL;
+    if (overlap(x, tensor_bytes(d), y, tensor_bytes(d))) return BNS_EINVAL;
+    return dev(launch_normalize(d, x, gamma, beta, running_mean, running_var, y, 0, d.C,
+                                static_cast<hipStream_t>(stream), eps));
+}
+
 bns_status bns_forward(const bns_shape* shape, const bns_spec* spec, uint64_t seed, const void* x,
                        const float* gamma, const float* beta, float eps, float momentum, void* y, float* save_mean,
                        float* save_invstd, float* running_mean, float* running_var, void* workspace,
@@ -210,7 +223,7 @@ bns_status bns_forward(const bns_shape* shape, const bns_spec* spec, uint64_t se
         io.running_mean = running_mean;
         io.running_var = running_var;
         const hipError_t fe = launch_fused(d, ip, false, io, eps, momentum,
-                                           static_cast<char*>(workspace) + partial_bytes(d), kSlotBytes, 0, d.C, st);
+                                           static_cast<char*>(workspace) + 2 * partial_bytes(d), kSlotBytes, 0, d.C, st);
         if (fe == hipSuccess) return BNS_OK;
         if (fe != hipErrorNotSupported) return BNS_EDEVICE;
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
@@ -281,7 +294,7 @@ bns_status bns_backward(const bns_shape* shape, const bns_spec* spec, uint64_t s
         io.save_invstd = const_cast<float*>(save_invstd);
         io.dgamma = dgamma;
         io.dbeta = dbeta;
-        const hipError_t fe = launch_fused(d, ip, true, io, 0.f, 0.f, static_cast<char*>(workspace) + partial_bytes(d),
+        const hipError_t fe = launch_fused(d, ip, true, io, 0.f, 0.f, static_cast<char*>(workspace) + 2 * partial_bytes(d),
                                            kSlotBytes, 0, d.C, st);
         if (fe == hipSuccess) return BNS_OK;
         if (fe != hipErrorNotSupported) return BNS_EDEVICE;
@@ -296,6 +309,86 @@ bns_status bns_backward(const bns_shape* shape, const bns_spec* spec, uint64_t s
         if (s != BNS_OK) return s;
     }
     return BNS_OK;
+}
+
+// ---- "VDN + sampling", Eq. 4 ---------------------------------------------------------------
+namespace {
+bns_status check_mixed(const bns_shape* shape, const bns_spec* spec, int32_t n_v, float mix_beta, Dims* d) {
+    bns_status s = check_shape(shape, d);
+    if (s != BNS_OK) return s;
+    if (!spec || n_v < 1 || n_v >= shape->N) return BNS_EINVAL;
+    if (!(mix_beta >= 0.f && mix_beta <= 1.f)) return BNS_EINVAL;
+    if (spec->mode == BNS_VDN) return BNS_EINVAL;            // the real part needs a sampling strategy
+    bns_shape real = *shape;
+    real.N = shape->N - n_v;
+    return check_spec(&real, spec);
+}
+}  // namespace
+
+bns_status bns_sample_index_mixed(const bns_shape* shape, const bns_spec* spec, uint64_t seed, int32_t n_v,
+                                  bns_box* boxes) {
+    Dims d;
+    bns_status s = check_mixed(shape, spec, n_v, 0.5f, &d);
+    if (s != BNS_OK) return s;
+    if (!boxes) return BNS_EINVAL;
+    const IndexParams ip = make_index_params_mixed(*shape, *spec, seed, n_v);
+    for (int c = 0; c < d.C; ++c) boxes[c] = box_of_channel(ip, c);
+    return BNS_OK;
+}
+
+bns_status bns_forward_mixed(const bns_shape* shape, const bns_spec* spec, uint64_t seed, int32_t n_v, float mix_beta,
+                             const void* x, const float* gamma, const float* beta, float eps, float momentum,
+                             void* y, float* save_mean, float* save_invstd, float* save_mean_parts,
+                             float* running_mean, float* running_var, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+    Dims d;
+    bns_status s = check_mixed(shape, spec, n_v, mix_beta, &d);
+    if (s != BNS_OK) return s;
+    if (!x || !gamma || !beta || !y || !save_mean || !save_invstd || !save_mean_parts || !workspace) return BNS_EINVAL;
+    if (!aligned16(x) || !aligned16(y) || !aligned16(workspace)) return BNS_EINVAL;
+    if (overlap(x, tensor_bytes(d), y, tensor_bytes(d))) return BNS_EINVAL;
+    if (!(eps >= 0.f) || !(momentum >= 0.f && momentum <= 1.f)) return BNS_EINVAL;
+    if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const IndexParams ip_s = make_index_params_mixed(*shape, *spec, seed, n_v);
+    const IndexParams ip_v = make_index_params_virtual(*shape, n_v);
+    Partial* ws_s = static_cast<Partial*>(workspace);
+    Partial* ws_v = reinterpret_cast<Partial*>(static_cast<char*>(workspace) + partial_bytes(d));
+    const int splits_s = stats_splits(d, ip_s, d.C);
+    const int splits_v = stats_splits(d, ip_v, d.C);
+    if (launch_stats_partial(d, ip_s, x, ws_s, splits_s, 0, d.C, st) != hipSuccess) return BNS_EDEVICE;
+    if (launch_stats_partial(d, ip_v, x, ws_v, splits_v, 0, d.C, st) != hipSuccess) return BNS_EDEVICE;
+    if (launch_stats_finalize_mixed(d, ip_s, ip_v, x, ws_s, splits_s, ws_v, splits_v, mix_beta, eps, momentum, save_mean,
+                                    save_invstd, save_mean_parts, running_mean, running_var, st) != hipSuccess)
+        return BNS_EDEVICE;
+    return dev(launch_normalize(d, x, gamma, beta, save_mean, save_invstd, y, 0, d.C, st));
+}
+
+bns_status bns_backward_mixed(const bns_shape* shape, const bns_spec* spec, uint64_t seed, int32_t n_v, float mix_beta,
+                              const void* x, const void* dy, const float* gamma, const float* save_mean,
+                              const float* save_invstd, const float* save_mean_parts, void* dx, float* dgamma,
+                              float* dbeta, void* workspace, size_t workspace_bytes, void* stream) {
+    Dims d;
+    bns_status s = check_mixed(shape, spec, n_v, mix_beta, &d);
+    if (s != BNS_OK) return s;
+    if (!x || !dy || !gamma || !save_mean || !save_invstd || !save_mean_parts || !dx || !dgamma || !dbeta || !workspace)
+        return BNS_EINVAL;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || !aligned16(workspace)) return BNS_EINVAL;
+    const size_t tb = tensor_bytes(d);
+    if (overlap(dx, tb, x, tb) || overlap(dx, tb, dy, tb)) return BNS_EINVAL;
+    if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const IndexParams ip_s = make_index_params_mixed(*shape, *spec, seed, n_v);
+    s = reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, static_cast<Partial*>(workspace), 0, d.C, st);
+    if (s != BNS_OK) return s;
+    const bns_box& b = ip_s.shared;
+    DxSets sets;
+    sets.n_v = n_v;
+    sets.w_s = float((1.0 - double(mix_beta)) / (double(b.n_cnt) * double(b.h_cnt) * double(b.w_cnt)));
+    sets.w_v = float(double(mix_beta) / (double(n_v) * double(d.HW)));
+    sets.centre_v = save_mean_parts;
+    sets.centre_s = save_mean_parts + d.C;
+    return dev(launch_dx(d, ip_s, x, dy, gamma, save_mean, save_invstd, dgamma, dbeta, dx, 0, d.C, st, &sets));
 }
 
 bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* stream) {

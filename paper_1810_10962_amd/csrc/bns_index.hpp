@@ -95,4 +95,25 @@ inline IndexParams make_index_params(const bns_shape& sh, const bns_spec& sp, ui
     return p;
 }
 
+// "VDN + sampling" (Eq. 4): the first n_v samples are virtual, and the sampling strategy of
+// `sp` is applied to the N - n_v real samples behind them (Alg. 1 / Alg. 2 on the real part of
+// the batch, sample indices shifted by n_v).  Returns the index of the sampled REAL set.
+inline IndexParams make_index_params_mixed(const bns_shape& sh, const bns_spec& sp, uint64_t seed, int32_t n_v) {
+    bns_shape real = sh;
+    real.N = sh.N - n_v;
+    IndexParams p = make_index_params(real, sp, seed);
+    p.shared.n0 += n_v;
+    return p;
+}
+
+// The virtual set: samples 0 .. n_v-1, every row and column (Alg. 3).
+inline IndexParams make_index_params_virtual(const bns_shape& sh, int32_t n_v) {
+    IndexParams p;
+    p.key = 0;
+    p.per_channel = 0;
+    p.k_h = p.k_w = 0;
+    p.shared = bns_box{0, n_v, 0, sh.H, 0, sh.W};
+    return p;
+}
+
 }  // namespace bns

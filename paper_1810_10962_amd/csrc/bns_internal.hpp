@@ -51,18 +51,35 @@ hipError_t launch_stats_finalize(const Dims& d, const IndexParams& ip, const voi
                                  int splits, int c0, int cg, float eps, float momentum,
                                  float* save_mean, float* save_invstd, float* running_mean,
                                  float* running_var, hipStream_t st);
-// Eq. 1 over every element.
+// Eq. 1 over every element.  var_eps >= 0: `invstd` holds variances and 1/sqrt(var + var_eps) is used.
 hipError_t launch_normalize(const Dims& d, const void* x, const float* gamma, const float* beta,
-                            const float* mean, const float* invstd, void* y, int c0, int cg, hipStream_t st);
+                            const float* mean, const float* invstd, void* y, int c0, int cg, hipStream_t st,
+                            float var_eps = -1.f);
 // Backward sums of Eq. 5 over all m points: partial sums of dy and dy * (x - mean).
 hipError_t launch_reduce_partial(const Dims& d, const void* x, const void* dy, const float* mean,
                                  Partial* partial, int splits, int c0, int cg, hipStream_t st);
 hipError_t launch_reduce_finalize(const Dims& d, const Partial* partial, int splits, int c0, int cg,
                                   const float* invstd, float* dgamma, float* dbeta, hipStream_t st);
+// Which 1/s terms an element receives in the dx pass.  Plain sampled BN: one set, weight 1/s,
+// centred on the saved mean.  "VDN + sampling" (Eq. 4): samples below n_v form the virtual set
+// (weight beta_mix / s_v, centre E_v), the index describes the sampled real set (weight
+// (1 - beta_mix) / s_s, centre E_s).
+struct DxSets {
+    int32_t n_v = 0;
+    float w_s = 0.f, w_v = 0.f;
+    const float* centre_s = nullptr;
+    const float* centre_v = nullptr;
+};
 // Eq. 6 over every element.
 hipError_t launch_dx(const Dims& d, const IndexParams& ip, const void* x, const void* dy, const float* gamma,
                      const float* mean, const float* invstd, const float* dgamma, const float* dbeta,
-                     void* dx, int c0, int cg, hipStream_t st);
+                     void* dx, int c0, int cg, hipStream_t st, const DxSets* sets = nullptr);
+// Eq. 4: combine the partial sums of the virtual set and of the sampled real set.
+hipError_t launch_stats_finalize_mixed(const Dims& d, const IndexParams& ip_s, const IndexParams& ip_v, const void* x,
+                                       const Partial* partial_s, int splits_s, const Partial* partial_v,
+                                       int splits_v, float mix_beta, float eps, float momentum, float* save_mean,
+                                       float* save_invstd, float* mean_parts, float* running_mean,
+                                       float* running_var, hipStream_t st);
 
 // Fused single-launch passes (bns_fused.hip).  Pointers a pass does not use are null.
 struct FusedIo {

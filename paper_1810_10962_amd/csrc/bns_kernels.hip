@@ -159,6 +159,61 @@ __global__ __launch_bounds__(kBlock) void stats_finalize_kernel(
     if (running_var) running_var[c] = float((1.0 - a) * rv + a * var);
 }
 
+// "VDN + sampling" (Eq. 4): one wave per channel combines the partial sums of the sampled real
+// set and of the virtual set, each into its own E and Var (Eq. 3), and blends them.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void stats_finalize_mixed_kernel(
+    const T* __restrict__ x, const Partial* __restrict__ partial_s, int splits_s,
+    const Partial* __restrict__ partial_v, int splits_v, IndexParams ip_s, IndexParams ip_v, int C, int W, int HW,
+    float mix_beta, float eps, float momentum, float* __restrict__ save_mean, float* __restrict__ save_invstd,
+    float* __restrict__ mean_parts, float* __restrict__ running_mean, float* __restrict__ running_var) {
+    const int lane = threadIdx.x % kWave;
+    const int c = blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    if (c >= C) return;
+    double a1 = 0.0, a2 = 0.0, v1 = 0.0, v2 = 0.0;
+    if (lane < splits_s) {
+        const Partial p = partial_s[size_t(c) * splits_s + lane];
+        a1 = double(p.a);
+        a2 = double(p.b);
+    }
+    if (lane < splits_v) {
+        const Partial p = partial_v[size_t(c) * splits_v + lane];
+        v1 = double(p.a);
+        v2 = double(p.b);
+    }
+    const bns_box bs = box_of_channel(ip_s, c);
+    const bns_box bv = ip_v.shared;
+    double piv_s = 0.0, piv_v = 0.0, rm = 0.0, rv = 0.0;
+    if (lane == 0) {
+        piv_s = load_scalar<T>(x + (size_t(bs.n0) * C + c) * HW + size_t(bs.h0) * W + bs.w0);
+        piv_v = load_scalar<T>(x + size_t(c) * HW);
+        if (running_mean) rm = double(running_mean[c]);
+        if (running_var) rv = double(running_var[c]);
+    }
+    a1 = wave_sum(a1);
+    a2 = wave_sum(a2);
+    v1 = wave_sum(v1);
+    v2 = wave_sum(v2);
+    if (lane != 0) return;
+    const double ss = double(bs.n_cnt) * double(bs.h_cnt) * double(bs.w_cnt);
+    const double sv = double(bv.n_cnt) * double(bv.h_cnt) * double(bv.w_cnt);
+    const double ms = a1 / ss, mv = v1 / sv;
+    const double e_s = piv_s + ms, e_v = piv_v + mv;
+    double var_s = a2 / ss - ms * ms, var_v = v2 / sv - mv * mv;
+    if (var_s < 0.0) var_s = 0.0;
+    if (var_v < 0.0) var_v = 0.0;
+    const double bm = double(mix_beta);
+    const double mean = bm * e_v + (1.0 - bm) * e_s;            // Eq. 4, X = E
+    const double var = bm * var_v + (1.0 - bm) * var_s;         // Eq. 4, X = Var
+    save_mean[c] = float(mean);
+    save_invstd[c] = float(1.0 / sqrt(var + double(eps)));
+    mean_parts[c] = float(e_v);
+    mean_parts[C + c] = float(e_s);
+    const double al = double(momentum);
+    if (running_mean) running_mean[c] = float((1.0 - al) * rm + al * mean);
+    if (running_var) running_var[c] = float((1.0 - al) * rv + al * var);
+}
+
 // ===========================================================================
 // Forward normalise + affine over every element (Eq. 1)
 // ===========================================================================
@@ -168,7 +223,9 @@ template <typename T, int V, int U, int NT>
 __global__ __launch_bounds__(kBlock) void normalize_kernel(
     const T* __restrict__ x, T* __restrict__ y, const float* __restrict__ gamma,
     const float* __restrict__ beta, const float* __restrict__ mean, const float* __restrict__ invstd,
-    int C, int HW, FastDiv hwv_div, int c0, uint32_t run_vectors) {
+    int C, int HW, FastDiv hwv_div, int c0, uint32_t run_vectors, float var_eps) {
+    // var_eps >= 0: `invstd` holds variances (inference from the moving averages, App. D) and
+    // 1 / sqrt(var + var_eps) is taken here; var_eps < 0: it holds inverse standard deviations.
     const size_t run0 = (size_t(blockIdx.y) * C + c0) * HW;
     const T* xr = x + run0;
     T* yr = y + run0;
@@ -189,7 +246,8 @@ __global__ __launch_bounds__(kBlock) void normalize_kernel(
         if (vi < run_vectors) {
             const int c = c0 + int(fdiv(vi, hwv_div));
             mu[u] = mean[c];
-            sc[u] = gamma[c] * invstd[c];
+            const float r = var_eps >= 0.f ? 1.0f / sqrtf(invstd[c] + var_eps) : invstd[c];
+            sc[u] = gamma[c] * r;
             sh[u] = beta[c];
         }
     }
@@ -313,8 +371,11 @@ __global__ __launch_bounds__(kBlock) void dx_kernel(
     const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx, const float* __restrict__ gamma,
     const float* __restrict__ mean, const float* __restrict__ invstd, const float* __restrict__ dgamma,
     const float* __restrict__ dbeta, IndexParams ip, int C, int W, int HW, FastDiv hwv_div, FastDiv w_div,
-    int c0, uint32_t run_vectors, float inv_s) {
+    int c0, uint32_t run_vectors, DxSets sets) {
     const int n = blockIdx.y;
+    const bool virt = n < sets.n_v;                 // sample of the virtual set (Eq. 4); block-uniform
+    const float wgt = virt ? sets.w_v : sets.w_s;
+    const float* __restrict__ centre = virt ? sets.centre_v : sets.centre_s;
     const size_t run0 = (size_t(n) * C + c0) * HW;
     const T* xr = x + run0;
     const T* gr = dy + run0;
@@ -337,7 +398,7 @@ __global__ __launch_bounds__(kBlock) void dx_kernel(
         const uint32_t cl = fdiv(vi, hwv_div);
         const int c = c0 + int(cl);
         const uint32_t e0 = (vi - cl * hwv) * V;                  // first element, within its plane
-        const bns_box b = box_of_channel(ip, c);
+        const bns_box b = virt ? bns_box{0, sets.n_v, 0, HW / W, 0, W} : box_of_channel(ip, c);
         const float r = invstd[c];
         const float a = gamma[c] * r;
         // rows [h0, h0 + h_cnt) of the plane are the elements [h0 * W, (h0 + h_cnt) * W)
@@ -346,9 +407,9 @@ __global__ __launch_bounds__(kBlock) void dx_kernel(
         if (touches) {
             Vec<T, V> xv;
             if (NT & 1) xv.load_nt(xr + size_t(vi) * V); else xv.load(xr + size_t(vi) * V);
-            const float mu = mean[c];
-            const float k1 = a * inv_s * dbeta[c];
-            const float k2 = a * inv_s * dgamma[c] * r;
+            const float mu = centre[c];
+            const float k1 = a * wgt * dbeta[c];
+            const float k2 = a * wgt * dgamma[c] * r;
             uint32_t h = fdiv(e0, w_div);
             uint32_t w = e0 - h * uint32_t(W);
 #pragma unroll
@@ -502,8 +563,27 @@ hipError_t launch_stats_finalize(const Dims& d, const IndexParams& ip, const voi
     return hipGetLastError();
 }
 
+hipError_t launch_stats_finalize_mixed(const Dims& d, const IndexParams& ip_s, const IndexParams& ip_v, const void* x,
+                                       const Partial* partial_s, int splits_s, const Partial* partial_v,
+                                       int splits_v, float mix_beta, float eps, float momentum, float* save_mean,
+                                       float* save_invstd, float* mean_parts, float* running_mean,
+                                       float* running_var, hipStream_t st) {
+    const dim3 grid(ceil_div(uint32_t(d.C), kBlock / kWave));
+    if (d.dtype == BNS_F32)
+        hipLaunchKernelGGL((stats_finalize_mixed_kernel<float>), grid, dim3(kBlock), 0, st,
+                           static_cast<const float*>(x), partial_s, splits_s, partial_v, splits_v, ip_s, ip_v, d.C, d.W,
+                           d.HW, mix_beta, eps, momentum, save_mean, save_invstd, mean_parts, running_mean, running_var);
+    else
+        hipLaunchKernelGGL((stats_finalize_mixed_kernel<bf16_t>), grid, dim3(kBlock), 0, st,
+                           static_cast<const bf16_t*>(x), partial_s, splits_s, partial_v, splits_v, ip_s, ip_v, d.C,
+                           d.W, d.HW, mix_beta, eps, momentum, save_mean, save_invstd, mean_parts, running_mean,
+                           running_var);
+    return hipGetLastError();
+}
+
 hipError_t launch_normalize(const Dims& d, const void* x, const float* gamma, const float* beta,
-                            const float* mean, const float* invstd, void* y, int c0, int cg, hipStream_t st) {
+                            const float* mean, const float* invstd, void* y, int c0, int cg, hipStream_t st,
+                            float var_eps) {
     return dispatch(d, [&](auto t, auto vt) {
         using T = decltype(t);
         constexpr int V = decltype(vt)::value;
@@ -515,7 +595,7 @@ hipError_t launch_normalize(const Dims& d, const void* x, const float* gamma, co
             const dim3 grid(ceil_div(run_vectors, kBlock * U), uint32_t(d.N));
             hipLaunchKernelGGL((normalize_kernel<T, V, U, NT>), grid, dim3(kBlock), 0, st, static_cast<const T*>(x),
                                static_cast<T*>(y), gamma, beta, mean, invstd, d.C, d.HW, make_fastdiv(hwv), c0,
-                               run_vectors);
+                               run_vectors, var_eps);
             return hipGetLastError();
         });
     });
@@ -552,10 +632,16 @@ hipError_t launch_reduce_finalize(const Dims& d, const Partial* partial, int spl
 
 hipError_t launch_dx(const Dims& d, const IndexParams& ip, const void* x, const void* dy, const float* gamma,
                      const float* mean, const float* invstd, const float* dgamma, const float* dbeta, void* dx,
-                     int c0, int cg, hipStream_t st) {
+                     int c0, int cg, hipStream_t st, const DxSets* mixed) {
     const bns_box& b = ip.shared;
     const double s = double(b.n_cnt) * double(b.h_cnt) * double(b.w_cnt);
-    const float inv_s = float(1.0 / s);
+    DxSets sets;
+    if (mixed) {
+        sets = *mixed;
+    } else {
+        sets.w_s = float(1.0 / s);
+        sets.centre_s = mean;
+    }
     return dispatch(d, [&](auto t, auto vt) {
         using T = decltype(t);
         constexpr int V = decltype(vt)::value;
@@ -568,7 +654,7 @@ hipError_t launch_dx(const Dims& d, const IndexParams& ip, const void* x, const 
             hipLaunchKernelGGL((dx_kernel<T, V, U, NT>), grid, dim3(kBlock), 0, st, static_cast<const T*>(x),
                                static_cast<const T*>(dy), static_cast<T*>(dx), gamma, mean, invstd, dgamma, dbeta,
                                ip, d.C, d.W, d.HW, make_fastdiv(hwv), make_fastdiv(uint32_t(d.W)), c0, run_vectors,
-                               inv_s);
+                               sets);
             return hipGetLastError();
         });
     });

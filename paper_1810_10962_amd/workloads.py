@@ -40,6 +40,8 @@ class Workload:
     patch_h: int = 0        # FS
     patch_w: int = 0        # FS
     fs_per_channel: int = 0
+    n_v: int = 0            # "VDN + sampling" (Eq. 4): virtual samples in front; mode then samples the real ones
+    mix_beta: float = 0.5   # beta of Eq. 4
     dtype: str = "f32"      # "f32" | "bf16" : storage type of x, y, dy, dx
     data_seed: int = 0
     sampling_seed: int = 0
@@ -92,6 +94,10 @@ WORKLOADS = {
         _wl(3, "imagenet_fs_bf16", 64, 256, 56, 56, FS, patch_h=14, patch_w=14, dtype="bf16"),
         _wl(3, "imagenet_full_bf16", 64, 256, 56, 56, FULL, dtype="bf16"),
         _wl(4, "vdn", 130, 128, 28, 28, VDN, n_s=2),
+        # "FS + VDN", the paper's best-accuracy combination (Table 2): 2 virtual + 128 real samples,
+        # one 7x7 patch (1/16 of a 28x28 map) of every real sample, beta = 0.5
+        _wl(4, "vdn_fs_mix", 130, 128, 28, 28, FS, patch_h=7, patch_w=7, n_v=2, mix_beta=0.5),
+        _wl(4, "vdn_bs_mix", 130, 128, 28, 28, BS, n_s=4, n_v=2, mix_beta=0.5),
         _wl(5, "micro_a_fs", 2, 512, 14, 14, FS, patch_h=4, patch_w=4),
         _wl(5, "micro_a_full", 2, 512, 14, 14, FULL),
         _wl(6, "micro_b_fs", 1, 1024, 7, 7, FS, patch_h=4, patch_w=4),
@@ -167,8 +173,8 @@ def make_inputs(wl: Workload, channels: slice | None = None):
     x += mu[None, :, None, None]
     dy = rng.standard_normal(size=(N, C, H, W), dtype=np.float32)
 
-    if wl.mode == VDN:
-        n_v = wl.n_s
+    if wl.mode == VDN or wl.n_v > 0:
+        n_v = wl.n_s if wl.mode == VDN else wl.n_v
         cin = 3
         v_in = rng.uniform(0.0, 1.0, size=(n_v, cin, H, W))
         wgt = rng.standard_normal(size=(C, cin, 3, 3)) * np.sqrt(2.0 / (9 * cin))

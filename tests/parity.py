@@ -14,9 +14,30 @@ def oracle_boxes(wl, C=None):
                                layer_id=wl.layer_id, epoch=wl.epoch)
 
 
+def oracle_boxes_mixed(wl):
+    return oracle.sample_index_mixed(wl.N, wl.C, wl.H, wl.W, wl.mode, wl.n_v, n_s=wl.n_s, patch_h=wl.patch_h,
+                                     patch_w=wl.patch_w, fs_per_channel=wl.fs_per_channel, seed=wl.sampling_seed,
+                                     layer_id=wl.layer_id, epoch=wl.epoch)
+
+
+def oracle_reference_mixed(wl, inp):
+    """Oracle forward + backward for "VDN + sampling" (Eq. 4)."""
+    bv, bs = oracle_boxes_mixed(wl)
+    f = oracle.forward_mixed(inp["x"], inp["gamma"], inp["beta"], bv, bs, wl.mix_beta, wl.eps, wl.momentum,
+                             inp["running_mean"], inp["running_var"])
+    b = oracle.backward_mixed(inp["x"], inp["dy"], inp["gamma"], f["mean"], f["var"], f["mean_v"], f["mean_s"], bv, bs,
+                              wl.mix_beta, wl.eps)
+    return dict(y=f["y"], save_mean=f["mean"], save_invstd=f["invstd"], running_mean=f["running_mean"],
+                running_var=f["running_var"], dx=b["dx"], dgamma=b["dgamma"], dbeta=b["dbeta"],
+                save_mean_parts=np.concatenate([f["mean_v"], f["mean_s"]]))
+
+
 def oracle_reference(wl, inp, channels=None):
     """Oracle forward + backward.  ``channels``: list of channel ids to evaluate (all by default);
     the returned tensors then hold only those channels, in that order."""
+    if wl.n_v and wl.mode != 4:
+        assert channels is None
+        return oracle_reference_mixed(wl, inp)
     boxes = oracle_boxes(wl)
     if channels is not None:
         ch = np.asarray(channels)

@@ -129,6 +129,41 @@ def test_null_misaligned_overlapping_and_small_workspace_are_rejected_without_a_
     assert lib.bns_copy_reference(P(x), P(x + 32), 64, None) == bns.BNS_EINVAL
 
 
+def test_mixed_index_and_argument_checks():
+    rng = np.random.default_rng(4)
+    for _ in range(400):
+        N, H, W = int(rng.integers(2, 40)), int(rng.integers(1, 30)), int(rng.integers(1, 30))
+        C_ = int(rng.integers(1, 6))
+        n_v = int(rng.integers(1, N))
+        mode = int(rng.choice([o.FULL, o.NS, o.BS, o.FS]))
+        n_s = int(rng.integers(1, N - n_v + 1))
+        ph, pw, pc = int(rng.integers(1, H + 1)), int(rng.integers(1, W + 1)), int(rng.integers(0, 2))
+        seed, layer, epoch = int(rng.integers(0, 2 ** 62)), int(rng.integers(0, 2 ** 32)), int(rng.integers(0, 2 ** 32))
+        got = bns.bns_sample_index_mixed(bns.make_shape(N, C_, H, W), bns.make_spec(mode, n_s, ph, pw, pc, layer, epoch),
+                                         seed, n_v)
+        _, ref = o.sample_index_mixed(N, C_, H, W, mode, n_v, n_s=n_s, patch_h=ph, patch_w=pw, fs_per_channel=pc,
+                                      seed=seed, layer_id=layer, epoch=epoch)
+        assert (got == ref).all()
+    shape = bns.make_shape(8, 4, 6, 6)
+    _expect(bns.BNS_EINVAL, bns.bns_sample_index_mixed, shape, bns.make_spec(bns.BNS_BS, 2), 0, 0)      # no virtual sample
+    _expect(bns.BNS_EINVAL, bns.bns_sample_index_mixed, shape, bns.make_spec(bns.BNS_BS, 2), 0, 8)      # no real sample
+    _expect(bns.BNS_EINVAL, bns.bns_sample_index_mixed, shape, bns.make_spec(bns.BNS_BS, 7), 0, 2)      # n_s > real samples
+    _expect(bns.BNS_EINVAL, bns.bns_sample_index_mixed, shape, bns.make_spec(bns.BNS_VDN, 2), 0, 2)
+    lib = bns.load()
+    spec = bns.make_spec(bns.BNS_BS, 2)
+    P = lambda a: C.c_void_p(a)
+    need = bns.bns_workspace_bytes(shape, spec)
+    args = lambda n_v, mix, wsb=need, parts=0x70000: (C.byref(shape), C.byref(spec), 1, n_v, C.c_float(mix), P(0x10000),
+                                                      P(0x60000), P(0x60100), C.c_float(1e-5), C.c_float(0.1),
+                                                      P(0x20000), P(0x60200), P(0x60300), P(parts), None, None,
+                                                      P(0x50000), wsb, None)
+    assert lib.bns_forward_mixed(*args(2, 1.5)) == bns.BNS_EINVAL
+    assert lib.bns_forward_mixed(*args(2, -0.1)) == bns.BNS_EINVAL
+    assert lib.bns_forward_mixed(*args(0, 0.5)) == bns.BNS_EINVAL
+    assert lib.bns_forward_mixed(*args(2, 0.5, parts=0)) == bns.BNS_EINVAL
+    assert lib.bns_forward_mixed(*args(2, 0.5, wsb=need - 1)) == bns.BNS_EWORKSPACE
+
+
 def test_options():
     assert bns.bns_get_option("splits_stats") == 0 and bns.bns_get_option("nonsense") == -1
     bns.bns_set_option("splits_reduce", 8)

@@ -6,7 +6,7 @@ import torch
 from oracle import bns_oracle as oracle
 from paper_1810_10962_amd import bns, workloads
 from paper_1810_10962_amd.workloads import BS, FS, FULL, NS, VDN, Workload
-from parity import assert_parity, oracle_boxes, oracle_reference, scaled_err
+from parity import assert_parity, oracle_boxes, oracle_boxes_mixed, oracle_reference, scaled_err
 
 pytestmark = pytest.mark.gpu
 
@@ -325,6 +325,66 @@ def test_bf16_stores_round_to_nearest_even():
         diff = np.abs(want - got)
         assert diff.max() <= 1, k
         assert (diff == 0).mean() > 0.999, (k, (diff == 0).mean())
+
+
+MIXED_MODES = [
+    ("bs", dict(mode=BS, n_s=2)),
+    ("ns", dict(mode=NS, n_s=1)),
+    ("fs", dict(mode=FS, patch_h=3, patch_w=2)),
+    ("fs_pc", dict(mode=FS, patch_h=2, patch_w=3, fs_per_channel=1)),
+    ("full", dict(mode=FULL)),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mname,mkw", MIXED_MODES, ids=[m[0] for m in MIXED_MODES])
+@pytest.mark.parametrize("shape", [(6, 10, 8, 8), (5, 7, 7, 7), (9, 33, 6, 6), (12, 4, 40, 52)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_vdn_plus_sampling_small_shapes(shape, mname, mkw, dtype, kernel_path):
+    """Eq. 4: statistics blended from the virtual samples and the sampled real samples."""
+    if kernel_path != "auto":
+        pytest.skip("the mixed statistics have one kernel path")
+    N, C_, H, W = shape
+    for n_v, mix in ((1, 0.5), (2, 0.3), (2, 1.0), (1, 0.0)):
+        wl = Workload(name=f"mix_{mname}", N=N, C=C_, H=H, W=W, dtype=dtype, n_v=n_v, mix_beta=mix, data_seed=40 + n_v,
+                      sampling_seed=13, layer_id=6, epoch=n_v, **mkw)
+        inp, res = _run(wl)
+        bv, bs = oracle_boxes_mixed(wl)
+        assert (res["boxes"] == bs).all()
+        assert_parity(res, oracle_reference(wl, inp), wl, what=f"mixed {shape} {mname} {dtype} n_v={n_v} beta={mix}",
+                      inp=inp)
+
+
+@pytest.mark.parametrize("name", ["vdn_fs_mix", "vdn_bs_mix"])
+def test_vdn_plus_sampling_benchmark_shape(name, kernel_path):
+    if kernel_path != "auto":
+        pytest.skip("the mixed statistics have one kernel path")
+    wl = workloads.WORKLOADS[name]
+    inp, res = _run(wl)
+    errs = assert_parity(res, oracle_reference(wl, inp), wl, what=name, inp=inp)
+    _announce(f"{name} scaled errors {errs}")
+    again = bns.run_workload(wl, inp)
+    for k in res:
+        assert (res[k] == again[k]).all(), k
+
+
+@pytest.mark.parametrize("shape,dtype", [((6, 10, 12, 12), "f32"), ((3, 5, 7, 7), "f32"), ((8, 64, 28, 28), "bf16"),
+                                         ((4, 9, 6, 6), "bf16")])
+def test_inference_mode(shape, dtype, kernel_path):
+    if kernel_path != "auto":
+        pytest.skip("one kernel only")
+    N, C_, H, W = shape
+    wl = Workload(name="infer", N=N, C=C_, H=H, W=W, mode=FULL, dtype=dtype, data_seed=9)
+    inp = workloads.make_inputs(wl)
+    rng = np.random.default_rng(3)
+    rm = rng.standard_normal(C_).astype(np.float32)
+    rv = rng.uniform(0.2, 3.0, C_).astype(np.float32)
+    inp["running_mean"], inp["running_var"] = rm, rv
+    buf = bns.Buffers(wl, inp)
+    bns.bns_inference(buf.shape, buf.x, buf.gamma, buf.beta, buf.running_mean, buf.running_var, wl.eps, buf.y)
+    got = buf.results()["y"]
+    ref = oracle.inference(inp["x"], inp["gamma"], inp["beta"], rm, rv, wl.eps)
+    assert scaled_err(got, ref) <= (1e-5 if dtype == "f32" else 1e-2)
 
 
 def test_copy_reference():

@@ -127,3 +127,19 @@ def test_moving_average_variance_closed_form():
     ratio = rm.var() / 1.0
     assert ratio == pytest.approx(alpha / (2 - alpha), rel=0.1)
     np.testing.assert_allclose(rv, (1 - alpha) ** steps, rtol=1e-9)      # Var of one point is 0 each step
+
+
+def test_inference_is_torch_eval_batch_norm_and_continues_training_statistics():
+    N, C, H, W = 5, 4, 6, 3
+    x, gamma, beta = _data(N, C, H, W, seed=21)
+    rng = np.random.default_rng(1)
+    rm, rv = rng.standard_normal(C), rng.uniform(0.3, 2.0, C)
+    y = o.inference(x, gamma, beta, rm, rv, EPS)
+    ref = torch.nn.functional.batch_norm(torch.tensor(x), torch.tensor(rm), torch.tensor(rv), torch.tensor(gamma),
+                                         torch.tensor(beta), training=False, eps=EPS)
+    np.testing.assert_allclose(y, ref.numpy(), rtol=1e-12, atol=1e-13)
+    # Eq. 8 at it = 1 copies the statistics, so inference on the same batch reproduces the training output
+    boxes = o.sample_index(N, C, H, W, o.BS, n_s=2, seed=4)
+    f = o.forward(x, gamma, beta, boxes, EPS, momentum=1.0, running_mean=rm, running_var=rv)
+    np.testing.assert_allclose(o.inference(x, gamma, beta, f["running_mean"], f["running_var"], EPS), f["y"],
+                               rtol=1e-12, atol=1e-13)
