@@ -69,6 +69,7 @@ class DeviceSet:
         for _ in range(nset - 1):
             b = bns.Buffers.__new__(bns.Buffers)
             b.__dict__.update(self.bufs[0].__dict__)
+            b._fwd_args = b._bwd_args = None
             for name in ("x", "dy"):
                 setattr(b, name, getattr(self.bufs[0], name).clone())
             for name in ("y", "dx"):

@@ -285,9 +285,25 @@ class Buffers:
         self.workspace = torch.empty(max(bns_workspace_bytes(self.shape, self.spec), 16), dtype=torch.uint8,
                                      device=dev)
         self.n_v = getattr(wl, "n_v", 0) if wl.mode != BNS_VDN else 0
+        self._fwd_args = self._bwd_args = None
         self.save_mean_parts = torch.empty(2 * wl.C, **f32) if self.n_v else None
 
+    def _stream_ptr(self):
+        import torch
+        return C.c_void_p(torch.cuda.current_stream(self.x.device).cuda_stream)
+
     def forward(self):
+        if self.n_v == 0:
+            # same call as bns_forward(...) below, with the argument marshalling done once per buffer set
+            if self._fwd_args is None:
+                ws = self.workspace
+                self._fwd_args = (C.byref(self.shape), C.byref(self.spec), C.c_uint64(self.seed), _ptr(self.x),
+                                  _ptr(self.gamma), _ptr(self.beta), C.c_float(self.wl.eps),
+                                  C.c_float(self.wl.momentum), _ptr(self.y), _ptr(self.save_mean),
+                                  _ptr(self.save_invstd), _ptr(self.running_mean), _ptr(self.running_var), _ptr(ws),
+                                  C.c_size_t(ws.numel() * ws.element_size()))
+            _check(_lib.bns_forward(*self._fwd_args, self._stream_ptr()), "bns_forward")
+            return
         if self.n_v:
             bns_forward_mixed(self.shape, self.spec, self.seed, self.n_v, self.wl.mix_beta, self.x, self.gamma,
                               self.beta, self.wl.eps, self.wl.momentum, self.y, self.save_mean, self.save_invstd,
@@ -297,6 +313,15 @@ class Buffers:
                     self.y, self.save_mean, self.save_invstd, self.running_mean, self.running_var, self.workspace)
 
     def backward(self):
+        if self.n_v == 0:
+            if self._bwd_args is None:
+                ws = self.workspace
+                self._bwd_args = (C.byref(self.shape), C.byref(self.spec), C.c_uint64(self.seed), _ptr(self.x),
+                                  _ptr(self.dy), _ptr(self.gamma), _ptr(self.save_mean), _ptr(self.save_invstd),
+                                  _ptr(self.dx), _ptr(self.dgamma), _ptr(self.dbeta), _ptr(ws),
+                                  C.c_size_t(ws.numel() * ws.element_size()))
+            _check(_lib.bns_backward(*self._bwd_args, self._stream_ptr()), "bns_backward")
+            return
         if self.n_v:
             bns_backward_mixed(self.shape, self.spec, self.seed, self.n_v, self.wl.mix_beta, self.x, self.dy,
                                self.gamma, self.save_mean, self.save_invstd, self.save_mean_parts, self.dx,

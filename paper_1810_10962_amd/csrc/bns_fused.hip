@@ -589,6 +589,14 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     // a read-only and a write-only phase in step and lose more bandwidth than the saved bytes buy.
     if (best_key >= 200000 && g_tuning.path != 2) return hipErrorNotSupported;
 
+    // The exchange stamps are drawn on the host, so a captured launch would replay the same stamps
+    // and a team could pick up its previous replay's sums.  Single-member teams exchange nothing.
+    if (bestT > 1) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(st, &cap) != hipSuccess) return hipErrorNotSupported;
+        if (cap != hipStreamCaptureStatusNone) return hipErrorNotSupported;
+    }
+
     FusedArgs A;
     A.x = io.x;
     A.dy = io.dy;

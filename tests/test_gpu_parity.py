@@ -387,6 +387,46 @@ def test_inference_mode(shape, dtype, kernel_path):
     assert scaled_err(got, ref) <= (1e-5 if dtype == "f32" else 1e-2)
 
 
+@pytest.mark.parametrize("name", ["micro_a_fs", "tiny_bs", "cifar_fs"])
+def test_hip_graph_capture_and_replay(name, kernel_path):
+    """The library allocates nothing and never synchronises, so a forward + backward can be captured
+    into a HIP graph.  Every replay is checked against the eager result, with eager work and
+    synchronisation between replays."""
+    wl = workloads.WORKLOADS[name]
+    if name == "cifar_fs":
+        wl = wl.replace(N=16)
+    inp = workloads.make_inputs(wl)
+    eager = bns.run_workload(wl, inp)
+    buf = bns.Buffers(wl, inp)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        buf.forward()                                   # warm-up outside capture (first-use queries)
+        buf.backward()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    buf.running_mean.copy_(torch.from_numpy(inp["running_mean"]))
+    buf.running_var.copy_(torch.from_numpy(inp["running_var"]))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        buf.forward()
+        buf.backward()
+    for replay in range(4):
+        buf.running_mean.copy_(torch.from_numpy(inp["running_mean"]))
+        buf.running_var.copy_(torch.from_numpy(inp["running_var"]))
+        buf.y.fill_(float("nan"))                       # eager work between replays
+        buf.dx.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        got = buf.results()
+        first = got if replay == 0 else first
+        for k in eager:
+            # multi-block teams are not captured (their exchange stamps come from the host), so a captured
+            # call may take other kernels than the eager one and sum in another order
+            np.testing.assert_allclose(got[k], eager[k], rtol=2e-5, atol=2e-5, err_msg=f"replay {replay}: {k}")
+            assert (got[k] == first[k]).all(), f"replay {replay}: {k} differs from the first replay"
+
+
 def test_copy_reference():
     src = torch.arange(0, 1 << 20, dtype=torch.int32, device="cuda:0")
     for n in (4, 1024, 4096 + 4, 1 << 20):
