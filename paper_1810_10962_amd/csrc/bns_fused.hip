@@ -128,7 +128,6 @@ struct FusedArgs {
     int32_t C, W, HW;
     int32_t c0, cg;
     int32_t T, num_teams;
-    uint32_t per;   // vectors per team member
     uint32_t tot;   // vectors per channel: N * HW / V
     uint32_t stamp0;
     float eps, momentum, inv_s;
@@ -251,8 +250,11 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
     if (team >= A.num_teams) return;                       // blocks beyond the last whole team
     const int j = blockIdx.x - team * A.T;
     const uint32_t hwv = A.hwv_div.d;
-    const uint32_t beg = uint32_t(j) * A.per;
-    const uint32_t end = min(beg + A.per, A.tot);
+    // Member j owns the NT-vector chunks j, j + T, j + 2T, ... of the channel (round-robin, so that
+    // every member sees the same mix of sampled and unsampled planes and finishes at the same time).
+    const uint32_t beg = uint32_t(j) * NT;
+    const uint32_t step = uint32_t(A.T) * NT;
+    const uint32_t end = A.tot;
     const size_t nstride = size_t(A.C) * A.HW;
     const T* x = static_cast<const T*>(A.x);
     T* y = static_cast<T*>(A.out);
@@ -270,7 +272,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
         const uint32_t ia = opaque(beg + threadIdx.x);
 #pragma unroll
         for (int k = 0; k < KMAX; ++k) {
-            const uint32_t i = ia + uint32_t(k) * NT;
+            const uint32_t i = ia + uint32_t(k) * step;
             if (i < end) {
                 const uint32_t n = fdiv(i, A.hwv_div);
                 v[k] = RV::ld(xc + n * nstride + size_t(i - n * hwv) * V);
@@ -280,7 +282,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
         const uint32_t ib = opaque(beg + threadIdx.x);
 #pragma unroll
         for (int k = 0; k < KMAX; ++k) {
-            const uint32_t i = ib + uint32_t(k) * NT;
+            const uint32_t i = ib + uint32_t(k) * step;
             if (i < end) {
                 const uint32_t n = fdiv(i, A.hwv_div);
                 if (n >= uint32_t(b.n0) && n < uint32_t(b.n0 + b.n_cnt)) {
@@ -338,7 +340,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
         const uint32_t ic = opaque(beg + threadIdx.x);
 #pragma unroll
         for (int k = 0; k < KMAX; ++k) {
-            const uint32_t i = ic + uint32_t(k) * NT;
+            const uint32_t i = ic + uint32_t(k) * step;
             if (i < end) {
                 const uint32_t n = fdiv(i, A.hwv_div);
                 float f[V];
@@ -365,8 +367,9 @@ __global__ __launch_bounds__(NT) void fused_backward_kernel(FusedArgs A) {
     if (team >= A.num_teams) return;
     const int j = blockIdx.x - team * A.T;
     const uint32_t hwv = A.hwv_div.d;
-    const uint32_t beg = uint32_t(j) * A.per;
-    const uint32_t end = min(beg + A.per, A.tot);
+    const uint32_t beg = uint32_t(j) * NT;                    // chunks j, j + T, ... as in the forward kernel
+    const uint32_t step = uint32_t(A.T) * NT;
+    const uint32_t end = A.tot;
     const size_t nstride = size_t(A.C) * A.HW;
     const T* x = static_cast<const T*>(A.x);
     const T* dy = static_cast<const T*>(A.dy);
@@ -387,21 +390,21 @@ __global__ __launch_bounds__(NT) void fused_backward_kernel(FusedArgs A) {
         const uint32_t ia = opaque(beg + threadIdx.x);
 #pragma unroll
         for (int k = 0; k < KMAX; ++k) {
-            const uint32_t i = ia + uint32_t(k) * NT;
+            const uint32_t i = ia + uint32_t(k) * step;
             if (i < end) {
                 const uint32_t n = fdiv(i, A.hwv_div);
                 g[k] = RV::ld(gc + n * nstride + size_t(i - n * hwv) * V);
             }
         }
         float s1 = 0.f, s2 = 0.f;
-        constexpr int XB = (KMAX >= 50 || V == 8) ? 2 : 4;        // x vectors in flight per thread (register budget)
+        constexpr int XB = (KMAX >= 50 || (V == 8 && KMAX > 16)) ? 2 : 4;        // x vectors in flight per thread (register budget)
         const uint32_t ib = opaque(beg + threadIdx.x);
 #pragma unroll
         for (int k0 = 0; k0 < KMAX; k0 += XB) {
             typename RV::raw_t xv[XB];
 #pragma unroll
             for (int u = 0; u < XB; ++u) {
-                const uint32_t i = ib + uint32_t(k0 + u) * NT;
+                const uint32_t i = ib + uint32_t(k0 + u) * step;
                 if (k0 + u < KMAX && i < end) {
                     const uint32_t n = fdiv(i, A.hwv_div);
                     xv[u] = RV::ld(xc + n * nstride + size_t(i - n * hwv) * V);
@@ -409,7 +412,7 @@ __global__ __launch_bounds__(NT) void fused_backward_kernel(FusedArgs A) {
             }
 #pragma unroll
             for (int u = 0; u < XB; ++u) {
-                const uint32_t i = ib + uint32_t(k0 + u) * NT;
+                const uint32_t i = ib + uint32_t(k0 + u) * step;
                 if (k0 + u < KMAX && i < end) {
                     float fg[V], fx[V];
                     RV::unpack(g[k0 + u < KMAX ? k0 + u : 0], fg);
@@ -438,7 +441,7 @@ __global__ __launch_bounds__(NT) void fused_backward_kernel(FusedArgs A) {
         const uint32_t ic = opaque(beg + threadIdx.x);
 #pragma unroll
         for (int k = 0; k < KMAX; ++k) {
-            const uint32_t i = ic + uint32_t(k) * NT;
+            const uint32_t i = ic + uint32_t(k) * step;
             if (i < end) {
                 const uint32_t n = fdiv(i, A.hwv_div);
                 const uint32_t off = i - n * hwv;
@@ -547,47 +550,82 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     const uint32_t tot = uint32_t(d.N) * hwv;
     const int combo = combo_index(d);
 
-    // Every variant moves the same bytes, so what differs is the number of rounds (each round
-    // ends in a team exchange) and the team size.  Take the fewest rounds; among those the
-    // smallest variant (most threads per compute unit) whose teams stay small, else the
-    // smallest team.  With fewer channels than blocks a team is widened so every block has work.
-    int best = -1, bestT = 0, best_blocks = 0;
-    long best_key = -1;
-    for (int v = 0; v < kNumVariants; ++v) {
-        if (g_tuning.fused_variant > 0 && v != g_tuning.fused_variant - 1) continue;
+    // Choice of variant and team size, from sweeps on MI355X (64x256x56x56 fp32/bf16, 128x64x32x32,
+    // 130x128x28x28):
+    //  * a team of T blocks needs T * nt * kmax >= vectors per channel; T is then widened so that
+    //    every block has work, and nudged (up to 2x) to the T that minimises rounds x vectors per
+    //    thread, i.e. that leaves no half-empty last round;
+    //  * candidate A = fewest rounds, then no exchange (T = 1), then the smallest variant;
+    //  * backward, and forward with S = everything: (512 threads, 16 vectors), two blocks per
+    //    compute unit, beats the bigger variants even when it needs more rounds (two teams per
+    //    unit overlap one team's exchange and stores with the other's loads), so A is capped there;
+    //  * forward with a sampled S saves only r of the bytes; it wins when all channels are in
+    //    flight at once (one round), else the streaming kernels are faster.
+    struct Plan {
+        int v = -1, T = 0, blocks = 0;
+        long rounds = 0;
+    };
+    auto plan_for = [&](int v, Plan* out) -> hipError_t {
         const Variant& va = kVariants[v];
         int& bpc = di.blocks_per_cu[backward ? 1 : 0][combo][v];
         if (bpc == 0) {
             int nb = 0;
-            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel_for(d, backward, v), va.nt, 0);
-            if (e != hipSuccess) return e;
+            const hipError_t oe = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel_for(d, backward, v), va.nt, 0);
+            if (oe != hipSuccess) return oe;
             bpc = nb > 0 ? nb : -1;
         }
-        if (bpc < 0) continue;
-        const int blocks = di.cus * bpc;
-        const uint32_t cap = uint32_t(va.nt) * uint32_t(va.kmax);           // vectors one block can hold
-        long T = long((tot + cap - 1) / cap);                               // members needed for one channel
-        if (T > blocks || T > kMaxTeam) continue;
-        if (long(cg) * T < blocks) {
-            long Tw = blocks / cg;
-            if (Tw > kMaxTeam) Tw = kMaxTeam;
-            if (Tw > T) T = Tw;
+        out->v = -1;
+        if (bpc < 0) return hipSuccess;
+        const long blocks = long(di.cus) * bpc;
+        const long chunks = long((tot + va.nt - 1) / va.nt);                // nt-vector chunks per channel
+        const long Tmin = (chunks + va.kmax - 1) / va.kmax;                 // members needed for one channel
+        if (Tmin > blocks || Tmin > kMaxTeam) return hipSuccess;
+        long bestT = 0, best_cost = 0, best_rounds = 0;
+        const long Thi = (long(cg) * Tmin < blocks) ? blocks / cg : 2 * Tmin;
+        for (long T = Tmin; T <= Thi && T <= kMaxTeam && T <= blocks; ++T) {
+            const long teams = blocks / T < cg ? blocks / T : cg;
+            const long rounds = (cg + teams - 1) / teams;
+            const long cost = rounds * ((chunks + T - 1) / T + 2);          // +2: exchange and ramp per round
+            if (bestT == 0 || cost < best_cost) {
+                bestT = T;
+                best_cost = cost;
+                best_rounds = rounds;
+            }
         }
-        const long teams = blocks / T < cg ? blocks / T : cg;
-        const long rounds = (cg + teams - 1) / teams;
-        const long key = rounds * 100000 + (T == 1 ? 0 : T <= 64 ? 1 : T) * 8 + v;   // smaller is better
-        if (best < 0 || key < best_key) {
-            best = v;
-            bestT = int(T);
-            best_blocks = blocks;
-            best_key = key;
+        out->v = v;
+        out->T = int(bestT);
+        out->blocks = int(blocks);
+        out->rounds = best_rounds;
+        return hipSuccess;
+    };
+    Plan chosen;
+    if (g_tuning.fused_variant > 0) {
+        if ((e = plan_for(g_tuning.fused_variant - 1, &chosen)) != hipSuccess) return e;
+    } else {
+        long best_key = -1;
+        for (int v = 0; v < kNumVariants; ++v) {
+            Plan p;
+            if ((e = plan_for(v, &p)) != hipSuccess) return e;
+            if (p.v < 0) continue;
+            const long key = p.rounds * 100000 + (p.T == 1 ? 0 : p.T <= 64 ? 1 : p.T) * 8 + v;
+            if (chosen.v < 0 || key < best_key) {
+                chosen = p;
+                best_key = key;
+            }
         }
+        const bns_box& sb = ip.shared;
+        const bool everything = !ip.per_channel && sb.n_cnt == d.N && sb.h_cnt == d.H && sb.w_cnt == d.W;
+        constexpr int kTwoPerUnit = 4;                                       // {512, 16}
+        if (chosen.v > kTwoPerUnit && (backward || everything)) {
+            Plan p;
+            if ((e = plan_for(kTwoPerUnit, &p)) != hipSuccess) return e;
+            if (p.v >= 0) chosen = p;
+        }
+        if (chosen.v >= 0 && !backward && !everything && chosen.rounds > 1 && g_tuning.path != 2)
+            return hipErrorNotSupported;
     }
-    if (best < 0) return hipErrorNotSupported;
-    // Measured on MI355X: with every channel in flight at once (one round) the fused kernels beat
-    // the streaming kernels at every size tried; with several rounds all teams alternate between
-    // a read-only and a write-only phase in step and lose more bandwidth than the saved bytes buy.
-    if (best_key >= 200000 && g_tuning.path != 2) return hipErrorNotSupported;
+    if (chosen.v < 0) return hipErrorNotSupported;
+    const int best = chosen.v, bestT = chosen.T, best_blocks = chosen.blocks;
 
     // The exchange stamps are drawn on the host, so a captured launch would replay the same stamps
     // and a team could pick up its previous replay's sums.  Single-member teams exchange nothing.
@@ -621,7 +659,6 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     A.T = bestT;
     A.num_teams = best_blocks / bestT;
     if (A.num_teams > cg) A.num_teams = cg;
-    A.per = (tot + uint32_t(bestT) - 1) / uint32_t(bestT);
     A.tot = tot;
     const uint32_t rounds = uint32_t((cg + A.num_teams - 1) / A.num_teams);
     A.stamp0 = g_stamp.fetch_add(rounds + 1);
@@ -633,7 +670,10 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
 
     const int grid = A.num_teams * bestT;
     if (size_t(grid) * 2 * 2 * sizeof(unsigned long long) > slot_bytes) return hipErrorNotSupported;
-    if (uint64_t(A.per) > uint64_t(kVariants[best].nt) * kVariants[best].kmax) return hipErrorNotSupported;
+    {
+        const uint64_t chunks = (uint64_t(tot) + kVariants[best].nt - 1) / kVariants[best].nt;
+        if ((chunks + bestT - 1) / bestT > uint64_t(kVariants[best].kmax)) return hipErrorNotSupported;
+    }
     void* params[] = {&A};
     if (g_tuning.fused_coop)
         return hipLaunchCooperativeKernel(kernel_for(d, backward, best), dim3(grid), dim3(kVariants[best].nt), params,
