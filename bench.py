@@ -33,9 +33,11 @@ METRIC = "BN fwd+bwd effective HBM GB/s (% peak) and speedup vs full BN, 64x256x
 # scaled by what the same counters read for bns_copy_reference of known size; bytes per launch.
 # Filled from profiles/ (see there for the commands); None where no counter run exists.
 MEASURED_TRAFFIC = {
-    ("imagenet_bs", "dx"): 436892054,           # profiles/imagenet_bs_f32_hbm_traffic.md
-    ("imagenet_bs", "normalize"): 411166831,
-    ("imagenet_bs", "reduce"): 411101108,
+    # profiles/imagenet_bs_f32_hbm_traffic.md
+    ("imagenet_bs", "bwd"): 642780850,          # fused_backward_kernel
+    ("imagenet_bs", "normalize"): 411176456,
+    ("imagenet_bs", "dx"): 436934656,
+    ("imagenet_bs", "reduce"): 411114496,
 }
 
 
@@ -124,6 +126,26 @@ def time_stages(ds, steps, torch, bns):
     return out
 
 
+def time_directions(ds, steps, torch, bns):
+    """Average duration of bns_forward and of bns_backward as the library runs them by default
+    (event pairs on the launch stream), and which kernels each took."""
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    for s in range(steps):
+        b = ds.next()
+        e = evs[s]
+        e[0].record()
+        b.forward()
+        e[1].record()
+        b.backward()
+        e[2].record()
+    torch.cuda.synchronize()
+    paths = {1: "streaming", 2: "fused"}
+    return dict(forward=float(np.mean([e[0].elapsed_time(e[1]) for e in evs])) * 1e-3,
+                backward=float(np.mean([e[1].elapsed_time(e[2]) for e in evs])) * 1e-3,
+                forward_path=paths.get(bns.bns_get_option("last_path_forward"), "?"),
+                backward_path=paths.get(bns.bns_get_option("last_path_backward"), "?"))
+
+
 def time_copy(ds, steps, torch, bns):
     for _ in range(3):
         b = ds.next()
@@ -207,18 +229,30 @@ def main():
     alg = algorithmic_bytes(wl, r)
 
     sec = time_steps(ds, K, W, torch)
-    stages = time_stages(ds, K, torch, bns)
+    dirs = time_directions(ds, K, torch, bns)
+    stages = time_stages(ds, K, torch, bns)          # the streaming kernels one by one, for reference
     copy_s = time_copy(ds, min(K, 50), torch, bns)
 
-    # dominant kernel = the longest single-kernel stage (statistics and reduce stages also
-    # contain a one-block finalize kernel, so their event pair covers two launches)
-    dom = max(("normalize", "dx", "reduce"), key=lambda k: stages[k])
-    kernel_name = {"normalize": "normalize_kernel", "dx": "dx_kernel", "reduce": "reduce_partial_kernel"}[dom]
-    achieved = alg[dom] / stages[dom] / 1e9
+    # Dominant kernel of the default path.  A fused direction is ONE kernel covering two rows of the
+    # byte model (reduction + element-wise pass); a streaming direction is several kernels, of which
+    # the longest single-kernel stage is taken (the statistics and reduce stages also contain a
+    # one-block finalize kernel, so their event pair covers two launches).
+    cands = []
+    if dirs["backward_path"] == "fused":
+        cands.append(("fused_backward_kernel", dirs["backward"], alg["reduce"] + alg["dx"], "bwd"))
+    else:
+        cands += [("reduce_partial_kernel", stages["reduce"], alg["reduce"], "reduce"),
+                  ("dx_kernel", stages["dx"], alg["dx"], "dx")]
+    if dirs["forward_path"] == "fused":
+        cands.append(("fused_forward_kernel", dirs["forward"], alg["stats"] + alg["normalize"], "fwd"))
+    else:
+        cands.append(("normalize_kernel", stages["normalize"], alg["normalize"], "normalize"))
+    kernel_name, dom_s, dom_bytes, dom_key = max(cands, key=lambda c: c[1])
+    achieved = dom_bytes / dom_s / 1e9
     roofline = dict(bound="hbm", kernel=kernel_name, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=MEASURED_TRAFFIC.get((wl.name, dom)),
-                    algorithmic_bytes_per_launch=int(alg[dom]), avg_launch_us=round(stages[dom] * 1e6, 2),
-                    timing="HIP events on the launch stream around the stage, mean over the timed steps")
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=MEASURED_TRAFFIC.get((wl.name, dom_key)),
+                    algorithmic_bytes_per_launch=int(dom_bytes), avg_launch_us=round(dom_s * 1e6, 2),
+                    timing="HIP events on the launch stream around the call, mean over the timed steps")
 
     out = {
         "metric": METRIC, "value": round(alg["fwd+bwd"] / sec / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": K,
@@ -231,8 +265,10 @@ def main():
         "pct_of_hbm_peak": round(100 * alg["fwd+bwd"] / sec / 1e9 / HBM_PEAK_GBS, 2),
         "elements_per_s": round(wl.elements / sec, 1),
         "algorithmic_bytes_per_step": int(alg["fwd+bwd"]),
-        "stages_us": {k: round(v * 1e6, 2) for k, v in stages.items()},
-        "stages_GBs": {k: round(alg[k] / stages[k] / 1e9, 1) for k in stages},
+        "default_path": {"forward": dirs["forward_path"], "backward": dirs["backward_path"],
+                         "forward_us": round(dirs["forward"] * 1e6, 2), "backward_us": round(dirs["backward"] * 1e6, 2)},
+        "streaming_stages_us": {k: round(v * 1e6, 2) for k, v in stages.items()},
+        "streaming_stages_GBs": {k: round(alg[k] / stages[k] / 1e9, 1) for k in stages},
         "copy_reference": {"us": round(copy_s * 1e6, 2), "GBs": round(2 * tensor_bytes / copy_s / 1e9, 1)},
         "roofline": roofline,
     }

@@ -210,15 +210,29 @@ bns_status bns_inference(const bns_shape* shape, const void* x, const float* gam
  * and the known-size kernel that hardware traffic counters are calibrated against. */
 bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* stream);
 
-/* Process-wide tuning overrides for benchmarking; value 0 restores the automatic choice.
- *   "splits_stats"   blocks per channel in the statistics reduction      (1..64)
- *   "splits_reduce"  blocks per channel in the backward reduction        (1..64)
- *   "channel_group"  bns_forward / bns_backward walk the channels in groups of this many,
- *                    running every stage on one group before the next, so that a group's
- *                    second read of dy / x can be served from the last-level cache   (1..C)
- * Returns BNS_EINVAL for an unknown name or a value out of range.  name: HOST string. */
+/* Process-wide overrides of launch choices, for benchmarking and tests; value 0 restores the
+ * automatic choice.  name: HOST string.  Returns BNS_EINVAL for an unknown name or a value out of range.
+ *   "path"           1: only the streaming kernels (statistics / normalise / reduce / dx, several
+ *                    launches per direction); 2: only the fused single-launch kernels, which keep a
+ *                    channel in registers between its reduction and its element-wise pass
+ *                    (BNS_EUNSUPPORTED if a channel does not fit); 0: whichever is faster for the shape
+ *   "fused_variant"  1..7: block size / registers-per-thread variant of the fused kernels
+ *   "fused_coop"     1: launch the fused kernels with hipLaunchCooperativeKernel
+ *   "splits_stats"   blocks per channel in the statistics reduction              (1..64)
+ *   "splits_reduce"  blocks per channel in the backward reduction                (1..64)
+ *   "channel_group"  the streaming path walks the channels in groups of this many, every stage on
+ *                    one group before the next                                   (1..C)
+ *   "norm_unroll", "dx_unroll", "reduce_unroll"   128-bit accesses per thread    (1, 2, 4)
+ *   "norm_nt", "dx_nt", "reduce_nt"   non-temporal access mask + 1: bit 0 loads, bit 1 stores
+ * Notes on the fused kernels: blocks of a team exchange partial sums through the workspace and wait
+ * for each other with a bounded spin (the grid never exceeds what the device holds at once); they
+ * are bit-reproducible like the streaming kernels; teams of more than one block are not used while
+ * the stream is being captured into a graph (the streaming kernels are captured instead). */
 bns_status bns_set_option(const char* name, int32_t value);
-int32_t bns_get_option(const char* name); /* -1 for an unknown name */
+/* Current value of an option (as set, 0 = automatic); also "last_path_forward" / "last_path_backward":
+ * 1 if the last bns_forward / bns_backward took the streaming kernels, 2 if the fused one.
+ * -1 for an unknown name. */
+int32_t bns_get_option(const char* name);
 
 #ifdef __cplusplus
 }

@@ -16,6 +16,8 @@ namespace {
 std::atomic<int32_t> g_splits_stats{0};
 std::atomic<int32_t> g_splits_reduce{0};
 std::atomic<int32_t> g_channel_group{0};
+std::atomic<int32_t> g_last_path_forward{0};    // what the last bns_forward / bns_backward launched:
+std::atomic<int32_t> g_last_path_backward{0};   // 1 = streaming kernels, 2 = fused single-launch kernel
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -224,10 +226,14 @@ bns_status bns_forward(const bns_shape* shape, const bns_spec* spec, uint64_t se
         io.running_var = running_var;
         const hipError_t fe = launch_fused(d, ip, false, io, eps, momentum,
                                            static_cast<char*>(workspace) + 2 * partial_bytes(d), kSlotBytes, 0, d.C, st);
-        if (fe == hipSuccess) return BNS_OK;
+        if (fe == hipSuccess) {
+            g_last_path_forward.store(2);
+            return BNS_OK;
+        }
         if (fe != hipErrorNotSupported) return BNS_EDEVICE;
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
     }
+    g_last_path_forward.store(1);
     const int G = channel_group(d);
     for (int c0 = 0; c0 < d.C; c0 += G) {
         const int cg = (d.C - c0 < G) ? d.C - c0 : G;
@@ -296,10 +302,14 @@ bns_status bns_backward(const bns_shape* shape, const bns_spec* spec, uint64_t s
         io.dbeta = dbeta;
         const hipError_t fe = launch_fused(d, ip, true, io, 0.f, 0.f, static_cast<char*>(workspace) + 2 * partial_bytes(d),
                                            kSlotBytes, 0, d.C, st);
-        if (fe == hipSuccess) return BNS_OK;
+        if (fe == hipSuccess) {
+            g_last_path_backward.store(2);
+            return BNS_OK;
+        }
         if (fe != hipErrorNotSupported) return BNS_EDEVICE;
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
     }
+    g_last_path_backward.store(1);
     const int G = channel_group(d);
     for (int c0 = 0; c0 < d.C; c0 += G) {
         const int cg = (d.C - c0 < G) ? d.C - c0 : G;
@@ -414,19 +424,18 @@ bns_status bns_set_option(const char* name, int32_t value) {
         const char* n;
         int* p;
         int hi, bias;
+        bool pow2;      // unroll factors: 1, 2 or 4
     } tun[] = {
-        {"norm_unroll", &g_tuning.norm_unroll, 4, 0},     {"norm_nt", &g_tuning.norm_nt, 4, 1},
-        {"dx_unroll", &g_tuning.dx_unroll, 4, 0},         {"dx_nt", &g_tuning.dx_nt, 4, 1},
-        {"reduce_unroll", &g_tuning.reduce_unroll, 4, 0}, {"reduce_nt", &g_tuning.reduce_nt, 2, 1},
-        {"reduce_split_major", &g_tuning.reduce_split_major, 1, 0},
-        {"reduce_align", &g_tuning.reduce_align, 1, 0},
-        {"path", &g_tuning.path, 2, 0},
-        {"fused_variant", &g_tuning.fused_variant, 7, 0},
-        {"fused_coop", &g_tuning.fused_coop, 1, 0},
+        {"norm_unroll", &g_tuning.norm_unroll, 4, 0, true},     {"norm_nt", &g_tuning.norm_nt, 4, 1, false},
+        {"dx_unroll", &g_tuning.dx_unroll, 4, 0, true},         {"dx_nt", &g_tuning.dx_nt, 4, 1, false},
+        {"reduce_unroll", &g_tuning.reduce_unroll, 4, 0, true}, {"reduce_nt", &g_tuning.reduce_nt, 2, 1, false},
+        {"path", &g_tuning.path, 2, 0, false},
+        {"fused_variant", &g_tuning.fused_variant, 7, 0, false},
+        {"fused_coop", &g_tuning.fused_coop, 1, 0, false},
     };
     for (auto& t : tun)
         if (!strcmp(name, t.n)) {
-            if (value > t.hi || (value == 3 && t.hi == 4 && t.bias == 0 && t.n[0] != 'f')) return BNS_EINVAL;
+            if (value > t.hi || (t.pow2 && value == 3)) return BNS_EINVAL;
             *t.p = value - t.bias;
             return BNS_OK;
         }
@@ -438,6 +447,9 @@ int32_t bns_get_option(const char* name) {
     if (!strcmp(name, "splits_stats")) return g_splits_stats.load();
     if (!strcmp(name, "splits_reduce")) return g_splits_reduce.load();
     if (!strcmp(name, "channel_group")) return g_channel_group.load();
+    if (!strcmp(name, "last_path_forward")) return g_last_path_forward.load();
+    if (!strcmp(name, "last_path_backward")) return g_last_path_backward.load();
+    if (!strcmp(name, "path")) return g_tuning.path;
     return -1;
 }
 

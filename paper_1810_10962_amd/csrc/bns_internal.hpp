@@ -27,8 +27,6 @@ struct Tuning {
     int norm_unroll = 0, norm_nt = -1;      // accesses per thread; bit 0: non-temporal loads, bit 1: stores
     int dx_unroll = 0, dx_nt = -1;
     int reduce_unroll = 0, reduce_nt = -1;
-    int reduce_split_major = 0;             // block order of the backward reduction
-    int reduce_align = 0;                   // round a block's range up to whole planes
     int path = 0;                           // 0: fused kernels when a channel fits on chip, else streaming;
                                             // 1: streaming kernels only; 2: fused only (error if it cannot)
     int fused_variant = 0;                  // 1..7 forces a (block size, registers) variant of the fused kernels

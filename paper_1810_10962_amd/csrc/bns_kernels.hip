@@ -271,17 +271,11 @@ __global__ __launch_bounds__(kBlock) void normalize_kernel(
 template <typename T, int V, int U, int NT>
 __global__ __launch_bounds__(kBlock) void reduce_partial_kernel(
     const T* __restrict__ x, const T* __restrict__ dy, const float* __restrict__ mean,
-    Partial* __restrict__ partial, int C, int HW, FastDiv hwv_div, int c0, int cg, int splits, uint32_t per_block,
-    uint32_t tot, int split_major) {
+    Partial* __restrict__ partial, int C, int HW, FastDiv hwv_div, int c0, int splits, uint32_t per_block,
+    uint32_t tot) {
     __shared__ float lds[2 * (kBlock / kWave)];
-    int cl, k;
-    if (split_major) {            // consecutive blocks: consecutive channels of the same sample range
-        k = blockIdx.x / cg;
-        cl = blockIdx.x - k * cg;
-    } else {                      // consecutive blocks: consecutive ranges of the same channel
-        cl = blockIdx.x / splits;
-        k = blockIdx.x - cl * splits;
-    }
+    const int cl = blockIdx.x / splits;       // consecutive blocks: consecutive ranges of the same channel
+    const int k = blockIdx.x - cl * splits;
     const int c = c0 + cl;
     const uint32_t hwv = hwv_div.d;
     const uint32_t j0 = uint32_t(k) * per_block;
@@ -611,12 +605,11 @@ hipError_t launch_reduce_partial(const Dims& d, const void* x, const void* dy, c
             constexpr int NT = decltype(nt)::value;
             const uint32_t hwv = uint32_t(d.HW / V);
             const uint32_t tot = uint32_t(d.N) * hwv;
-            uint32_t per_block = ceil_div(tot, uint32_t(splits));
-            if (g_tuning.reduce_align && per_block > hwv) per_block = ceil_div(per_block, hwv) * hwv;   // whole planes
+            const uint32_t per_block = ceil_div(tot, uint32_t(splits));
             const dim3 grid(uint32_t(cg) * uint32_t(splits));
             hipLaunchKernelGGL((reduce_partial_kernel<T, V, U, NT>), grid, dim3(kBlock), 0, st,
                                static_cast<const T*>(x), static_cast<const T*>(dy), mean, partial, d.C, d.HW,
-                               make_fastdiv(hwv), c0, cg, splits, per_block, tot, g_tuning.reduce_split_major);
+                               make_fastdiv(hwv), c0, splits, per_block, tot);
             return hipGetLastError();
         });
     });
