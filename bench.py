@@ -207,7 +207,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (sampled BN keeps its statistics local to a GPU; "
-              "see DESIGN.md, 'More than one GPU'); run with --gpus 1", file=sys.stderr)
+              "no exchange between GPUs is part of the method); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch

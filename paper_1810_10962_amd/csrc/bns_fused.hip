@@ -159,12 +159,24 @@ __device__ __forceinline__ void block_allsum2(float& a, float& b, float* red) {
     }
 }
 
-// All-gather of one (a, b) pair per team member, summed in member order in fp64.
-// Returns the team totals to every thread of the block.
+// All-gather of one (a, b) pair per team member, summed in member order in fp64, in two steps so
+// that a kernel can put independent work (prefetching the next channel) between them.
+// team_publish: thread 0 writes this member's stamped pair.
+__device__ __forceinline__ void team_publish(const FusedArgs& A, int team_first_block, int j, uint32_t it, float a,
+                                             float b) {
+    if (A.T == 1 || threadIdx.x != 0) return;
+    const uint32_t stamp = A.stamp0 + it;
+    unsigned long long* mine = A.slots + (size_t(it & 1u) * gridDim.x + size_t(team_first_block + j)) * 2;
+    __hip_atomic_store(mine, (static_cast<unsigned long long>(stamp) << 32) | __float_as_uint(a), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(mine + 1, (static_cast<unsigned long long>(stamp) << 32) | __float_as_uint(b), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// team_collect: waits for every member's pair and returns the team totals to every thread.
 template <int NT>
-__device__ __forceinline__ void team_allsum2(const FusedArgs& A, int team_first_block, int j, uint32_t it,
-                                             float a, float b, double& ta, double& tb, float* team_lds,
-                                             double* bc) {
+__device__ __forceinline__ void team_collect(const FusedArgs& A, int team_first_block, uint32_t it, float a, float b,
+                                             double& ta, double& tb, float* team_lds, double* bc) {
     if (A.T == 1) {
         ta = double(a);
         tb = double(b);
@@ -172,13 +184,6 @@ __device__ __forceinline__ void team_allsum2(const FusedArgs& A, int team_first_
     }
     const uint32_t stamp = A.stamp0 + it;
     unsigned long long* base = A.slots + size_t(it & 1u) * gridDim.x * 2;
-    if (threadIdx.x == 0) {
-        unsigned long long* mine = base + size_t(team_first_block + j) * 2;
-        __hip_atomic_store(mine, (static_cast<unsigned long long>(stamp) << 32) | __float_as_uint(a),
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(mine + 1, (static_cast<unsigned long long>(stamp) << 32) | __float_as_uint(b),
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
     for (int t = threadIdx.x; t < A.T; t += NT) {
         unsigned long long* theirs = base + size_t(team_first_block + t) * 2;
         float pa = __builtin_nanf(""), pb = __builtin_nanf("");
@@ -208,6 +213,14 @@ __device__ __forceinline__ void team_allsum2(const FusedArgs& A, int team_first_
     __syncthreads();
     ta = bc[0];
     tb = bc[1];
+}
+
+template <int NT>
+__device__ __forceinline__ void team_allsum2(const FusedArgs& A, int team_first_block, int j, uint32_t it,
+                                             float a, float b, double& ta, double& tb, float* team_lds,
+                                             double* bc) {
+    team_publish(A, team_first_block, j, it, a, b);
+    team_collect<NT>(A, team_first_block, it, a, b, ta, tb, team_lds, bc);
 }
 
 // Returns v unchanged but opaque to the optimiser.  Each phase of a fused kernel derives its
@@ -567,6 +580,7 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     };
     auto plan_for = [&](int v, Plan* out) -> hipError_t {
         const Variant& va = kVariants[v];
+        out->v = -1;
         int& bpc = di.blocks_per_cu[backward ? 1 : 0][combo][v];
         if (bpc == 0) {
             int nb = 0;

@@ -264,6 +264,8 @@ def test_channel_groups_and_split_overrides_give_the_same_answer():
     (4, (32, 40, 56, 56), dict(mode=BS, n_s=4)),
     (5, (32, 40, 56, 56), dict(mode=FULL)),
     (7, (64, 24, 56, 56), dict(mode=FS, patch_h=14, patch_w=14)),      # 50 vectors per thread
+    (5, (32, 300, 28, 28), dict(mode=BS, n_s=4)),                      # several rounds, two blocks per unit
+    (4, (5, 700, 7, 7), dict(mode=BS, n_s=2)),                         # scalar path, many channels
 ])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_fused_kernels_every_variant(variant, shape, mkw, dtype, kernel_path):
