@@ -54,17 +54,27 @@ def oracle_reference(wl, inp, channels=None):
 def scaled_err(got, ref, floor=0.0):
     """max_i |got_i - ref_i| / (|ref_i| + max(RMS(ref), floor)).
 
-    A purely element-wise relative error is undefined where y, dx or dbeta cross zero; adding the
-    tensor's RMS to the denominator keeps it a relative measure at the tensor's own scale.
-    ``floor`` is the RMS of the terms the output is a difference of, for outputs that cancel."""
+    A purely element-wise relative error is undefined where y, dx or dbeta cross zero; adding an RMS
+    to the denominator keeps it a relative measure at the output's own scale.  Every channel is a
+    normalisation problem of its own, with its own scale gamma_c / sigma_c, so for the N x C x H x W
+    outputs the RMS is taken per channel; per-channel vectors use the RMS over channels.
+    ``floor`` (scalar or per channel) is the RMS of the terms the output is a difference of, for
+    outputs that cancel."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
-    rms = max(np.sqrt(np.mean(ref ** 2)), floor)
+    if ref.ndim == 4:
+        rms = np.sqrt(np.mean(ref ** 2, axis=(0, 2, 3), keepdims=True))
+        floor = np.asarray(floor, dtype=np.float64)
+        if floor.ndim == 1:
+            floor = floor[None, :, None, None]
+        rms = np.maximum(rms, floor)
+    else:
+        rms = max(np.sqrt(np.mean(ref ** 2)), float(np.max(floor)))
     return float(np.max(np.abs(got - ref) / (np.abs(ref) + rms + 1e-300)))
 
 
 def direct_term_rms(inp, ref, channels=None):
-    """RMS of gamma * invstd * dy, the first term of both branches of Eq. 6.
+    """Per-channel RMS of gamma * invstd * dy, the first term of both branches of Eq. 6.
 
     dx is that term minus the 1/s corrections.  For s of a few points the two nearly cancel
     (with s = m = 2 exactly, up to eps), and fp32 rounding of the terms then dominates the
@@ -72,7 +82,7 @@ def direct_term_rms(inp, ref, channels=None):
     benchmark shapes (s in the thousands) the two are equal to within 1/s."""
     ch = slice(None) if channels is None else np.asarray(channels)
     a = (np.asarray(inp["gamma"], dtype=np.float64)[ch] * ref["save_invstd"])[None, :, None, None]
-    return float(np.sqrt(np.mean((a * inp["dy"][:, ch].astype(np.float64)) ** 2)))
+    return np.sqrt(np.mean((a * inp["dy"][:, ch].astype(np.float64)) ** 2, axis=(0, 2, 3)))
 
 
 def assert_parity(res, ref, wl, channels=None, what="", inp=None):

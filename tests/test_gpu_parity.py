@@ -124,6 +124,23 @@ def test_extreme_offsets_are_exercised():
     assert len(seen_fs) >= 2
 
 
+@pytest.mark.parametrize("shape,mkw", [
+    ((65535, 2, 1, 1), dict(mode=BS, n_s=4096)),            # the largest N: fully-connected style, m = 65535
+    ((65535, 1, 1, 3), dict(mode=FS, patch_h=1, patch_w=2)),
+    ((2, 70000, 2, 2), dict(mode=BS, n_s=1)),               # many channels, tiny planes
+    ((3, 40000, 1, 1), dict(mode=FULL)),
+    ((1, 2, 1024, 1024), dict(mode=FS, patch_h=256, patch_w=128)),   # one very large plane per channel
+    ((2, 1, 1500, 1400), dict(mode=BS, n_s=1)),             # a single channel: every block works on it
+    ((5, 3, 333, 17), dict(mode=FS, patch_h=100, patch_w=5, fs_per_channel=1)),   # odd plane size, scalar path
+], ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else None)
+def test_extents_at_the_edges_of_the_supported_range(shape, mkw):
+    N, C_, H, W = shape
+    wl = Workload(name="edge", N=N, C=C_, H=H, W=W, data_seed=77, sampling_seed=5, layer_id=9, epoch=1, **mkw)
+    inp, res = _run(wl)
+    assert (res["boxes"] == oracle_boxes(wl)).all()
+    assert_parity(res, oracle_reference(wl, inp), wl, what=f"edge {shape}", inp=inp)
+
+
 def test_degenerate_subsets():
     """One sampled point per channel (Var = 0, inv-std = 1/sqrt(eps)); constant input; ratio 1 via BS and FS."""
     wl = Workload(name="one_point", N=4, C=5, H=6, W=6, mode=FS, patch_h=1, patch_w=1, sampling_seed=3)
