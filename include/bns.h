@@ -218,7 +218,10 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  *                    (BNS_EUNSUPPORTED if a channel does not fit); 0: whichever is faster for the shape
  *   "fused_variant"  1..7: block size / registers-per-thread variant of the fused kernels
  *   "fused_coop"     1: launch the fused kernels with hipLaunchCooperativeKernel
- *   "splits_stats"   blocks per channel in the statistics reduction              (1..64)
+ *   "split_statistics"  1: the streaming forward statistics always run as partial sums + finalize
+ *                    (by default one 1024-thread block per channel does both when a channel has few
+ *                    sampled points)
+ *   "splits_stats"   blocks per channel in the statistics reduction (implies split_statistics) (1..64)
  *   "splits_reduce"  blocks per channel in the backward reduction                (1..64)
  *   "channel_group"  the streaming path walks the channels in groups of this many, every stage on
  *                    one group before the next                                   (1..C)

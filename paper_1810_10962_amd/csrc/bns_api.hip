@@ -101,6 +101,10 @@ int channel_group(const Dims& d) {
 bns_status stats_range(const Dims& d, const IndexParams& ip, const void* x, float eps, float momentum,
                        float* save_mean, float* save_invstd, float* rm, float* rv, Partial* ws, int c0, int cg,
                        hipStream_t st) {
+    if (!g_tuning.split_statistics && g_splits_stats.load() == 0) {
+        hipError_t e = hipSuccess;
+        if (launch_stats_one_block(d, ip, x, c0, cg, eps, momentum, save_mean, save_invstd, rm, rv, st, &e)) return dev(e);
+    }
     const int splits = stats_splits(d, ip, cg);
     if (launch_stats_partial(d, ip, x, ws, splits, c0, cg, st) != hipSuccess) return BNS_EDEVICE;
     return dev(launch_stats_finalize(d, ip, x, ws, splits, c0, cg, eps, momentum, save_mean, save_invstd, rm, rv, st));
@@ -432,6 +436,7 @@ bns_status bns_set_option(const char* name, int32_t value) {
         {"path", &g_tuning.path, 2, 0, false},
         {"fused_variant", &g_tuning.fused_variant, 7, 0, false},
         {"fused_coop", &g_tuning.fused_coop, 1, 0, false},
+        {"split_statistics", &g_tuning.split_statistics, 1, 0, false},
     };
     for (auto& t : tun)
         if (!strcmp(name, t.n)) {

@@ -172,12 +172,14 @@ __device__ __forceinline__ double wave_sum(double v) {
     return v;
 }
 
-// Sum of two values over the block; result valid in thread 0.  `lds` holds 2 * (kBlock / kWave) floats.
+// Sum of two values over a block of NT threads; result valid in thread 0.  `lds` holds
+// 2 * (NT / kWave) floats.
+template <int NT = kBlock>
 __device__ __forceinline__ void block_sum2(float& a, float& b, float* lds) {
     a = wave_sum(a);
     b = wave_sum(b);
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    constexpr int nw = kBlock / kWave;
+    constexpr int nw = NT / kWave;
     if (lane == 0) {
         lds[wave] = a;
         lds[nw + wave] = b;

@@ -31,6 +31,7 @@ struct Tuning {
                                             // 1: streaming kernels only; 2: fused only (error if it cannot)
     int fused_variant = 0;                  // 1..7 forces a (block size, registers) variant of the fused kernels
     int fused_coop = 0;                     // 1: launch the fused kernels with hipLaunchCooperativeKernel
+    int split_statistics = 0;               // 1: forward statistics always as partial sums + finalize
 };
 extern Tuning g_tuning;
 inline int tuned(int v, int dflt) { return v > 0 ? v : dflt; }
@@ -44,6 +45,11 @@ struct Partial {
 // Forward statistics (Eq. 3): partial sums of (x - pivot) and (x - pivot)^2 over S.
 hipError_t launch_stats_partial(const Dims& d, const IndexParams& ip, const void* x, Partial* partial,
                                 int splits, int c0, int cg, hipStream_t st);
+// Statistics and Eq. 8 in one launch with one 1024-thread block per channel, for channels with few
+// sampled points; returns false (nothing launched) when that does not apply.
+bool launch_stats_one_block(const Dims& d, const IndexParams& ip, const void* x, int c0, int cg, float eps,
+                            float momentum, float* save_mean, float* save_invstd, float* running_mean,
+                            float* running_var, hipStream_t st, hipError_t* err);
 // Fixed-order combine, mean / inv-std, running averages (Eq. 8).
 hipError_t launch_stats_finalize(const Dims& d, const IndexParams& ip, const void* x, const Partial* partial,
                                  int splits, int c0, int cg, float eps, float momentum,

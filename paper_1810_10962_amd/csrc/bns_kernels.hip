@@ -119,6 +119,89 @@ __global__ __launch_bounds__(kBlock) void stats_partial_patch_kernel(
     if (threadIdx.x == 0) partial[size_t(c) * splits + k] = Partial{s1, s2};
 }
 
+// Few sampled points per channel (Batch Sampling or Feature Sampling at the paper's ratios): ONE
+// block of 1024 threads per channel reduces all of them and applies Eq. 3 and Eq. 8 itself, so
+// the statistics need a single launch and no hand-over between blocks.
+// PLANES: S made of whole planes and HW a multiple of V (128-bit accesses); else scalar patch walk.
+constexpr int kOneBlock = 1024;
+template <typename T, int V, bool PLANES>
+__global__ __launch_bounds__(kOneBlock) void stats_one_block_kernel(
+    const T* __restrict__ x, IndexParams ip, int C, int W, int HW, FastDiv hwv_div, FastDiv patch_div, FastDiv pw_div,
+    int c0, float eps, float momentum, float* __restrict__ save_mean, float* __restrict__ save_invstd,
+    float* __restrict__ running_mean, float* __restrict__ running_var) {
+    __shared__ float lds[2 * (kOneBlock / kWave)];
+    const int c = c0 + blockIdx.x;
+    const bns_box b = box_of_channel(ip, c);
+    const size_t nstride = size_t(C) * HW;
+    const T* base = x + (size_t(b.n0) * C + c) * HW + size_t(b.h0) * W + b.w0;   // first sampled element
+    const float pivot = load_scalar<T>(base);
+    float s1 = 0.f, s2 = 0.f;
+    if (PLANES) {
+        const uint32_t hwv = hwv_div.d;
+        const uint32_t tot = uint32_t(b.n_cnt) * hwv;
+        constexpr int U = 8;                                   // all of a thread's loads in flight at once
+        for (uint32_t j0 = threadIdx.x; j0 < tot; j0 += U * kOneBlock) {
+            Vec<T, V> v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t j = j0 + u * kOneBlock;
+                if (j < tot) {
+                    const uint32_t n = fdiv(j, hwv_div);
+                    v[u].load_nt(base + n * nstride + size_t(j - n * hwv) * V);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t j = j0 + u * kOneBlock;
+                if (j < tot) {
+#pragma unroll
+                    for (int i = 0; i < V; ++i) {
+                        const float dlt = v[u].f[i] - pivot;
+                        s1 += dlt;
+                        s2 = fmaf(dlt, dlt, s2);
+                    }
+                }
+            }
+        }
+    } else {
+        const uint32_t tot = uint32_t(b.n_cnt) * patch_div.d;
+        constexpr int U = 8;
+        for (uint32_t j0 = threadIdx.x; j0 < tot; j0 += U * kOneBlock) {
+            float v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t j = j0 + u * kOneBlock;
+                if (j < tot) {
+                    const uint32_t n = fdiv(j, patch_div);
+                    const uint32_t r = j - n * patch_div.d;
+                    const uint32_t ph = fdiv(r, pw_div);
+                    v[u] = load_scalar<T>(base + n * nstride + size_t(ph) * W + (r - ph * pw_div.d));
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (j0 + u * kOneBlock < tot) {
+                    const float dlt = v[u] - pivot;
+                    s1 += dlt;
+                    s2 = fmaf(dlt, dlt, s2);
+                }
+            }
+        }
+    }
+    block_sum2<kOneBlock>(s1, s2, lds);
+    if (threadIdx.x != 0) return;
+    const double s = double(b.n_cnt) * double(b.h_cnt) * double(b.w_cnt);
+    const double m1 = double(s1) / s;
+    const double mean = double(pivot) + m1;
+    double var = double(s2) / s - m1 * m1;
+    if (var < 0.0) var = 0.0;
+    save_mean[c] = float(mean);
+    save_invstd[c] = float(1.0 / sqrt(var + double(eps)));
+    const double a = double(momentum);
+    if (running_mean) running_mean[c] = float((1.0 - a) * double(running_mean[c]) + a * mean);
+    if (running_var) running_var[c] = float((1.0 - a) * double(running_var[c]) + a * var);
+}
+
 // One wave per channel: lane k holds split k, fp64 butterfly (a fixed pattern, so the
 // rounding order never changes), then lane 0 applies Eq. 3 and Eq. 8.  splits <= 64.
 template <typename T>
@@ -540,6 +623,36 @@ hipError_t launch_stats_partial(const Dims& d, const IndexParams& ip, const void
                            static_cast<const bf16_t*>(x), partial, ip, d.C, d.W, d.HW, make_fastdiv(patch),
                            make_fastdiv(uint32_t(b.w_cnt)), c0, splits, per_block);
     return hipGetLastError();
+}
+
+// Statistics in one launch, one block per channel; false if the channel has too many sampled
+// points for that (the caller then uses partial sums + finalize).
+bool launch_stats_one_block(const Dims& d, const IndexParams& ip, const void* x, int c0, int cg, float eps,
+                            float momentum, float* save_mean, float* save_invstd, float* running_mean,
+                            float* running_var, hipStream_t st, hipError_t* err) {
+    const bns_box& b = ip.shared;
+    const bool planes = !ip.per_channel && b.h_cnt == d.H && b.w_cnt == d.W && d.vec > 1;
+    const uint64_t pts = uint64_t(b.n_cnt) * b.h_cnt * b.w_cnt;
+    const uint64_t accesses = planes ? pts / d.vec : pts;
+    if (accesses > uint64_t(kOneBlock) * 16 || cg < 64) return false;     // <= 16 accesses per thread; enough blocks
+    const uint32_t hwv = uint32_t(d.HW / d.vec);
+    const uint32_t patch = uint32_t(b.h_cnt) * uint32_t(b.w_cnt);
+    const dim3 grid{uint32_t(cg)}, blk{uint32_t(kOneBlock)};
+    *err = dispatch(d, [&](auto t, auto vt) {
+        using T = decltype(t);
+        constexpr int V = decltype(vt)::value;
+        if (planes)
+            hipLaunchKernelGGL((stats_one_block_kernel<T, V, true>), grid, blk, 0, st, static_cast<const T*>(x), ip, d.C,
+                               d.W, d.HW, make_fastdiv(hwv), make_fastdiv(patch), make_fastdiv(uint32_t(b.w_cnt)), c0,
+                               eps, momentum, save_mean, save_invstd, running_mean, running_var);
+        else
+            hipLaunchKernelGGL((stats_one_block_kernel<T, V, false>), grid, blk, 0, st, static_cast<const T*>(x), ip,
+                               d.C, d.W, d.HW, make_fastdiv(hwv), make_fastdiv(patch),
+                               make_fastdiv(uint32_t(b.w_cnt)), c0, eps, momentum, save_mean, save_invstd, running_mean,
+                               running_var);
+        return hipGetLastError();
+    });
+    return true;
 }
 
 hipError_t launch_stats_finalize(const Dims& d, const IndexParams& ip, const void* x, const Partial* partial,
