@@ -595,7 +595,14 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
         const long Tmin = (chunks + va.kmax - 1) / va.kmax;                 // members needed for one channel
         if (Tmin > blocks || Tmin > kMaxTeam) return hipSuccess;
         long bestT = 0, best_cost = 0, best_rounds = 0;
-        const long Thi = (long(cg) * Tmin < blocks) ? blocks / cg : 2 * Tmin;
+        // widen only while every thread still keeps >= 4 vectors: below that the exchange costs more
+        // than the extra blocks bring
+        long Thi = 2 * Tmin;
+        if (long(cg) * Tmin < blocks) {
+            Thi = blocks / cg;
+            if (Thi > chunks / 4) Thi = chunks / 4;
+            if (Thi < Tmin) Thi = Tmin;
+        }
         for (long T = Tmin; T <= Thi && T <= kMaxTeam && T <= blocks; ++T) {
             const long teams = blocks / T < cg ? blocks / T : cg;
             const long rounds = (cg + teams - 1) / teams;
