@@ -34,10 +34,10 @@ METRIC = "BN fwd+bwd effective HBM GB/s (% peak) and speedup vs full BN, 64x256x
 # Filled from profiles/ (see there for the commands); None where no counter run exists.
 MEASURED_TRAFFIC = {
     # profiles/imagenet_bs_f32_hbm_traffic.md
-    ("imagenet_bs", "bwd"): 642780850,          # fused_backward_kernel
-    ("imagenet_bs", "normalize"): 411176456,
-    ("imagenet_bs", "dx"): 436934656,
-    ("imagenet_bs", "reduce"): 411114496,
+    ("imagenet_bs", "bwd"): 642812082,          # fused_backward_kernel
+    ("imagenet_bs", "normalize"): 411248852,
+    ("imagenet_bs", "dx"): 436968405,
+    ("imagenet_bs", "reduce"): 411114431,
 }
 
 
