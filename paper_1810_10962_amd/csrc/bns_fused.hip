@@ -19,12 +19,16 @@
 // Every member adds the T partials in member order, so all members get bit-identical
 // statistics, and results do not depend on timing.
 //
-// The grid is launched cooperatively (all blocks co-resident), which is what makes waiting
-// on a team-mate safe.  The wait is bounded: if a team-mate's slot never arrives, the sums
-// become NaN and the kernel still runs to completion.
+// Waiting on a team-mate is safe because the grid never exceeds what the device holds at once
+// (occupancy query x compute units) and because the blocks of a team have consecutive indices and
+// blocks are started in index order: a team-mate that is not running yet is next in line for a
+// slot, and slots are freed by complete teams, which depend on nothing else.  The wait is bounded
+// all the same: if a team-mate's slot never arrives, the sums become NaN and the kernel still
+// runs to completion.
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <mutex>
 
 #include "bns_device.hpp"
 #include "bns_internal.hpp"
@@ -531,6 +535,7 @@ struct DeviceInfo {
     int blocks_per_cu[2][5][kNumVariants];  // [backward][type/vec combo][variant], 0 = not queried yet
 };
 DeviceInfo g_dev[16];
+std::mutex g_dev_mutex;   // guards g_dev: launches may come from several host threads
 
 int combo_index(const Dims& d) {
     if (d.dtype == BNS_F32) return d.vec == 4 ? 0 : 1;
@@ -549,6 +554,7 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     hipError_t e = hipGetDevice(&devid);
     if (e != hipSuccess) return e;
     if (devid < 0 || devid >= 16) return hipErrorNotSupported;
+    std::lock_guard<std::mutex> lock(g_dev_mutex);      // planning only; released before the launch returns
     DeviceInfo& di = g_dev[devid];
     if (di.cus == 0) {
         int cus = 0, coop = 0;

@@ -23,6 +23,7 @@ struct Dims {
 // 64x256x56x56: one 128-bit access per thread and non-temporal loads and stores stream
 // fastest (streamed data is not re-read, so keeping it out of L2 avoids write-backs of
 // lines nobody will hit).
+// Plain ints set by bns_set_option: meant to be set before work is launched, not concurrently with it.
 struct Tuning {
     int norm_unroll = 0, norm_nt = -1;      // accesses per thread; bit 0: non-temporal loads, bit 1: stores
     int dx_unroll = 0, dx_nt = -1;
