@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kOneBlock) void stats_one_block_kernel(
         }
     } else {
         const uint32_t tot = uint32_t(b.n_cnt) * patch_div.d;
-        constexpr int U = 8;
+        constexpr int U = 16;                                  // scalar loads: one round trip for all of them
         for (uint32_t j0 = threadIdx.x; j0 < tot; j0 += U * kOneBlock) {
             float v[U];
 #pragma unroll
