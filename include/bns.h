@@ -7,11 +7,15 @@
  *
  * Conventions shared by every entry point
  * ---------------------------------------
- * Layout     x, y, dy, dx are dense N x C x H x W tensors (channel planes of H*W
- *            contiguous elements), element type given by bns_shape.dtype.  The
- *            reduction axes are N, H, W, i.e. the paper's E_{0,1,2} / Var_{0,1,2}
- *            on its N x H x W x C layout (Appendix A, notation).  Per-channel
- *            vectors (gamma, beta, statistics, dgamma, dbeta) are float[C].
+ * Layout     x, y, dy, dx are dense tensors, element type given by
+ *            bns_shape.dtype, in the layout bns_shape.layout names: N x C x H x W
+ *            (channel planes of H*W contiguous elements; the default) or
+ *            N x H x W x C (channels contiguous, the layout the paper's notation
+ *            uses, Appendix A).  Either way the reduction axes are N, H, W, the
+ *            paper's E_{0,1,2} / Var_{0,1,2}, and the same (shape, spec, seed) give
+ *            the same index and, up to rounding order, the same results.
+ *            Per-channel vectors (gamma, beta, statistics, dgamma, dbeta) are
+ *            float[C].
  * Memory     Unless an argument is marked HOST it is a DEVICE pointer owned by
  *            the caller, at least 16-byte aligned.  The library allocates and
  *            frees nothing and keeps no state between calls except the tuning
@@ -68,11 +72,17 @@ typedef enum {
 
 typedef enum { BNS_F32 = 0, BNS_BF16 = 1 } bns_dtype; /* storage of x, y, dy, dx; arithmetic is fp32 */
 
+typedef enum { BNS_NCHW = 0, BNS_NHWC = 1 } bns_layout; /* memory order of x, y, dy, dx */
+
 /* Tensor extents.  For VDN, N counts virtual + real samples (virtual first).
- * Limits: N <= 65535, C <= 2^24, H*W < 2^31, N*H*W < 2^31, C*H*W < 2^31. */
+ * Limits: N <= 65535, C <= 2^24, H*W < 2^31, N*H*W < 2^31, C*H*W < 2^31.
+ * BNS_NHWC: every channel shares one location set there, so Feature Sampling with
+ * fs_per_channel = 1 and the bns_*_mixed calls return BNS_EUNSUPPORTED; the other modes, both
+ * storage types and every stage call are available (streaming kernels only). */
 typedef struct {
     int32_t N, C, H, W;
-    int32_t dtype; /* bns_dtype */
+    int32_t dtype;  /* bns_dtype */
+    int32_t layout; /* bns_layout */
 } bns_shape;
 
 /* Sampling specification.  (seed, layer_id, epoch) select the random index: the paper
@@ -107,7 +117,8 @@ bns_status bns_sample_index(const bns_shape* shape, const bns_spec* spec, uint64
 bns_status bns_sample_index_device(const bns_shape* shape, const bns_spec* spec, uint64_t seed,
                                    bns_box* boxes /* DEVICE, C entries */, void* stream);
 
-/* Bytes of device scratch that bns_forward / bns_backward and their stages need. */
+/* Bytes of device scratch that bns_forward / bns_backward and their stages need (depends on the
+ * extents and the layout only). */
 size_t bns_workspace_bytes(const bns_shape* shape, const bns_spec* spec);
 
 /* Forward (Eq. 1 with the statistics of Eq. 3):
@@ -225,6 +236,7 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  *   "splits_reduce"  blocks per channel in the backward reduction                (1..64)
  *   "channel_group"  the streaming path walks the channels in groups of this many, every stage on
  *                    one group before the next                                   (1..C)
+ *   "nhwc_blocks"    blocks that an N x H x W x C kernel launch aims for         (1..8192)
  *   "norm_unroll", "dx_unroll", "reduce_unroll"   128-bit accesses per thread    (1, 2, 4)
  *   "norm_nt", "dx_nt", "reduce_nt"   non-temporal access mask + 1: bit 0 loads, bit 1 stores
  * Notes on the fused kernels: blocks of a team exchange partial sums through the workspace and wait

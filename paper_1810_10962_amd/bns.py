@@ -20,10 +20,12 @@ HEADER_PATH = os.path.join(os.path.dirname(_HERE), "include", "bns.h")
 BNS_OK, BNS_EINVAL, BNS_EUNSUPPORTED, BNS_EWORKSPACE, BNS_EDEVICE = range(5)
 BNS_FULL, BNS_NS, BNS_BS, BNS_FS, BNS_VDN = range(5)
 BNS_F32, BNS_BF16 = 0, 1
+BNS_NCHW, BNS_NHWC = 0, 1
 
 
 class bns_shape(C.Structure):
-    _fields_ = [("N", C.c_int32), ("C", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("dtype", C.c_int32)]
+    _fields_ = [("N", C.c_int32), ("C", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("dtype", C.c_int32),
+                ("layout", C.c_int32)]
 
 
 class bns_spec(C.Structure):
@@ -123,8 +125,9 @@ def _check(status, where):
         raise BnsError(status, where)
 
 
-def make_shape(N, C_, H, W, dtype="f32") -> bns_shape:
-    return bns_shape(N, C_, H, W, {"f32": BNS_F32, "bf16": BNS_BF16}[dtype] if isinstance(dtype, str) else dtype)
+def make_shape(N, C_, H, W, dtype="f32", layout="nchw") -> bns_shape:
+    return bns_shape(N, C_, H, W, {"f32": BNS_F32, "bf16": BNS_BF16}[dtype] if isinstance(dtype, str) else dtype,
+                     {"nchw": BNS_NCHW, "nhwc": BNS_NHWC}[layout] if isinstance(layout, str) else layout)
 
 
 def make_spec(mode, n_s=0, patch_h=0, patch_w=0, fs_per_channel=0, layer_id=0, epoch=0) -> bns_spec:
@@ -258,19 +261,25 @@ def bns_get_option(name: str) -> int:
 # convenience for tests, smoke and bench: device buffers for one workload
 # --------------------------------------------------------------------------------------
 class Buffers:
-    """Device tensors for one workload: inputs uploaded, outputs and workspace allocated."""
+    """Device tensors for one workload: inputs uploaded, outputs and workspace allocated.
+
+    ``inputs`` and ``results()`` are always indexed [n, c, h, w]; for an "nhwc" workload the device
+    copies of x, dy, y, dx are stored N x H x W x C (a transposition of the data, nothing else).
+    """
 
     def __init__(self, wl, inputs, device="cuda:0"):
         import torch
         tdt = torch.float32 if wl.dtype == "f32" else torch.bfloat16
         dev = torch.device(device)
         self.wl = wl
-        self.shape = make_shape(wl.N, wl.C, wl.H, wl.W, wl.dtype)
+        self.nhwc = getattr(wl, "layout", "nchw") == "nhwc"
+        self.shape = make_shape(wl.N, wl.C, wl.H, wl.W, wl.dtype, "nhwc" if self.nhwc else "nchw")
         self.spec = make_spec(wl.mode, wl.n_s, wl.patch_h, wl.patch_w, wl.fs_per_channel, wl.layer_id, wl.epoch)
         self.seed = wl.sampling_seed
         up = lambda a, dt=torch.float32: torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(dt).contiguous()
-        self.x = up(inputs["x"], tdt)
-        self.dy = up(inputs["dy"], tdt)
+        stored = (lambda a: np.transpose(a, (0, 2, 3, 1))) if self.nhwc else (lambda a: a)
+        self.x = up(stored(inputs["x"]), tdt)
+        self.dy = up(stored(inputs["dy"]), tdt)
         self.gamma = up(inputs["gamma"])
         self.beta = up(inputs["beta"])
         self.running_mean = up(inputs["running_mean"])
@@ -334,7 +343,8 @@ class Buffers:
         import torch
         torch.cuda.synchronize()
         host = lambda t: t.detach().float().cpu().numpy()
-        return dict(y=host(self.y), dx=host(self.dx), save_mean=host(self.save_mean),
+        logical = (lambda t: np.ascontiguousarray(np.transpose(host(t), (0, 3, 1, 2)))) if self.nhwc else host
+        return dict(y=logical(self.y), dx=logical(self.dx), save_mean=host(self.save_mean),
                     save_invstd=host(self.save_invstd), running_mean=host(self.running_mean),
                     running_var=host(self.running_var), dgamma=host(self.dgamma), dbeta=host(self.dbeta),
                     boxes=(bns_sample_index_mixed(self.shape, self.spec, self.seed, self.n_v) if self.n_v

@@ -30,6 +30,7 @@ bns_status check_shape(const bns_shape* sh, Dims* d) {
     if (!sh) return BNS_EINVAL;
     if (sh->N <= 0 || sh->C <= 0 || sh->H <= 0 || sh->W <= 0) return BNS_EINVAL;
     if (sh->dtype != BNS_F32 && sh->dtype != BNS_BF16) return BNS_EINVAL;
+    if (sh->layout != BNS_NCHW && sh->layout != BNS_NHWC) return BNS_EINVAL;
     const int64_t hw = int64_t(sh->H) * sh->W;
     const int64_t lim = int64_t(1) << 31;
     if (sh->N > 65535 || sh->C > (1 << 24) || hw >= lim || hw * sh->N >= lim || hw * sh->C >= lim)
@@ -40,6 +41,7 @@ bns_status check_shape(const bns_shape* sh, Dims* d) {
     d->W = sh->W;
     d->HW = int32_t(hw);
     d->dtype = sh->dtype;
+    d->layout = sh->layout;
     if (sh->dtype == BNS_BF16 && hw % 8 == 0)
         d->vec = 8;
     else if (hw % 4 == 0)
@@ -72,7 +74,15 @@ bns_status check_spec(const bns_shape* sh, const bns_spec* sp) {
 inline size_t elem_bytes(const Dims& d) { return d.dtype == BNS_F32 ? 4 : 2; }
 inline size_t tensor_bytes(const Dims& d) { return size_t(d.N) * d.C * d.HW * elem_bytes(d); }
 inline size_t partial_bytes(const Dims& d) { return (size_t(d.C) * kMaxSplits * sizeof(Partial) + 255) & ~size_t(255); }
-inline size_t workspace_need(const Dims& d) { return 2 * partial_bytes(d) + kSlotBytes; }   // [sums S][sums V][slots]
+inline bool nhwc(const Dims& d) { return d.layout == BNS_NHWC; }
+inline size_t workspace_need(const Dims& d) {
+    if (nhwc(d)) return nhwc_partial_bytes(d);
+    return 2 * partial_bytes(d) + kSlotBytes;   // [sums S][sums V][slots]
+}
+// N x H x W x C: one location set for all channels
+inline bns_status check_layout(const Dims& d, const bns_spec* sp) {
+    return (nhwc(d) && sp->mode == BNS_FS && sp->fs_per_channel) ? BNS_EUNSUPPORTED : BNS_OK;
+}
 
 inline bns_status dev(hipError_t e) { return e == hipSuccess ? BNS_OK : BNS_EDEVICE; }
 
@@ -172,8 +182,12 @@ bns_status bns_forward_stats(const bns_shape* shape, const bns_spec* spec, uint6
     if (!x || !save_mean || !save_invstd || !workspace) return BNS_EINVAL;
     if (!aligned16(x) || !aligned16(workspace)) return BNS_EINVAL;
     if (!(eps >= 0.f) || !(momentum >= 0.f && momentum <= 1.f)) return BNS_EINVAL;
+    if ((s = check_layout(d, spec)) != BNS_OK) return s;
     if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
     const IndexParams ip = make_index_params(*shape, *spec, seed);
+    if (nhwc(d))
+        return dev(launch_nhwc_stats(d, ip.shared, x, static_cast<Partial*>(workspace), eps, momentum, save_mean,
+                                     save_invstd, running_mean, running_var, static_cast<hipStream_t>(stream)));
     return stats_range(d, ip, x, eps, momentum, save_mean, save_invstd, running_mean, running_var,
                        static_cast<Partial*>(workspace), 0, d.C, static_cast<hipStream_t>(stream));
 }
@@ -186,6 +200,8 @@ bns_status bns_forward_normalize(const bns_shape* shape, const void* x, const fl
     if (!x || !gamma || !beta || !save_mean || !save_invstd || !y) return BNS_EINVAL;
     if (!aligned16(x) || !aligned16(y)) return BNS_EINVAL;
     if (overlap(x, tensor_bytes(d), y, tensor_bytes(d))) return BNS_EINVAL;
+    if (nhwc(d))
+        return dev(launch_nhwc_normalize(d, x, gamma, beta, save_mean, save_invstd, y, static_cast<hipStream_t>(stream)));
     return dev(launch_normalize(d, x, gamma, beta, save_mean, save_invstd, y, 0, d.C, static_cast<hipStream_t>(stream)));
 }
 
@@ -198,6 +214,9 @@ bns_status bns_inference(const bns_shape* shape, const void* x, const float* gam
     if (!aligned16(x) || !aligned16(y)) return BNS_EINVAL;
     if (!(eps >= 0.f)) return BNS_EINVAL;
     if (overlap(x, tensor_bytes(d), y, tensor_bytes(d))) return BNS_EINVAL;
+    if (nhwc(d))
+        return dev(launch_nhwc_normalize(d, x, gamma, beta, running_mean, running_var, y,
+                                         static_cast<hipStream_t>(stream), eps));
     return dev(launch_normalize(d, x, gamma, beta, running_mean, running_var, y, 0, d.C,
                                 static_cast<hipStream_t>(stream), eps));
 }
@@ -214,10 +233,19 @@ bns_status bns_forward(const bns_shape* shape, const bns_spec* spec, uint64_t se
     if (!aligned16(x) || !aligned16(y) || !aligned16(workspace)) return BNS_EINVAL;
     if (overlap(x, tensor_bytes(d), y, tensor_bytes(d))) return BNS_EINVAL;
     if (!(eps >= 0.f) || !(momentum >= 0.f && momentum <= 1.f)) return BNS_EINVAL;
+    if ((s = check_layout(d, spec)) != BNS_OK) return s;
     if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
     const IndexParams ip = make_index_params(*shape, *spec, seed);
     hipStream_t st = static_cast<hipStream_t>(stream);
     Partial* ws = static_cast<Partial*>(workspace);
+    if (nhwc(d)) {
+        if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
+        g_last_path_forward.store(1);
+        if (launch_nhwc_stats(d, ip.shared, x, ws, eps, momentum, save_mean, save_invstd, running_mean, running_var,
+                              st) != hipSuccess)
+            return BNS_EDEVICE;
+        return dev(launch_nhwc_normalize(d, x, gamma, beta, save_mean, save_invstd, y, st));
+    }
     if (g_tuning.path != 1) {
         FusedIo io;
         io.x = x;
@@ -258,6 +286,9 @@ bns_status bns_backward_reduce(const bns_shape* shape, const void* x, const void
     if (!x || !dy || !save_mean || !save_invstd || !dgamma || !dbeta || !workspace) return BNS_EINVAL;
     if (!aligned16(x) || !aligned16(dy) || !aligned16(workspace)) return BNS_EINVAL;
     if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
+    if (nhwc(d))
+        return dev(launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, static_cast<Partial*>(workspace), dgamma, dbeta,
+                                      static_cast<hipStream_t>(stream)));
     return reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, static_cast<Partial*>(workspace), 0, d.C,
                         static_cast<hipStream_t>(stream));
 }
@@ -273,7 +304,11 @@ bns_status bns_backward_dx(const bns_shape* shape, const bns_spec* spec, uint64_
     if (!aligned16(x) || !aligned16(dy) || !aligned16(dx)) return BNS_EINVAL;
     const size_t tb = tensor_bytes(d);
     if (overlap(dx, tb, x, tb) || overlap(dx, tb, dy, tb)) return BNS_EINVAL;
+    if ((s = check_layout(d, spec)) != BNS_OK) return s;
     const IndexParams ip = make_index_params(*shape, *spec, seed);
+    if (nhwc(d))
+        return dev(launch_nhwc_dx(d, ip.shared, x, dy, gamma, save_mean, save_invstd, dgamma, dbeta, dx,
+                                  static_cast<hipStream_t>(stream)));
     return dev(launch_dx(d, ip, x, dy, gamma, save_mean, save_invstd, dgamma, dbeta, dx, 0, d.C,
                          static_cast<hipStream_t>(stream)));
 }
@@ -290,10 +325,17 @@ bns_status bns_backward(const bns_shape* shape, const bns_spec* spec, uint64_t s
     if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || !aligned16(workspace)) return BNS_EINVAL;
     const size_t tb = tensor_bytes(d);
     if (overlap(dx, tb, x, tb) || overlap(dx, tb, dy, tb)) return BNS_EINVAL;
+    if ((s = check_layout(d, spec)) != BNS_OK) return s;
     if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
     const IndexParams ip = make_index_params(*shape, *spec, seed);
     hipStream_t st = static_cast<hipStream_t>(stream);
     Partial* ws = static_cast<Partial*>(workspace);
+    if (nhwc(d)) {
+        if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
+        g_last_path_backward.store(1);
+        if (launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, ws, dgamma, dbeta, st) != hipSuccess) return BNS_EDEVICE;
+        return dev(launch_nhwc_dx(d, ip.shared, x, dy, gamma, save_mean, save_invstd, dgamma, dbeta, dx, st));
+    }
     if (g_tuning.path != 1) {
         FusedIo io;
         io.x = x;
@@ -331,6 +373,7 @@ bns_status check_mixed(const bns_shape* shape, const bns_spec* spec, int32_t n_v
     bns_status s = check_shape(shape, d);
     if (s != BNS_OK) return s;
     if (!spec || n_v < 1 || n_v >= shape->N) return BNS_EINVAL;
+    if (nhwc(*d)) return BNS_EUNSUPPORTED;
     if (!(mix_beta >= 0.f && mix_beta <= 1.f)) return BNS_EINVAL;
     if (spec->mode == BNS_VDN) return BNS_EINVAL;            // the real part needs a sampling strategy
     bns_shape real = *shape;
@@ -437,6 +480,7 @@ bns_status bns_set_option(const char* name, int32_t value) {
         {"fused_variant", &g_tuning.fused_variant, 7, 0, false},
         {"fused_coop", &g_tuning.fused_coop, 1, 0, false},
         {"split_statistics", &g_tuning.split_statistics, 1, 0, false},
+        {"nhwc_blocks", &g_tuning.nhwc_blocks, kNhwcBlocksMax, 0, false},
     };
     for (auto& t : tun)
         if (!strcmp(name, t.n)) {

@@ -16,6 +16,7 @@ struct Dims {
     int32_t HW;     // H * W
     int32_t dtype;  // bns_dtype
     int32_t vec;    // elements per memory access: largest of {8 (bf16 only), 4, 1} dividing HW
+    int32_t layout; // bns_layout
 };
 
 // Launch-shape choices; 0 = the default for the storage type (see tuned()).  The benchmark
@@ -33,6 +34,7 @@ struct Tuning {
     int fused_variant = 0;                  // 1..7 forces a (block size, registers) variant of the fused kernels
     int fused_coop = 0;                     // 1: launch the fused kernels with hipLaunchCooperativeKernel
     int split_statistics = 0;               // 1: forward statistics always as partial sums + finalize
+    int nhwc_blocks = 0;                    // blocks an N x H x W x C launch aims for (default kNhwcBlocks)
 };
 extern Tuning g_tuning;
 inline int tuned(int v, int dflt) { return v > 0 ? v : dflt; }
@@ -110,5 +112,22 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st)
 
 // Blocks per channel for a reduction over `vectors_per_channel` memory accesses.
 int auto_splits(int cg, uint32_t vectors_per_channel);
+
+// N x H x W x C layout (bns_nhwc.hip): streaming kernels over all channels; `b` is the one location
+// set shared by the channels.  Partial sums: nhwc_partial_bytes(d) bytes of workspace.
+constexpr int kNhwcBlocks = 2048;      // blocks a launch aims for (8 per compute unit)
+constexpr int kNhwcBlocksMax = 8192;   // largest value the "nhwc_blocks" override takes
+constexpr int kNhwcMaxSplits = 2048;   // upper bound on blocks that share one channel's reduction
+size_t nhwc_partial_bytes(const Dims& d);
+hipError_t launch_nhwc_stats(const Dims& d, const bns_box& b, const void* x, Partial* partial, float eps, float momentum,
+                             float* save_mean, float* save_invstd, float* running_mean, float* running_var,
+                             hipStream_t st);
+hipError_t launch_nhwc_normalize(const Dims& d, const void* x, const float* gamma, const float* beta, const float* mean,
+                                 const float* invstd, void* y, hipStream_t st, float var_eps = -1.f);
+hipError_t launch_nhwc_reduce(const Dims& d, const void* x, const void* dy, const float* mean, const float* invstd,
+                              Partial* partial, float* dgamma, float* dbeta, hipStream_t st);
+hipError_t launch_nhwc_dx(const Dims& d, const bns_box& b, const void* x, const void* dy, const float* gamma,
+                          const float* mean, const float* invstd, const float* dgamma, const float* dbeta, void* dx,
+                          hipStream_t st);
 
 }  // namespace bns

@@ -1,0 +1,511 @@
+// Kernels for the N x H x W x C layout (the layout the paper writes its tensors in,
+// Appendix A: B_l in R^{N x H x W x C}, statistics over dimensions 0, 1, 2).
+//
+// The tensor is a matrix of M = N*H*W rows and C columns, channels fastest.  Per-channel
+// reductions are column sums; the location set S is a set of ROWS: a contiguous block of rows for
+// Batch Sampling / NS / VDN, h_cnt runs of w_cnt consecutive rows per sample for Feature Sampling
+// (one patch location per layer, as in Alg. 2).  A 128-bit access holds V consecutive channels of
+// one row.
+//
+// All four streaming kernels share one decomposition.  A block is TX column lanes x TY row lanes
+// (TX * TY = 256, TX = up to 64 accesses = one wave per row).  Block (tile, k) owns TX * V channels
+// and the k-th share of the rows; a thread keeps the per-channel constants of its V channels in
+// registers and walks its rows, so the element-wise passes load no parameter twice and divide
+// nothing, and the reductions end with one LDS step over the TY row lanes and one partial per
+// channel and block: partial[k][c].  The finalize kernels add the partials of a channel in a fixed
+// order in fp64, so results are bit-identical from run to run.
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "bns_device.hpp"
+#include "bns_internal.hpp"
+
+namespace bns {
+
+namespace {
+
+struct Tiling {
+    int32_t C, CV;              // channels, channel vectors per row
+    int32_t log2_tx, splits;    // TX = 1 << log2_tx column lanes; blocks along the rows
+    uint32_t rows_per_block;
+};
+
+struct RowSet {                 // the rows of S: sampled row i -> (n, ph, pw) -> row
+    int32_t n0, h0, w0;
+    int32_t H, W;
+    FastDiv patch_div;          // h_cnt * w_cnt
+    FastDiv pw_div;             // w_cnt
+    uint32_t rows;              // n_cnt * h_cnt * w_cnt
+};
+
+__device__ __forceinline__ uint32_t sampled_row(const RowSet& s, uint32_t i) {
+    const uint32_t n = fdiv(i, s.patch_div);
+    const uint32_t r = i - n * s.patch_div.d;
+    const uint32_t ph = fdiv(r, s.pw_div);
+    const uint32_t pw = r - ph * s.pw_div.d;
+    return ((uint32_t(s.n0) + n) * uint32_t(s.H) + uint32_t(s.h0) + ph) * uint32_t(s.W) + uint32_t(s.w0) + pw;
+}
+
+struct Lane {
+    int tx, ty, TY, k, cv;
+    bool live;
+};
+
+__device__ __forceinline__ Lane lane_of(const Tiling& t) {
+    Lane l;
+    const int TX = 1 << t.log2_tx;
+    l.TY = kBlock >> t.log2_tx;
+    l.tx = threadIdx.x & (TX - 1);
+    l.ty = threadIdx.x >> t.log2_tx;
+    const int tile = blockIdx.x / t.splits;
+    l.k = blockIdx.x - tile * t.splits;
+    l.cv = tile * TX + l.tx;
+    l.live = l.cv < t.CV;
+    return l;
+}
+
+// Adds a[], q[] over the TY row lanes of the block (fixed order) and writes one partial per channel.
+template <int V>
+__device__ __forceinline__ void write_partials(float (&a)[V], float (&q)[V], float* lds, const Tiling& t, const Lane& l,
+                                               Partial* __restrict__ partial) {
+    const int stride = (1 << t.log2_tx) * V;            // floats per row lane; lds: [2][TY][stride]
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        lds[l.ty * stride + l.tx * V + i] = a[i];
+        lds[(l.TY + l.ty) * stride + l.tx * V + i] = q[i];
+    }
+    __syncthreads();
+    if (l.ty != 0 || !l.live) return;
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        float sa = lds[l.tx * V + i], sq = lds[l.TY * stride + l.tx * V + i];
+        for (int r = 1; r < l.TY; ++r) {
+            sa += lds[r * stride + l.tx * V + i];
+            sq += lds[(l.TY + r) * stride + l.tx * V + i];
+        }
+        partial[size_t(l.k) * t.C + size_t(l.cv) * V + i] = Partial{sa, sq};
+    }
+}
+
+// Forward statistics (Eq. 3): partial[k][c] = (sum (x - p_c), sum (x - p_c)^2) over the k-th share of
+// S, p_c = x at the first sampled row (a pivot that keeps the one-pass variance well conditioned).
+template <typename T, int V>
+__global__ __launch_bounds__(kBlock) void nhwc_stats_partial_kernel(const T* __restrict__ x,
+                                                                    Partial* __restrict__ partial, RowSet S, Tiling t) {
+    __shared__ float lds[2 * kBlock * V];
+    const Lane l = lane_of(t);
+    const uint32_t i0 = uint32_t(l.k) * t.rows_per_block;
+    const uint32_t i1 = min(i0 + t.rows_per_block, S.rows);
+    const uint32_t TY = uint32_t(l.TY);
+    float a[V], q[V], p[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) a[e] = q[e] = p[e] = 0.f;
+    if (l.live) {
+        const T* xc = x + size_t(l.cv) * V;
+        Vec<T, V> pv;
+        pv.load(xc + size_t(sampled_row(S, 0)) * t.C);
+#pragma unroll
+        for (int e = 0; e < V; ++e) p[e] = pv.f[e];
+        uint32_t i = i0 + uint32_t(l.ty);
+        for (; i + 3u * TY < i1; i += 4u * TY) {
+            Vec<T, V> v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u].load_nt(xc + size_t(sampled_row(S, i + uint32_t(u) * TY)) * t.C);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    const float dlt = v[u].f[e] - p[e];
+                    a[e] += dlt;
+                    q[e] = fmaf(dlt, dlt, q[e]);
+                }
+        }
+        for (; i < i1; i += TY) {
+            Vec<T, V> v;
+            v.load_nt(xc + size_t(sampled_row(S, i)) * t.C);
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const float dlt = v.f[e] - p[e];
+                a[e] += dlt;
+                q[e] = fmaf(dlt, dlt, q[e]);
+            }
+        }
+    }
+    write_partials<V>(a, q, lds, t, l, partial);
+}
+
+// Backward sums of Eq. 5 over all M rows: partial[k][c] = (sum dy, sum dy * (x - mean_c)).
+template <typename T, int V>
+__global__ __launch_bounds__(kBlock) void nhwc_reduce_partial_kernel(const T* __restrict__ x, const T* __restrict__ dy,
+                                                                     const float* __restrict__ mean,
+                                                                     Partial* __restrict__ partial, Tiling t,
+                                                                     uint32_t M) {
+    __shared__ float lds[2 * kBlock * V];
+    const Lane l = lane_of(t);
+    const uint32_t r0 = uint32_t(l.k) * t.rows_per_block;
+    const uint32_t r1 = min(r0 + t.rows_per_block, M);
+    const uint32_t TY = uint32_t(l.TY);
+    float a[V], q[V], mu[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) a[e] = q[e] = mu[e] = 0.f;
+    if (l.live) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) mu[e] = mean[l.cv * V + e];
+        const size_t col = size_t(l.cv) * V;
+        uint32_t r = r0 + uint32_t(l.ty);
+        for (; r + TY < r1; r += 2u * TY) {
+            Vec<T, V> g[2], v[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const size_t off = size_t(r + uint32_t(u) * TY) * t.C + col;
+                g[u].load_nt(dy + off);
+                v[u].load_nt(x + off);
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    a[e] += g[u].f[e];
+                    q[e] = fmaf(g[u].f[e], v[u].f[e] - mu[e], q[e]);
+                }
+        }
+        for (; r < r1; r += TY) {
+            const size_t off = size_t(r) * t.C + col;
+            Vec<T, V> g, v;
+            g.load_nt(dy + off);
+            v.load_nt(x + off);
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                a[e] += g.f[e];
+                q[e] = fmaf(g.f[e], v.f[e] - mu[e], q[e]);
+            }
+        }
+    }
+    write_partials<V>(a, q, lds, t, l, partial);
+}
+
+// Finalize kernels: a block takes kFinCh neighbouring channels; thread (ch, kl) adds the partials
+// k = kl, kl + kFinK, ... of channel ch in fp64 (a wave reads whole 64-byte runs of partial[k][.]),
+// then thread ch adds the kFinK lane sums in index order.
+constexpr int kFinCh = 8;
+constexpr int kFinK = kBlock / kFinCh;
+
+__device__ __forceinline__ bool sum_splits(const Partial* __restrict__ partial, int C, int splits, double* lds, int& c,
+                                           double& s1, double& s2) {
+    const int ch = threadIdx.x % kFinCh, kl = threadIdx.x / kFinCh;
+    c = blockIdx.x * kFinCh + ch;
+    double a = 0.0, b = 0.0;
+    if (c < C)
+        for (int k = kl; k < splits; k += kFinK) {
+            const Partial p = partial[size_t(k) * C + c];
+            a += double(p.a);
+            b += double(p.b);
+        }
+    lds[kl * kFinCh + ch] = a;
+    lds[(kFinK + kl) * kFinCh + ch] = b;
+    __syncthreads();
+    if (kl != 0 || c >= C) return false;
+    s1 = lds[ch];
+    s2 = lds[kFinK * kFinCh + ch];
+    for (int j = 1; j < kFinK; ++j) {
+        s1 += lds[j * kFinCh + ch];
+        s2 += lds[(kFinK + j) * kFinCh + ch];
+    }
+    return true;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void nhwc_stats_finalize_kernel(
+    const T* __restrict__ x, const Partial* __restrict__ partial, RowSet S, int C, int splits, float eps, float momentum,
+    float* __restrict__ save_mean, float* __restrict__ save_invstd, float* __restrict__ running_mean,
+    float* __restrict__ running_var) {
+    __shared__ double lds[2 * kBlock];
+    int c;
+    double s1, s2;
+    if (!sum_splits(partial, C, splits, lds, c, s1, s2)) return;
+    const double pivot = double(load_scalar<T>(x + size_t(sampled_row(S, 0)) * C + c));
+    const double s = double(S.rows);
+    const double m1 = s1 / s;
+    const double mean = pivot + m1;
+    double var = s2 / s - m1 * m1;      // biased (1/s), Eq. 3
+    if (var < 0.0) var = 0.0;
+    save_mean[c] = float(mean);
+    save_invstd[c] = float(1.0 / sqrt(var + double(eps)));
+    const double al = double(momentum);                       // Eq. 8
+    if (running_mean) running_mean[c] = float((1.0 - al) * double(running_mean[c]) + al * mean);
+    if (running_var) running_var[c] = float((1.0 - al) * double(running_var[c]) + al * var);
+}
+
+__global__ __launch_bounds__(kBlock) void nhwc_reduce_finalize_kernel(const Partial* __restrict__ partial, int C,
+                                                                      int splits, const float* __restrict__ invstd,
+                                                                      float* __restrict__ dgamma,
+                                                                      float* __restrict__ dbeta) {
+    __shared__ double lds[2 * kBlock];
+    int c;
+    double s1, s2;
+    if (!sum_splits(partial, C, splits, lds, c, s1, s2)) return;
+    dbeta[c] = float(s1);
+    dgamma[c] = float(s2 * double(invstd[c]));
+}
+
+// Eq. 1 on every element.  var_eps >= 0: `invstd` holds variances (inference, Appendix D).
+template <typename T, int V>
+__global__ __launch_bounds__(kBlock) void nhwc_normalize_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                                const float* __restrict__ gamma,
+                                                                const float* __restrict__ beta,
+                                                                const float* __restrict__ mean,
+                                                                const float* __restrict__ invstd, Tiling t, uint32_t M,
+                                                                float var_eps) {
+    const Lane l = lane_of(t);
+    if (!l.live) return;
+    const uint32_t r0 = uint32_t(l.k) * t.rows_per_block;
+    const uint32_t r1 = min(r0 + t.rows_per_block, M);
+    const uint32_t TY = uint32_t(l.TY);
+    float sc[V], mu[V], be[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        const int c = l.cv * V + e;
+        const float r = var_eps >= 0.f ? 1.0f / sqrtf(invstd[c] + var_eps) : invstd[c];
+        sc[e] = gamma[c] * r;
+        mu[e] = mean[c];
+        be[e] = beta[c];
+    }
+    const size_t col = size_t(l.cv) * V;
+    uint32_t r = r0 + uint32_t(l.ty);
+    for (; r + 3u * TY < r1; r += 4u * TY) {
+        Vec<T, V> v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u].load_nt(x + size_t(r + uint32_t(u) * TY) * t.C + col);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) v[u].f[e] = fmaf(v[u].f[e] - mu[e], sc[e], be[e]);
+            v[u].store_nt(y + size_t(r + uint32_t(u) * TY) * t.C + col);
+        }
+    }
+    for (; r < r1; r += TY) {
+        Vec<T, V> v;
+        v.load_nt(x + size_t(r) * t.C + col);
+#pragma unroll
+        for (int e = 0; e < V; ++e) v.f[e] = fmaf(v.f[e] - mu[e], sc[e], be[e]);
+        v.store_nt(y + size_t(r) * t.C + col);
+    }
+}
+
+struct RowBox {                 // membership of a row in S
+    uint32_t n0, n1, h0, h1, w0, w1;
+    FastDiv hw_div, w_div;
+};
+
+__device__ __forceinline__ bool row_in(const RowBox& b, uint32_t row) {
+    const uint32_t n = fdiv(row, b.hw_div);
+    const uint32_t rem = row - n * b.hw_div.d;
+    const uint32_t h = fdiv(rem, b.w_div);
+    const uint32_t w = rem - h * b.w_div.d;
+    return n >= b.n0 && n < b.n1 && h >= b.h0 && h < b.h1 && w >= b.w0 && w < b.w1;
+}
+
+// Eq. 6 on every element: rows outside S scale dy, rows in S also read x and take the 1/s terms.
+//   dx = a g                                   a  = gamma r
+//   dx = a g - (k1 (x - mean) + k2)            k1 = a r dgamma / s,  k2 = a dbeta / s
+template <typename T, int V>
+__global__ __launch_bounds__(kBlock) void nhwc_dx_kernel(const T* __restrict__ x, const T* __restrict__ dy,
+                                                         T* __restrict__ dx, const float* __restrict__ gamma,
+                                                         const float* __restrict__ mean,
+                                                         const float* __restrict__ invstd,
+                                                         const float* __restrict__ dgamma,
+                                                         const float* __restrict__ dbeta, RowBox B, Tiling t,
+                                                         uint32_t M, float inv_s) {
+    const Lane l = lane_of(t);
+    if (!l.live) return;
+    const uint32_t r0 = uint32_t(l.k) * t.rows_per_block;
+    const uint32_t r1 = min(r0 + t.rows_per_block, M);
+    const uint32_t TY = uint32_t(l.TY);
+    float a[V], mu[V], k1[V], k2[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        const int c = l.cv * V + e;
+        const float r = invstd[c];
+        a[e] = gamma[c] * r;
+        mu[e] = mean[c];
+        k1[e] = a[e] * inv_s * (dgamma[c] * r);
+        k2[e] = a[e] * inv_s * dbeta[c];
+    }
+    const size_t col = size_t(l.cv) * V;
+    uint32_t r = r0 + uint32_t(l.ty);
+    for (; r + 3u * TY < r1; r += 4u * TY) {
+        Vec<T, V> g[4], v[4];
+        bool in[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t row = r + uint32_t(u) * TY;
+            g[u].load_nt(dy + size_t(row) * t.C + col);
+            in[u] = row_in(B, row);
+            if (in[u]) v[u].load_nt(x + size_t(row) * t.C + col);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (in[u]) {
+#pragma unroll
+                for (int e = 0; e < V; ++e) g[u].f[e] = fmaf(a[e], g[u].f[e], -fmaf(k1[e], v[u].f[e] - mu[e], k2[e]));
+            } else {
+#pragma unroll
+                for (int e = 0; e < V; ++e) g[u].f[e] *= a[e];
+            }
+            g[u].store_nt(dx + size_t(r + uint32_t(u) * TY) * t.C + col);
+        }
+    }
+    for (; r < r1; r += TY) {
+        Vec<T, V> g;
+        g.load_nt(dy + size_t(r) * t.C + col);
+        if (row_in(B, r)) {
+            Vec<T, V> v;
+            v.load_nt(x + size_t(r) * t.C + col);
+#pragma unroll
+            for (int e = 0; e < V; ++e) g.f[e] = fmaf(a[e], g.f[e], -fmaf(k1[e], v.f[e] - mu[e], k2[e]));
+        } else {
+#pragma unroll
+            for (int e = 0; e < V; ++e) g.f[e] *= a[e];
+        }
+        g.store_nt(dx + size_t(r) * t.C + col);
+    }
+}
+
+inline uint32_t ceil_div_u(uint32_t a, uint32_t b) { return uint32_t((uint64_t(a) + b - 1) / b); }
+
+inline int column_vec(const Dims& d) { return (d.dtype == BNS_BF16 && d.C % 8 == 0) ? 8 : (d.C % 4 == 0) ? 4 : 1; }
+
+// Blocks: enough to fill the device a few times over, each row lane with at least four rows.
+Tiling make_tiling(const Dims& d, uint32_t rows, int blocks = 0) {
+    Tiling t;
+    const int V = column_vec(d);
+    t.C = d.C;
+    t.CV = d.C / V;
+    int l = 0;
+    while ((1 << l) < t.CV && l < 6) ++l;
+    t.log2_tx = l;
+    const uint32_t tiles = uint32_t((t.CV + (1 << l) - 1) >> l);
+    const uint32_t TY = uint32_t(kBlock >> l);
+    uint32_t s = ceil_div_u(uint32_t(blocks > 0 ? blocks : tuned(g_tuning.nhwc_blocks, kNhwcBlocks)), tiles);
+    const uint32_t cap = rows / (TY * 4u);
+    if (s > cap) s = cap;
+    if (s > uint32_t(kNhwcMaxSplits)) s = kNhwcMaxSplits;
+    if (s < 1u) s = 1u;
+    t.rows_per_block = ceil_div_u(rows, s);
+    t.splits = int32_t(ceil_div_u(rows, t.rows_per_block));     // no empty blocks
+    return t;
+}
+
+inline uint32_t grid_of(const Tiling& t) {
+    const uint32_t tiles = uint32_t((t.CV + (1 << t.log2_tx) - 1) >> t.log2_tx);
+    return tiles * uint32_t(t.splits);
+}
+
+RowSet make_rowset(const Dims& d, const bns_box& b) {
+    RowSet s;
+    s.n0 = b.n0;
+    s.h0 = b.h0;
+    s.w0 = b.w0;
+    s.H = d.H;
+    s.W = d.W;
+    s.patch_div = make_fastdiv(uint32_t(b.h_cnt) * uint32_t(b.w_cnt));
+    s.pw_div = make_fastdiv(uint32_t(b.w_cnt));
+    s.rows = uint32_t(b.n_cnt) * uint32_t(b.h_cnt) * uint32_t(b.w_cnt);
+    return s;
+}
+
+template <int V>
+using VecTag = std::integral_constant<int, V>;
+
+template <typename F>
+hipError_t dispatch_nhwc(const Dims& d, F&& f) {
+    const int V = column_vec(d);
+    if (d.dtype == BNS_F32) return V == 4 ? f(float(), VecTag<4>()) : f(float(), VecTag<1>());
+    if (V == 8) return f(bf16_t(), VecTag<8>());
+    return V == 4 ? f(bf16_t(), VecTag<4>()) : f(bf16_t(), VecTag<1>());
+}
+
+}  // namespace
+
+size_t nhwc_partial_bytes(const Dims& d) {
+    // the most splits make_tiling can choose for this C, whatever the row count
+    const Tiling t = make_tiling(d, 0x7FFFFFFFu, kNhwcBlocksMax);
+    return (size_t(t.splits) * size_t(d.C) * sizeof(Partial) + 255) & ~size_t(255);
+}
+
+hipError_t launch_nhwc_stats(const Dims& d, const bns_box& b, const void* x, Partial* partial, float eps, float momentum,
+                             float* save_mean, float* save_invstd, float* running_mean, float* running_var,
+                             hipStream_t st) {
+    const RowSet S = make_rowset(d, b);
+    const Tiling t = make_tiling(d, S.rows);
+    return dispatch_nhwc(d, [&](auto ty, auto vt) {
+        using T = decltype(ty);
+        constexpr int V = decltype(vt)::value;
+        hipLaunchKernelGGL((nhwc_stats_partial_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st,
+                           static_cast<const T*>(x), partial, S, t);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((nhwc_stats_finalize_kernel<T>), dim3(ceil_div_u(uint32_t(d.C), kFinCh)), dim3(kBlock), 0, st,
+                           static_cast<const T*>(x), partial, S, d.C, t.splits, eps, momentum, save_mean, save_invstd,
+                           running_mean, running_var);
+        return hipGetLastError();
+    });
+}
+
+hipError_t launch_nhwc_normalize(const Dims& d, const void* x, const float* gamma, const float* beta, const float* mean,
+                                 const float* invstd, void* y, hipStream_t st, float var_eps) {
+    const uint32_t M = uint32_t(d.N) * uint32_t(d.HW);
+    const Tiling t = make_tiling(d, M);
+    return dispatch_nhwc(d, [&](auto ty, auto vt) {
+        using T = decltype(ty);
+        constexpr int V = decltype(vt)::value;
+        hipLaunchKernelGGL((nhwc_normalize_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st, static_cast<const T*>(x),
+                           static_cast<T*>(y), gamma, beta, mean, invstd, t, M, var_eps);
+        return hipGetLastError();
+    });
+}
+
+hipError_t launch_nhwc_reduce(const Dims& d, const void* x, const void* dy, const float* mean, const float* invstd,
+                              Partial* partial, float* dgamma, float* dbeta, hipStream_t st) {
+    const uint32_t M = uint32_t(d.N) * uint32_t(d.HW);
+    const Tiling t = make_tiling(d, M);
+    return dispatch_nhwc(d, [&](auto ty, auto vt) {
+        using T = decltype(ty);
+        constexpr int V = decltype(vt)::value;
+        hipLaunchKernelGGL((nhwc_reduce_partial_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st,
+                           static_cast<const T*>(x), static_cast<const T*>(dy), mean, partial, t, M);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(nhwc_reduce_finalize_kernel, dim3(ceil_div_u(uint32_t(d.C), kFinCh)), dim3(kBlock), 0, st,
+                           partial, d.C, t.splits, invstd, dgamma, dbeta);
+        return hipGetLastError();
+    });
+}
+
+hipError_t launch_nhwc_dx(const Dims& d, const bns_box& b, const void* x, const void* dy, const float* gamma,
+                          const float* mean, const float* invstd, const float* dgamma, const float* dbeta, void* dx,
+                          hipStream_t st) {
+    const uint32_t M = uint32_t(d.N) * uint32_t(d.HW);
+    const Tiling t = make_tiling(d, M);
+    RowBox B;
+    B.n0 = uint32_t(b.n0);
+    B.n1 = uint32_t(b.n0 + b.n_cnt);
+    B.h0 = uint32_t(b.h0);
+    B.h1 = uint32_t(b.h0 + b.h_cnt);
+    B.w0 = uint32_t(b.w0);
+    B.w1 = uint32_t(b.w0 + b.w_cnt);
+    B.hw_div = make_fastdiv(uint32_t(d.HW));
+    B.w_div = make_fastdiv(uint32_t(d.W));
+    const double s = double(b.n_cnt) * double(b.h_cnt) * double(b.w_cnt);
+    return dispatch_nhwc(d, [&](auto ty, auto vt) {
+        using T = decltype(ty);
+        constexpr int V = decltype(vt)::value;
+        hipLaunchKernelGGL((nhwc_dx_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st, static_cast<const T*>(x),
+                           static_cast<const T*>(dy), static_cast<T*>(dx), gamma, mean, invstd, dgamma, dbeta, B, t, M,
+                           float(1.0 / s));
+        return hipGetLastError();
+    });
+}
+
+}  // namespace bns

@@ -43,6 +43,7 @@ class Workload:
     n_v: int = 0            # "VDN + sampling" (Eq. 4): virtual samples in front; mode then samples the real ones
     mix_beta: float = 0.5   # beta of Eq. 4
     dtype: str = "f32"      # "f32" | "bf16" : storage type of x, y, dy, dx
+    layout: str = "nchw"    # "nchw" | "nhwc" : memory order on the device; arrays here are always [n, c, h, w]
     data_seed: int = 0
     sampling_seed: int = 0
     layer_id: int = 0
@@ -93,6 +94,10 @@ WORKLOADS = {
         _wl(3, "imagenet_bs_bf16", 64, 256, 56, 56, BS, n_s=8, dtype="bf16"),
         _wl(3, "imagenet_fs_bf16", 64, 256, 56, 56, FS, patch_h=14, patch_w=14, dtype="bf16"),
         _wl(3, "imagenet_full_bf16", 64, 256, 56, 56, FULL, dtype="bf16"),
+        _wl(3, "imagenet_bs_nhwc", 64, 256, 56, 56, BS, n_s=8, layout="nhwc"),
+        _wl(3, "imagenet_fs_nhwc", 64, 256, 56, 56, FS, patch_h=14, patch_w=14, layout="nhwc"),
+        _wl(3, "imagenet_full_nhwc", 64, 256, 56, 56, FULL, layout="nhwc"),
+        _wl(3, "imagenet_bs_nhwc_bf16", 64, 256, 56, 56, BS, n_s=8, dtype="bf16", layout="nhwc"),
         _wl(4, "vdn", 130, 128, 28, 28, VDN, n_s=2),
         # "FS + VDN", the paper's best-accuracy combination (Table 2): 2 virtual + 128 real samples,
         # one 7x7 patch (1/16 of a 28x28 map) of every real sample, beta = 0.5

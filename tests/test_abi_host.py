@@ -172,3 +172,35 @@ def test_options():
     _expect(bns.BNS_EINVAL, bns.bns_set_option, "splits_stats", 65)
     _expect(bns.BNS_EINVAL, bns.bns_set_option, "nonsense", 1)
     _expect(bns.BNS_EINVAL, bns.bns_set_option, "channel_group", -1)
+
+
+def test_layout_field_is_validated_and_nhwc_limits_are_reported():
+    """N x H x W x C: same index as N x C x H x W; an unknown layout is invalid; per-channel Feature
+    Sampling and the Eq. 4 calls are refused as unsupported before anything is enqueued."""
+    spec = bns.make_spec(bns.BNS_FS, 0, 3, 2, 0, 7, 1)
+    a = bns.bns_sample_index(bns.make_shape(6, 5, 9, 8), spec, 99)
+    b = bns.bns_sample_index(bns.make_shape(6, 5, 9, 8, layout="nhwc"), spec, 99)
+    assert (a == b).all()
+    bad = bns.make_shape(6, 5, 9, 8, layout=2)
+    _expect(bns.BNS_EINVAL, bns.bns_sample_index, bad, spec, 99)
+    assert bns.bns_workspace_bytes(bad, spec) == 0
+    nhwc = bns.make_shape(64, 256, 56, 56, layout="nhwc")
+    need = bns.bns_workspace_bytes(nhwc, spec)
+    assert 0 < need <= 64 << 20 and need % 256 == 0
+    assert bns.bns_workspace_bytes(bns.make_shape(2, 1 << 20, 2, 2, layout="nhwc"), spec) >= (1 << 20) * 8
+    _expect(bns.BNS_EUNSUPPORTED, bns.bns_sample_index_mixed, bns.make_shape(6, 5, 9, 8, layout="nhwc"), spec, 99, 2)
+
+    # fake (never dereferenced) addresses: the refusal comes before any launch
+    lib = bns.load()
+    pc = bns.make_spec(bns.BNS_FS, 0, 3, 2, 1, 7, 1)
+    shape = bns.make_shape(6, 8, 9, 8, layout="nhwc")
+    P = lambda a: C.c_void_p(a)
+    x, y, dy, dx, ws, v = 0x100000, 0x200000, 0x300000, 0x400000, 0x500000, 0x600000
+    assert lib.bns_forward(C.byref(shape), C.byref(pc), 1, P(x), P(v), P(v + 128), C.c_float(1e-5), C.c_float(0.1),
+                           P(y), P(v + 256), P(v + 384), None, None, P(ws), 1 << 30, None) == bns.BNS_EUNSUPPORTED
+    assert lib.bns_backward(C.byref(shape), C.byref(pc), 1, P(x), P(dy), P(v), P(v + 128), P(v + 256), P(dx),
+                            P(v + 384), P(v + 512), P(ws), 1 << 30, None) == bns.BNS_EUNSUPPORTED
+    shared = bns.make_spec(bns.BNS_FS, 0, 3, 2, 0, 7, 1)
+    assert lib.bns_forward(C.byref(shape), C.byref(shared), 1, P(x), P(v), P(v + 128), C.c_float(1e-5), C.c_float(0.1),
+                           P(y), P(v + 256), P(v + 384), None, None, P(ws),
+                           bns.bns_workspace_bytes(shape, shared) - 1, None) == bns.BNS_EWORKSPACE
