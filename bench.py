@@ -260,7 +260,7 @@ def main():
         "warmup": W, "ms_per_step": round(sec * 1e3, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32" if wl.dtype == "f32" else "bf16 storage, f32 arithmetic",
         "data": "synthetic",
-        "config": {"workload": f"{wl.name}: NCHW {wl.N}x{wl.C}x{wl.H}x{wl.W} {wl.dtype}, {wl.label()} "
+        "config": {"workload": f"{wl.name}: {wl.layout.upper()} {wl.N}x{wl.C}x{wl.H}x{wl.W} {wl.dtype}, {wl.label()} "
                                f"(sampling ratio {r:.4f}), forward+backward, eps={wl.eps}, momentum={wl.momentum}",
                    "buffer_sets_rotated": nset},
         "pct_of_hbm_peak": round(100 * alg["fwd+bwd"] / sec / 1e9 / HBM_PEAK_GBS, 2),
@@ -284,7 +284,8 @@ def main():
         variants = {}
         base = wl.name.split("_")[0]
         for name in [f"{base}_bs", f"{base}_fs", f"{base}_full", f"{base}_bs_bf16", f"{base}_fs_bf16",
-                     f"{base}_full_bf16"]:
+                     f"{base}_full_bf16", f"{base}_bs_nhwc", f"{base}_fs_nhwc", f"{base}_full_nhwc",
+                     f"{base}_bs_nhwc_bf16", f"{base}_full_nhwc_bf16"]:
             if name not in workloads.WORKLOADS:
                 continue
             v = workloads.WORKLOADS[name]
@@ -298,7 +299,7 @@ def main():
             vr = sampling_ratio(v, bns.bns_sample_index(vds.bufs[0].shape, vds.bufs[0].spec, v.sampling_seed))
             vsec = time_steps(vds, K, W, torch)
             va = algorithmic_bytes(v, vr)["fwd+bwd"]
-            variants[name] = dict(label=v.label(), dtype=v.dtype, ratio=round(vr, 4), us_per_step=round(vsec * 1e6, 2),
+            variants[name] = dict(label=v.label(), dtype=v.dtype, layout=v.layout, ratio=round(vr, 4), us_per_step=round(vsec * 1e6, 2),
                                   effective_GBs=round(va / vsec / 1e9, 1),
                                   pct_of_hbm_peak=round(100 * va / vsec / 1e9 / HBM_PEAK_GBS, 2),
                                   elements_per_s=round(v.elements / vsec, 1))

@@ -236,7 +236,8 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  *   "splits_reduce"  blocks per channel in the backward reduction                (1..64)
  *   "channel_group"  the streaming path walks the channels in groups of this many, every stage on
  *                    one group before the next                                   (1..C)
- *   "nhwc_blocks"    blocks that an N x H x W x C kernel launch aims for         (1..8192)
+ *   "nhwc_blocks"    blocks that an N x H x W x C reduction launch aims for      (1..8192)
+ *   "nhwc_ew_rows"   rows per thread in the N x H x W x C element-wise kernels   (1..2^20)
  *   "norm_unroll", "dx_unroll", "reduce_unroll"   128-bit accesses per thread    (1, 2, 4)
  *   "norm_nt", "dx_nt", "reduce_nt"   non-temporal access mask + 1: bit 0 loads, bit 1 stores
  * Notes on the fused kernels: blocks of a team exchange partial sums through the workspace and wait

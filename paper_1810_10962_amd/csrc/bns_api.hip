@@ -481,6 +481,7 @@ bns_status bns_set_option(const char* name, int32_t value) {
         {"fused_coop", &g_tuning.fused_coop, 1, 0, false},
         {"split_statistics", &g_tuning.split_statistics, 1, 0, false},
         {"nhwc_blocks", &g_tuning.nhwc_blocks, kNhwcBlocksMax, 0, false},
+        {"nhwc_ew_rows", &g_tuning.nhwc_ew_rows, 1 << 20, 0, false},
     };
     for (auto& t : tun)
         if (!strcmp(name, t.n)) {

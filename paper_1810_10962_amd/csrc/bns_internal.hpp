@@ -34,7 +34,8 @@ struct Tuning {
     int fused_variant = 0;                  // 1..7 forces a (block size, registers) variant of the fused kernels
     int fused_coop = 0;                     // 1: launch the fused kernels with hipLaunchCooperativeKernel
     int split_statistics = 0;               // 1: forward statistics always as partial sums + finalize
-    int nhwc_blocks = 0;                    // blocks an N x H x W x C launch aims for (default kNhwcBlocks)
+    int nhwc_blocks = 0;                    // blocks an N x H x W x C reduction aims for (default kNhwcBlocks)
+    int nhwc_ew_rows = 0;                   // rows per row lane in its element-wise kernels (default kNhwcEwRows)
 };
 extern Tuning g_tuning;
 inline int tuned(int v, int dflt) { return v > 0 ? v : dflt; }
@@ -115,8 +116,10 @@ int auto_splits(int cg, uint32_t vectors_per_channel);
 
 // N x H x W x C layout (bns_nhwc.hip): streaming kernels over all channels; `b` is the one location
 // set shared by the channels.  Partial sums: nhwc_partial_bytes(d) bytes of workspace.
-constexpr int kNhwcBlocks = 2048;      // blocks a launch aims for (8 per compute unit)
+constexpr int kNhwcBlocks = 512;       // blocks a reduction launch aims for (2 per compute unit: measured best)
+constexpr int kNhwcFill = 2048;        // fewest blocks an element-wise launch aims for (8 per compute unit)
 constexpr int kNhwcBlocksMax = 8192;   // largest value the "nhwc_blocks" override takes
+constexpr int kNhwcEwRows = 4;         // rows per row lane and block in the element-wise kernels
 constexpr int kNhwcMaxSplits = 2048;   // upper bound on blocks that share one channel's reduction
 size_t nhwc_partial_bytes(const Dims& d);
 hipError_t launch_nhwc_stats(const Dims& d, const bns_box& b, const void* x, Partial* partial, float eps, float momentum,

@@ -196,12 +196,24 @@ __device__ __forceinline__ bool sum_splits(const Partial* __restrict__ partial, 
     const int ch = threadIdx.x % kFinCh, kl = threadIdx.x / kFinCh;
     c = blockIdx.x * kFinCh + ch;
     double a = 0.0, b = 0.0;
-    if (c < C)
-        for (int k = kl; k < splits; k += kFinK) {
+    if (c < C) {
+        int k = kl;
+        for (; k + 7 * kFinK < splits; k += 8 * kFinK) {     // eight loads in flight, added in index order
+            Partial p[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) p[u] = partial[size_t(k + u * kFinK) * C + c];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                a += double(p[u].a);
+                b += double(p[u].b);
+            }
+        }
+        for (; k < splits; k += kFinK) {
             const Partial p = partial[size_t(k) * C + c];
             a += double(p.a);
             b += double(p.b);
         }
+    }
     lds[kl * kFinCh + ch] = a;
     lds[(kFinK + kl) * kFinCh + ch] = b;
     __syncthreads();
@@ -262,15 +274,21 @@ __global__ __launch_bounds__(kBlock) void nhwc_normalize_kernel(const T* __restr
     const uint32_t r0 = uint32_t(l.k) * t.rows_per_block;
     const uint32_t r1 = min(r0 + t.rows_per_block, M);
     const uint32_t TY = uint32_t(l.TY);
-    float sc[V], mu[V], be[V];
+    float sc[V], mu[V], be[V], rs[V];
 #pragma unroll
-    for (int e = 0; e < V; ++e) {
+    for (int e = 0; e < V; ++e) {       // every load first: one round trip to memory, not one per channel
         const int c = l.cv * V + e;
-        const float r = var_eps >= 0.f ? 1.0f / sqrtf(invstd[c] + var_eps) : invstd[c];
-        sc[e] = gamma[c] * r;
+        sc[e] = gamma[c];
+        rs[e] = invstd[c];
         mu[e] = mean[c];
         be[e] = beta[c];
     }
+    if (var_eps >= 0.f) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) rs[e] = 1.0f / sqrtf(rs[e] + var_eps);
+    }
+#pragma unroll
+    for (int e = 0; e < V; ++e) sc[e] *= rs[e];
     const size_t col = size_t(l.cv) * V;
     uint32_t r = r0 + uint32_t(l.ty);
     for (; r + 3u * TY < r1; r += 4u * TY) {
@@ -376,8 +394,9 @@ inline uint32_t ceil_div_u(uint32_t a, uint32_t b) { return uint32_t((uint64_t(a
 
 inline int column_vec(const Dims& d) { return (d.dtype == BNS_BF16 && d.C % 8 == 0) ? 8 : (d.C % 4 == 0) ? 4 : 1; }
 
-// Blocks: enough to fill the device a few times over, each row lane with at least four rows.
-Tiling make_tiling(const Dims& d, uint32_t rows, int blocks = 0) {
+// Blocks: enough to fill the device a few times over.  Reductions (blocks > 0, or the reduction
+// default) keep at least four rows per row lane and a bounded number of partials per channel.
+Tiling make_tiling(const Dims& d, uint32_t rows, int blocks = 0, bool elementwise = false) {
     Tiling t;
     const int V = column_vec(d);
     t.C = d.C;
@@ -387,11 +406,22 @@ Tiling make_tiling(const Dims& d, uint32_t rows, int blocks = 0) {
     t.log2_tx = l;
     const uint32_t tiles = uint32_t((t.CV + (1 << l) - 1) >> l);
     const uint32_t TY = uint32_t(kBlock >> l);
-    uint32_t s = ceil_div_u(uint32_t(blocks > 0 ? blocks : tuned(g_tuning.nhwc_blocks, kNhwcBlocks)), tiles);
-    const uint32_t cap = rows / (TY * 4u);
-    if (s > cap) s = cap;
-    if (s > uint32_t(kNhwcMaxSplits)) s = kNhwcMaxSplits;
+    uint32_t s;
+    if (elementwise) {
+        // short blocks of a few rows per row lane (the launch then streams through memory front to back
+        // like a flat kernel); fewer rows per lane when that would leave compute units idle
+        s = ceil_div_u(rows, TY * uint32_t(tuned(g_tuning.nhwc_ew_rows, kNhwcEwRows)));
+        const uint32_t fill = ceil_div_u(uint32_t(kNhwcFill), tiles), cap = rows / TY;
+        if (s < fill) s = fill < cap ? fill : cap;
+    } else {
+        if (blocks <= 0) blocks = tuned(g_tuning.nhwc_blocks, kNhwcBlocks);
+        s = ceil_div_u(uint32_t(blocks), tiles);
+        const uint32_t cap = rows / (TY * 4u);
+        if (s > cap) s = cap;
+        if (s > uint32_t(kNhwcMaxSplits)) s = kNhwcMaxSplits;
+    }
     if (s < 1u) s = 1u;
+    while (uint64_t(tiles) * s > 0x7FFFFFFFu) s = (s + 1u) / 2u;      // grid.x limit
     t.rows_per_block = ceil_div_u(rows, s);
     t.splits = int32_t(ceil_div_u(rows, t.rows_per_block));     // no empty blocks
     return t;
@@ -456,7 +486,7 @@ hipError_t launch_nhwc_stats(const Dims& d, const bns_box& b, const void* x, Par
 hipError_t launch_nhwc_normalize(const Dims& d, const void* x, const float* gamma, const float* beta, const float* mean,
                                  const float* invstd, void* y, hipStream_t st, float var_eps) {
     const uint32_t M = uint32_t(d.N) * uint32_t(d.HW);
-    const Tiling t = make_tiling(d, M);
+    const Tiling t = make_tiling(d, M, 0, true);
     return dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
         constexpr int V = decltype(vt)::value;
@@ -487,7 +517,7 @@ hipError_t launch_nhwc_dx(const Dims& d, const bns_box& b, const void* x, const 
                           const float* mean, const float* invstd, const float* dgamma, const float* dbeta, void* dx,
                           hipStream_t st) {
     const uint32_t M = uint32_t(d.N) * uint32_t(d.HW);
-    const Tiling t = make_tiling(d, M);
+    const Tiling t = make_tiling(d, M, 0, true);
     RowBox B;
     B.n0 = uint32_t(b.n0);
     B.n1 = uint32_t(b.n0 + b.n_cnt);

@@ -98,6 +98,7 @@ WORKLOADS = {
         _wl(3, "imagenet_fs_nhwc", 64, 256, 56, 56, FS, patch_h=14, patch_w=14, layout="nhwc"),
         _wl(3, "imagenet_full_nhwc", 64, 256, 56, 56, FULL, layout="nhwc"),
         _wl(3, "imagenet_bs_nhwc_bf16", 64, 256, 56, 56, BS, n_s=8, dtype="bf16", layout="nhwc"),
+        _wl(3, "imagenet_full_nhwc_bf16", 64, 256, 56, 56, FULL, dtype="bf16", layout="nhwc"),
         _wl(4, "vdn", 130, 128, 28, 28, VDN, n_s=2),
         # "FS + VDN", the paper's best-accuracy combination (Table 2): 2 virtual + 128 real samples,
         # one 7x7 patch (1/16 of a 28x28 map) of every real sample, beta = 0.5
