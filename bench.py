@@ -249,6 +249,8 @@ def main():
     else:
         cands.append(("normalize_kernel", stages["normalize"], alg["normalize"], "normalize"))
     kernel_name, dom_s, dom_bytes, dom_key = max(cands, key=lambda c: c[1])
+    if wl.layout == "nhwc":
+        kernel_name = "nhwc_" + kernel_name
     achieved = dom_bytes / dom_s / 1e9
     roofline = dict(bound="hbm", kernel=kernel_name, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4), traffic=MEASURED_TRAFFIC.get((wl.name, dom_key)),
