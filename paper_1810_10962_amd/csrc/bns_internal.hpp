@@ -121,6 +121,7 @@ constexpr int kNhwcFill = 2048;        // fewest blocks an element-wise launch a
 constexpr int kNhwcBlocksMax = 8192;   // largest value the "nhwc_blocks" override takes
 constexpr int kNhwcEwRows = 4;         // rows per row lane and block in the element-wise kernels
 constexpr int kNhwcMaxSplits = 2048;   // upper bound on blocks that share one channel's reduction
+constexpr int kNhwcMaxLaneRows = 1024; // rows one thread accumulates in fp32 before the sums are combined
 size_t nhwc_partial_bytes(const Dims& d);
 hipError_t launch_nhwc_stats(const Dims& d, const bns_box& b, const void* x, Partial* partial, float eps, float momentum,
                              float* save_mean, float* save_invstd, float* running_mean, float* running_var,

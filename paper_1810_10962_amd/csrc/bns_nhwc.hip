@@ -37,7 +37,14 @@ struct RowSet {                 // the rows of S: sampled row i -> (n, ph, pw) -
     FastDiv patch_div;          // h_cnt * w_cnt
     FastDiv pw_div;             // w_cnt
     uint32_t rows;              // n_cnt * h_cnt * w_cnt
+    uint32_t pivot_rows;        // min(kPivotRows, rows)
+    float inv_pivot_rows;
 };
+
+// The one-pass variance is taken about a pivot p_c close to the mean: sum (x - p)^2 / s - (sum (x - p) / s)^2
+// loses (1 + 2 k^2) digits' worth for a pivot k standard deviations off.  p_c = mean of the first few
+// sampled rows (added in row order, the same expression in the partial and the finalize kernel).
+constexpr int kPivotRows = 8;
 
 __device__ __forceinline__ uint32_t sampled_row(const RowSet& s, uint32_t i) {
     const uint32_t n = fdiv(i, s.patch_div);
@@ -89,7 +96,7 @@ __device__ __forceinline__ void write_partials(float (&a)[V], float (&q)[V], flo
 }
 
 // Forward statistics (Eq. 3): partial[k][c] = (sum (x - p_c), sum (x - p_c)^2) over the k-th share of
-// S, p_c = x at the first sampled row (a pivot that keeps the one-pass variance well conditioned).
+// S, p_c = mean of x over the first few sampled rows.
 template <typename T, int V>
 __global__ __launch_bounds__(kBlock) void nhwc_stats_partial_kernel(const T* __restrict__ x,
                                                                     Partial* __restrict__ partial, RowSet S, Tiling t) {
@@ -103,10 +110,18 @@ __global__ __launch_bounds__(kBlock) void nhwc_stats_partial_kernel(const T* __r
     for (int e = 0; e < V; ++e) a[e] = q[e] = p[e] = 0.f;
     if (l.live) {
         const T* xc = x + size_t(l.cv) * V;
-        Vec<T, V> pv;
-        pv.load(xc + size_t(sampled_row(S, 0)) * t.C);
+        Vec<T, V> pv[kPivotRows];
 #pragma unroll
-        for (int e = 0; e < V; ++e) p[e] = pv.f[e];
+        for (int j = 0; j < kPivotRows; ++j)
+            if (uint32_t(j) < S.pivot_rows) pv[j].load(xc + size_t(sampled_row(S, uint32_t(j))) * t.C);
+#pragma unroll
+        for (int j = 0; j < kPivotRows; ++j)
+            if (uint32_t(j) < S.pivot_rows) {
+#pragma unroll
+                for (int e = 0; e < V; ++e) p[e] += pv[j].f[e];
+            }
+#pragma unroll
+        for (int e = 0; e < V; ++e) p[e] *= S.inv_pivot_rows;
         uint32_t i = i0 + uint32_t(l.ty);
         for (; i + 3u * TY < i1; i += 4u * TY) {
             Vec<T, V> v[4];
@@ -236,7 +251,14 @@ __global__ __launch_bounds__(kBlock) void nhwc_stats_finalize_kernel(
     int c;
     double s1, s2;
     if (!sum_splits(partial, C, splits, lds, c, s1, s2)) return;
-    const double pivot = double(load_scalar<T>(x + size_t(sampled_row(S, 0)) * C + c));
+    float pv[kPivotRows], psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < kPivotRows; ++j)
+        if (uint32_t(j) < S.pivot_rows) pv[j] = load_scalar<T>(x + size_t(sampled_row(S, uint32_t(j))) * C + c);
+#pragma unroll
+    for (int j = 0; j < kPivotRows; ++j)
+        if (uint32_t(j) < S.pivot_rows) psum += pv[j];
+    const double pivot = double(psum * S.inv_pivot_rows);
     const double s = double(S.rows);
     const double m1 = s1 / s;
     const double mean = pivot + m1;
@@ -418,6 +440,9 @@ Tiling make_tiling(const Dims& d, uint32_t rows, int blocks = 0, bool elementwis
         s = ceil_div_u(uint32_t(blocks), tiles);
         const uint32_t cap = rows / (TY * 4u);
         if (s > cap) s = cap;
+        // a row lane adds its rows one after the other in fp32: keep that chain short
+        const uint32_t lo = ceil_div_u(rows, TY * uint32_t(kNhwcMaxLaneRows));
+        if (s < lo) s = lo;
         if (s > uint32_t(kNhwcMaxSplits)) s = kNhwcMaxSplits;
     }
     if (s < 1u) s = 1u;
@@ -442,6 +467,8 @@ RowSet make_rowset(const Dims& d, const bns_box& b) {
     s.patch_div = make_fastdiv(uint32_t(b.h_cnt) * uint32_t(b.w_cnt));
     s.pw_div = make_fastdiv(uint32_t(b.w_cnt));
     s.rows = uint32_t(b.n_cnt) * uint32_t(b.h_cnt) * uint32_t(b.w_cnt);
+    s.pivot_rows = s.rows < uint32_t(kPivotRows) ? s.rows : uint32_t(kPivotRows);
+    s.inv_pivot_rows = 1.0f / float(s.pivot_rows);
     return s;
 }
 
@@ -459,8 +486,8 @@ hipError_t dispatch_nhwc(const Dims& d, F&& f) {
 }  // namespace
 
 size_t nhwc_partial_bytes(const Dims& d) {
-    // the most splits make_tiling can choose for this C, whatever the row count
-    const Tiling t = make_tiling(d, 0x7FFFFFFFu, kNhwcBlocksMax);
+    // the most splits make_tiling can choose for this shape: they grow with the row count and the block target
+    const Tiling t = make_tiling(d, uint32_t(d.N) * uint32_t(d.HW), kNhwcBlocksMax);
     return (size_t(t.splits) * size_t(d.C) * sizeof(Partial) + 255) & ~size_t(255);
 }
 
