@@ -46,6 +46,16 @@ struct RowSet {                 // the rows of S: sampled row i -> (n, ph, pw) -
 // sampled rows (added in row order, the same expression in the partial and the finalize kernel).
 constexpr int kPivotRows = 8;
 
+// The pivot keeps only its upper 16 bits (a bf16 pattern): x - p is then exact for bf16 data and
+// carries no low bits that every addition would round the same way.
+__device__ __forceinline__ float coarse(float p) { return __uint_as_float(__float_as_uint(p) & 0xFFFF0000u); }
+
+// Accumulation.  A thread adds up to a thousand rows.  Adding them one by one into an fp32 sum loses
+// n * eps / 4 of the result when the addends share their low bits (constant dy, activations on a grid,
+// exact zeros after a ReLU): every addition then rounds the same way and the errors add up instead of
+// averaging out.  So the rows of one unrolled iteration are added in fp32 and each group's sum goes
+// into an fp64 accumulator (one fp64 add per group and channel: far below the fp64 rate).
+
 __device__ __forceinline__ uint32_t sampled_row(const RowSet& s, uint32_t i) {
     const uint32_t n = fdiv(i, s.patch_div);
     const uint32_t r = i - n * s.patch_div.d;
@@ -106,35 +116,35 @@ __global__ __launch_bounds__(kBlock) void nhwc_stats_partial_kernel(const T* __r
     const uint32_t i1 = min(i0 + t.rows_per_block, S.rows);
     const uint32_t TY = uint32_t(l.TY);
     float a[V], q[V], p[V];
+    double A[V], Q[V];
 #pragma unroll
-    for (int e = 0; e < V; ++e) a[e] = q[e] = p[e] = 0.f;
+    for (int e = 0; e < V; ++e) {
+        a[e] = q[e] = p[e] = 0.f;
+        A[e] = Q[e] = 0.0;
+    }
     if (l.live) {
         const T* xc = x + size_t(l.cv) * V;
         Vec<T, V> pv[kPivotRows];
 #pragma unroll
-        for (int j = 0; j < kPivotRows; ++j)
-            if (uint32_t(j) < S.pivot_rows) pv[j].load(xc + size_t(sampled_row(S, uint32_t(j))) * t.C);
+        for (int j = 0; j < kPivotRows; ++j)     // no branches: all loads in flight together
+            pv[j].load(xc + size_t(sampled_row(S, min(uint32_t(j), S.pivot_rows - 1u))) * t.C);
 #pragma unroll
         for (int j = 0; j < kPivotRows; ++j)
-            if (uint32_t(j) < S.pivot_rows) {
 #pragma unroll
-                for (int e = 0; e < V; ++e) p[e] += pv[j].f[e];
-            }
+            for (int e = 0; e < V; ++e) p[e] += uint32_t(j) < S.pivot_rows ? pv[j].f[e] : 0.f;
 #pragma unroll
-        for (int e = 0; e < V; ++e) p[e] *= S.inv_pivot_rows;
+        for (int e = 0; e < V; ++e) p[e] = coarse(p[e] * S.inv_pivot_rows);
         uint32_t i = i0 + uint32_t(l.ty);
         for (; i + 3u * TY < i1; i += 4u * TY) {
             Vec<T, V> v[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) v[u].load_nt(xc + size_t(sampled_row(S, i + uint32_t(u) * TY)) * t.C);
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int e = 0; e < V; ++e) {
-                    const float dlt = v[u].f[e] - p[e];
-                    a[e] += dlt;
-                    q[e] = fmaf(dlt, dlt, q[e]);
-                }
+            for (int e = 0; e < V; ++e) {
+                const float d0 = v[0].f[e] - p[e], d1 = v[1].f[e] - p[e], d2 = v[2].f[e] - p[e], d3 = v[3].f[e] - p[e];
+                A[e] += double((d0 + d1) + (d2 + d3));
+                Q[e] += double(fmaf(d3, d3, fmaf(d2, d2, fmaf(d1, d1, d0 * d0))));
+            }
         }
         for (; i < i1; i += TY) {
             Vec<T, V> v;
@@ -142,9 +152,14 @@ __global__ __launch_bounds__(kBlock) void nhwc_stats_partial_kernel(const T* __r
 #pragma unroll
             for (int e = 0; e < V; ++e) {
                 const float dlt = v.f[e] - p[e];
-                a[e] += dlt;
-                q[e] = fmaf(dlt, dlt, q[e]);
+                A[e] += double(dlt);
+                Q[e] += double(dlt * dlt);
             }
+        }
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            a[e] = float(A[e]);
+            q[e] = float(Q[e]);
         }
     }
     write_partials<V>(a, q, lds, t, l, partial);
@@ -162,8 +177,12 @@ __global__ __launch_bounds__(kBlock) void nhwc_reduce_partial_kernel(const T* __
     const uint32_t r1 = min(r0 + t.rows_per_block, M);
     const uint32_t TY = uint32_t(l.TY);
     float a[V], q[V], mu[V];
+    double A[V], Q[V];
 #pragma unroll
-    for (int e = 0; e < V; ++e) a[e] = q[e] = mu[e] = 0.f;
+    for (int e = 0; e < V; ++e) {
+        a[e] = q[e] = mu[e] = 0.f;
+        A[e] = Q[e] = 0.0;
+    }
     if (l.live) {
 #pragma unroll
         for (int e = 0; e < V; ++e) mu[e] = mean[l.cv * V + e];
@@ -178,12 +197,10 @@ __global__ __launch_bounds__(kBlock) void nhwc_reduce_partial_kernel(const T* __
                 v[u].load_nt(x + off);
             }
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int e = 0; e < V; ++e) {
-                    a[e] += g[u].f[e];
-                    q[e] = fmaf(g[u].f[e], v[u].f[e] - mu[e], q[e]);
-                }
+            for (int e = 0; e < V; ++e) {
+                A[e] += double(g[0].f[e] + g[1].f[e]);
+                Q[e] += double(fmaf(g[1].f[e], v[1].f[e] - mu[e], g[0].f[e] * (v[0].f[e] - mu[e])));
+            }
         }
         for (; r < r1; r += TY) {
             const size_t off = size_t(r) * t.C + col;
@@ -192,9 +209,14 @@ __global__ __launch_bounds__(kBlock) void nhwc_reduce_partial_kernel(const T* __
             v.load_nt(x + off);
 #pragma unroll
             for (int e = 0; e < V; ++e) {
-                a[e] += g.f[e];
-                q[e] = fmaf(g.f[e], v.f[e] - mu[e], q[e]);
+                A[e] += double(g.f[e]);
+                Q[e] += double(g.f[e] * (v.f[e] - mu[e]));
             }
+        }
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            a[e] = float(A[e]);
+            q[e] = float(Q[e]);
         }
     }
     write_partials<V>(a, q, lds, t, l, partial);
@@ -254,11 +276,10 @@ __global__ __launch_bounds__(kBlock) void nhwc_stats_finalize_kernel(
     float pv[kPivotRows], psum = 0.f;
 #pragma unroll
     for (int j = 0; j < kPivotRows; ++j)
-        if (uint32_t(j) < S.pivot_rows) pv[j] = load_scalar<T>(x + size_t(sampled_row(S, uint32_t(j))) * C + c);
+        pv[j] = load_scalar<T>(x + size_t(sampled_row(S, min(uint32_t(j), S.pivot_rows - 1u))) * C + c);
 #pragma unroll
-    for (int j = 0; j < kPivotRows; ++j)
-        if (uint32_t(j) < S.pivot_rows) psum += pv[j];
-    const double pivot = double(psum * S.inv_pivot_rows);
+    for (int j = 0; j < kPivotRows; ++j) psum += uint32_t(j) < S.pivot_rows ? pv[j] : 0.f;
+    const double pivot = double(coarse(psum * S.inv_pivot_rows));
     const double s = double(S.rows);
     const double m1 = s1 / s;
     const double mean = pivot + m1;

@@ -25,6 +25,55 @@ CASES = [
 ]
 
 
+def _device_case(wl, structured=False):
+    """Seeded device tensors for `wl` in its layout, one forward + backward through the C ABI.
+    structured: activations after a ReLU on a grid of 1/32 (many exact zeros), the same gradient 1/3 everywhere."""
+    N, C_, H, W = wl.shape
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if wl.dtype == "f32" else torch.bfloat16
+    g = torch.Generator(device=dev)
+    g.manual_seed(wl.data_seed)
+    f32 = dict(dtype=torch.float32, device=dev)
+    t = {}
+    mu = torch.rand(C_, generator=g, **f32) * 2 - 1
+    sigma = torch.rand(C_, generator=g, **f32) * 1.5 + 0.5
+    t["gamma"] = torch.rand(C_, generator=g, **f32) + 0.5
+    t["beta"] = torch.rand(C_, generator=g, **f32) - 0.5
+    nhwc = wl.layout == "nhwc"
+    stored = (N, H, W, C_) if nhwc else (N, C_, H, W)
+    per_c = (lambda v: v.view(1, 1, 1, C_)) if nhwc else (lambda v: v.view(1, C_, 1, 1))
+    t["x"] = torch.randn(stored, generator=g, dtype=tdt, device=dev)
+    t["x"].mul_(per_c(sigma).to(tdt)).add_(per_c(mu).to(tdt))
+    t["dy"] = torch.randn(stored, generator=g, dtype=tdt, device=dev)
+    if structured:
+        t["x"].clamp_(min=0).mul_(32).round_().div_(32)
+        t["dy"].fill_(1.0 / 3.0)
+    t["y"], t["dx"] = torch.empty_like(t["x"]), torch.empty_like(t["x"])
+    for k in ("save_mean", "save_invstd", "dgamma", "dbeta"):
+        t[k] = torch.empty(C_, **f32)
+    t["running_mean"], t["running_var"] = torch.zeros(C_, **f32), torch.ones(C_, **f32)
+    shp = bns.make_shape(N, C_, H, W, wl.dtype, wl.layout)
+    spec = bns.make_spec(wl.mode, wl.n_s, wl.patch_h, wl.patch_w, 0, wl.layer_id, wl.epoch)
+    ws = torch.empty(bns.bns_workspace_bytes(shp, spec), dtype=torch.uint8, device=dev)
+    bns.bns_forward(shp, spec, wl.sampling_seed, t["x"], t["gamma"], t["beta"], wl.eps, wl.momentum, t["y"],
+                    t["save_mean"], t["save_invstd"], t["running_mean"], t["running_var"], ws)
+    bns.bns_backward(shp, spec, wl.sampling_seed, t["x"], t["dy"], t["gamma"], t["save_mean"], t["save_invstd"],
+                     t["dx"], t["dgamma"], t["dbeta"], ws)
+    torch.cuda.synchronize()
+    assert (bns.bns_sample_index(shp, spec, wl.sampling_seed) == oracle_boxes(wl)).all()
+    return t
+
+
+def _channels_to_host(t, wl, ch, names):
+    """[n, c, h, w] numpy copies of the channels `ch` of the 4-D tensors `names`; per-channel vectors whole."""
+    idx = torch.as_tensor(ch, device=t["x"].device)
+    if wl.layout == "nhwc":
+        take = lambda a: a.index_select(3, idx).permute(0, 3, 1, 2).float().cpu().numpy()
+    else:
+        take = lambda a: a.index_select(1, idx).float().cpu().numpy()
+    return {k: take(t[k]) for k in names}
+
+
 @pytest.mark.parametrize("layout", ["nchw", "nhwc"])
 @pytest.mark.parametrize("kind,shape,mkw,dtype", CASES, ids=[f"{c[0]}-{c[2]['mode']}-{c[3]}" for c in CASES])
 def test_more_than_2_31_elements(kind, shape, mkw, dtype, layout):
@@ -33,46 +82,18 @@ def test_more_than_2_31_elements(kind, shape, mkw, dtype, layout):
     wl = Workload(name=f"large_{kind}", N=N, C=C_, H=H, W=W, dtype=dtype, layout=layout, data_seed=5, sampling_seed=11,
                   layer_id=2, epoch=3, **mkw)
     print(f"[gpu-case] large {layout} {shape} {dtype} {mkw}", flush=True)
-    dev = torch.device("cuda:0")
-    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
-    g = torch.Generator(device=dev)
-    g.manual_seed(wl.data_seed)
-    f32 = dict(dtype=torch.float32, device=dev)
-    mu = torch.rand(C_, generator=g, **f32) * 2 - 1
-    sigma = torch.rand(C_, generator=g, **f32) * 1.5 + 0.5
-    gamma = torch.rand(C_, generator=g, **f32) + 0.5
-    beta = torch.rand(C_, generator=g, **f32) - 0.5
-    stored = (N, H, W, C_) if layout == "nhwc" else (N, C_, H, W)
-    per_c = (lambda v: v.view(1, 1, 1, C_)) if layout == "nhwc" else (lambda v: v.view(1, C_, 1, 1))
-    x = torch.randn(stored, generator=g, dtype=tdt, device=dev)
-    x.mul_(per_c(sigma).to(tdt)).add_(per_c(mu).to(tdt))
-    dy = torch.randn(stored, generator=g, dtype=tdt, device=dev)
-    y, dx = torch.empty_like(x), torch.empty_like(x)
-    save_mean, save_invstd, dgamma, dbeta = (torch.empty(C_, **f32) for _ in range(4))
-    rm, rv = torch.zeros(C_, **f32), torch.ones(C_, **f32)
-    shp = bns.make_shape(N, C_, H, W, dtype, layout)
-    spec = bns.make_spec(wl.mode, wl.n_s, wl.patch_h, wl.patch_w, 0, wl.layer_id, wl.epoch)
-    ws = torch.empty(bns.bns_workspace_bytes(shp, spec), dtype=torch.uint8, device=dev)
-    bns.bns_forward(shp, spec, wl.sampling_seed, x, gamma, beta, wl.eps, wl.momentum, y, save_mean, save_invstd, rm, rv, ws)
-    bns.bns_backward(shp, spec, wl.sampling_seed, x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta, ws)
-    torch.cuda.synchronize()
+    t = _device_case(wl)
     if layout == "nchw" and kind == "channels":
         assert bns.bns_get_option("last_path_backward") == 2          # the single-launch kernel ran
-
     ch = [0, 1, C_ // 2 - 1, C_ // 2, C_ - 2, C_ - 1]
-    idx = torch.tensor(ch, device=dev)
-    if layout == "nhwc":
-        take = lambda t: t.index_select(3, idx).permute(0, 3, 1, 2).float().cpu().numpy()
-    else:
-        take = lambda t: t.index_select(1, idx).float().cpu().numpy()
-    vec = lambda t: t[idx].cpu().numpy()
-    inp = dict(x=take(x), dy=take(dy), gamma=vec(gamma), beta=vec(beta))
-    res = dict(y=take(y), dx=take(dx), save_mean=vec(save_mean), save_invstd=vec(save_invstd), running_mean=vec(rm),
-               running_var=vec(rv), dgamma=vec(dgamma), dbeta=vec(dbeta))
-    del x, dy, y, dx
+    host = _channels_to_host(t, wl, ch, ("x", "dy", "y", "dx"))
+    vec = lambda k: t[k][ch].cpu().numpy()
+    inp = dict(x=host["x"], dy=host["dy"], gamma=vec("gamma"), beta=vec("beta"))
+    res = dict(y=host["y"], dx=host["dx"], **{k: vec(k) for k in ("save_mean", "save_invstd", "running_mean",
+                                                                  "running_var", "dgamma", "dbeta")})
+    del t
     torch.cuda.empty_cache()
     boxes = oracle_boxes(wl)[ch]
-    assert (bns.bns_sample_index(shp, spec, wl.sampling_seed)[ch] == boxes).all()
     k = len(ch)
     f = oracle.forward(inp["x"], inp["gamma"], inp["beta"], boxes, wl.eps, wl.momentum, np.zeros(k), np.ones(k))
     b = oracle.backward(inp["x"], inp["dy"], inp["gamma"], f["mean"], f["var"], boxes, wl.eps)
@@ -80,3 +101,67 @@ def test_more_than_2_31_elements(kind, shape, mkw, dtype, layout):
                running_var=f["running_var"], dx=b["dx"], dgamma=b["dgamma"], dbeta=b["dbeta"])
     errs = assert_parity(res, ref, wl, what=f"large {layout} {shape}")
     print(f"[gpu-case] large scaled errors {errs}", flush=True)
+
+
+@pytest.mark.parametrize("layout", ["nchw", "nhwc"])
+def test_statistics_of_every_channel_of_a_large_tensor(layout):
+    """All 16384 channels of a 64x16384x48x48 tensor: the sampled samples are copied back a block of
+    channels at a time and the oracle computes Eq. 3 / Eq. 8 for each (statistics over a Batch Sampling
+    set are the full statistics of those samples alone)."""
+    N, C_, H, W = 64, 16384, 48, 48
+    wl = Workload(name="large_stats", N=N, C=C_, H=H, W=W, mode=BS, n_s=8, dtype="bf16", layout=layout, data_seed=6,
+                  sampling_seed=12, layer_id=1, epoch=0)
+    print(f"[gpu-case] large statistics {layout}", flush=True)
+    t = _device_case(wl)
+    n0, n_cnt = (int(v) for v in oracle_boxes(wl)[0, :2])
+    sub = dict(t)
+    sub["x"] = t["x"][n0:n0 + n_cnt]
+    got = {k: t[k].cpu().numpy() for k in ("save_mean", "save_invstd", "running_mean", "running_var")}
+    ref = {k: np.empty(C_) for k in got}
+    step = 2048
+    for c0 in range(0, C_, step):
+        ch = np.arange(c0, c0 + step)
+        xs = _channels_to_host(sub, wl, ch, ("x",))["x"]
+        whole = np.tile(np.array([0, n_cnt, 0, H, 0, W]), (step, 1))
+        f = oracle.forward(xs, np.ones(step), np.zeros(step), whole, wl.eps, wl.momentum, np.zeros(step), np.ones(step))
+        for k, name in (("save_mean", "mean"), ("save_invstd", "invstd"), ("running_mean", "running_mean"),
+                        ("running_var", "running_var")):
+            ref[k][ch] = f[name]
+    worst, where = {}, {}
+    for k in got:
+        err = np.abs(got[k] - ref[k]) / (np.abs(ref[k]) + np.sqrt(np.mean(ref[k] ** 2)))
+        c = int(np.argmax(err))
+        worst[k], where[k] = float(err[c]), (c, float(got[k][c]), float(ref[k][c]))
+    print(f"[gpu-case] large statistics worst scaled errors over {C_} channels {worst} at {where}", flush=True)
+    for k in got:
+        assert worst[k] <= 1e-5, (k, worst[k], where[k])
+
+
+@pytest.mark.parametrize("layout", ["nchw", "nhwc"])
+def test_structured_values_do_not_bias_long_sums(layout):
+    """Addends that share their low bits (a constant gradient, activations on a grid with exact zeros) make
+    every fp32 addition of a long running sum round the same way; the kernels must not let that add up.
+    64x8192x32x32 fp32: 65536 rows, in the channels-last kernels a thread adds a thousand of them."""
+    N, C_, H, W = 64, 8192, 32, 32
+    wl = Workload(name="structured", N=N, C=C_, H=H, W=W, mode=BS, n_s=16, dtype="f32", layout=layout, data_seed=8,
+                  sampling_seed=3, layer_id=4, epoch=1)
+    print(f"[gpu-case] structured {layout}", flush=True)
+    t = _device_case(wl, structured=True)
+    ch = list(range(0, C_, 16))
+    host = _channels_to_host(t, wl, ch, ("x", "dy", "y", "dx"))
+    vec = lambda k: t[k][ch].cpu().numpy()
+    inp = dict(x=host["x"], dy=host["dy"], gamma=vec("gamma"), beta=vec("beta"))
+    res = dict(y=host["y"], dx=host["dx"], **{k: vec(k) for k in ("save_mean", "save_invstd", "running_mean",
+                                                                  "running_var", "dgamma", "dbeta")})
+    del t
+    torch.cuda.empty_cache()
+    boxes = oracle_boxes(wl)[ch]
+    k = len(ch)
+    f = oracle.forward(inp["x"], inp["gamma"], inp["beta"], boxes, wl.eps, wl.momentum, np.zeros(k), np.ones(k))
+    b = oracle.backward(inp["x"], inp["dy"], inp["gamma"], f["mean"], f["var"], boxes, wl.eps)
+    ref = dict(y=f["y"], save_mean=f["mean"], save_invstd=f["invstd"], running_mean=f["running_mean"],
+               running_var=f["running_var"], dx=b["dx"], dgamma=b["dgamma"], dbeta=b["dbeta"])
+    errs = assert_parity(res, ref, wl, what=f"structured {layout}")
+    print(f"[gpu-case] structured scaled errors {errs}", flush=True)
+    # dbeta is 65536 / 3 for every channel; a biased sum shows here first
+    assert np.max(np.abs(res["dbeta"] / (N * H * W / 3.0) - 1)) <= 2e-6
