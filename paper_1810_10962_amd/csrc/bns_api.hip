@@ -86,6 +86,26 @@ inline bns_status check_layout(const Dims& d, const bns_spec* sp) {
 
 inline bns_status dev(hipError_t e) { return e == hipSuccess ? BNS_OK : BNS_EDEVICE; }
 
+// Launch-choice overrides reachable through bns_set_option / bns_get_option.  Value 0 = automatic;
+// non-temporal masks are given as mask + 1 so that 0 keeps that meaning.
+struct TuningEntry {
+    const char* name;
+    int Tuning::*field;
+    int hi, bias;
+    bool pow2;      // unroll factors: 1, 2 or 4
+};
+const TuningEntry kTuningTable[] = {
+    {"norm_unroll", &Tuning::norm_unroll, 4, 0, true},     {"norm_nt", &Tuning::norm_nt, 4, 1, false},
+    {"dx_unroll", &Tuning::dx_unroll, 4, 0, true},         {"dx_nt", &Tuning::dx_nt, 4, 1, false},
+    {"reduce_unroll", &Tuning::reduce_unroll, 4, 0, true}, {"reduce_nt", &Tuning::reduce_nt, 2, 1, false},
+    {"path", &Tuning::path, 2, 0, false},
+    {"fused_variant", &Tuning::fused_variant, 7, 0, false},
+    {"fused_coop", &Tuning::fused_coop, 1, 0, false},
+    {"split_statistics", &Tuning::split_statistics, 1, 0, false},
+    {"nhwc_blocks", &Tuning::nhwc_blocks, kNhwcBlocksMax, 0, false},
+    {"nhwc_ew_rows", &Tuning::nhwc_ew_rows, 1 << 20, 0, false},
+};
+
 int stats_splits(const Dims& d, const IndexParams& ip, int cg) {
     const int32_t o = g_splits_stats.load();
     if (o > 0) return o;
@@ -466,27 +486,10 @@ bns_status bns_set_option(const char* name, int32_t value) {
         g_channel_group.store(value);
         return BNS_OK;
     }
-    // value 0 = automatic; non-temporal masks are given as mask + 1 so that 0 keeps that meaning
-    struct {
-        const char* n;
-        int* p;
-        int hi, bias;
-        bool pow2;      // unroll factors: 1, 2 or 4
-    } tun[] = {
-        {"norm_unroll", &g_tuning.norm_unroll, 4, 0, true},     {"norm_nt", &g_tuning.norm_nt, 4, 1, false},
-        {"dx_unroll", &g_tuning.dx_unroll, 4, 0, true},         {"dx_nt", &g_tuning.dx_nt, 4, 1, false},
-        {"reduce_unroll", &g_tuning.reduce_unroll, 4, 0, true}, {"reduce_nt", &g_tuning.reduce_nt, 2, 1, false},
-        {"path", &g_tuning.path, 2, 0, false},
-        {"fused_variant", &g_tuning.fused_variant, 7, 0, false},
-        {"fused_coop", &g_tuning.fused_coop, 1, 0, false},
-        {"split_statistics", &g_tuning.split_statistics, 1, 0, false},
-        {"nhwc_blocks", &g_tuning.nhwc_blocks, kNhwcBlocksMax, 0, false},
-        {"nhwc_ew_rows", &g_tuning.nhwc_ew_rows, 1 << 20, 0, false},
-    };
-    for (auto& t : tun)
-        if (!strcmp(name, t.n)) {
+    for (const TuningEntry& t : kTuningTable)
+        if (!strcmp(name, t.name)) {
             if (value > t.hi || (t.pow2 && value == 3)) return BNS_EINVAL;
-            *t.p = value - t.bias;
+            g_tuning.*(t.field) = value - t.bias;
             return BNS_OK;
         }
     return BNS_EINVAL;
@@ -499,7 +502,11 @@ int32_t bns_get_option(const char* name) {
     if (!strcmp(name, "channel_group")) return g_channel_group.load();
     if (!strcmp(name, "last_path_forward")) return g_last_path_forward.load();
     if (!strcmp(name, "last_path_backward")) return g_last_path_backward.load();
-    if (!strcmp(name, "path")) return g_tuning.path;
+    for (const TuningEntry& t : kTuningTable)
+        if (!strcmp(name, t.name)) {
+            const int v = g_tuning.*(t.field) + t.bias;         // as it was set; 0 = automatic
+            return v < 0 ? 0 : v;
+        }
     return -1;
 }
 

@@ -172,6 +172,19 @@ def test_options():
     _expect(bns.BNS_EINVAL, bns.bns_set_option, "splits_stats", 65)
     _expect(bns.BNS_EINVAL, bns.bns_set_option, "nonsense", 1)
     _expect(bns.BNS_EINVAL, bns.bns_set_option, "channel_group", -1)
+    # every documented override reads back as it was set, 0 again after the reset, and rejects values out of range
+    ranges = {"path": 2, "fused_variant": 7, "fused_coop": 1, "split_statistics": 1, "nhwc_blocks": 8192,
+              "nhwc_ew_rows": 1 << 20, "norm_unroll": 4, "dx_unroll": 4, "reduce_unroll": 4, "norm_nt": 4, "dx_nt": 4,
+              "reduce_nt": 2}
+    for name, hi in ranges.items():
+        assert bns.bns_get_option(name) == 0, name
+        for v in (1, hi):
+            bns.bns_set_option(name, v)
+            assert bns.bns_get_option(name) == v, name
+        _expect(bns.BNS_EINVAL, bns.bns_set_option, name, hi + 1)
+        bns.bns_set_option(name, 0)
+        assert bns.bns_get_option(name) == 0, name
+    _expect(bns.BNS_EINVAL, bns.bns_set_option, "norm_unroll", 3)
 
 
 def test_layout_field_is_validated_and_nhwc_limits_are_reported():
