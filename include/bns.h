@@ -238,6 +238,8 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  *                    one group before the next                                   (1..C)
  *   "nhwc_blocks"    blocks that an N x H x W x C reduction launch aims for      (1..8192)
  *   "nhwc_ew_rows"   rows per thread in the N x H x W x C element-wise kernels   (1..2^20)
+ *   "nhwc_small"     2: small N x H x W x C tensors also take the streaming kernels (by default one launch
+ *                    per direction does everything when a thread would walk at most 16 rows)
  *   "norm_unroll", "dx_unroll", "reduce_unroll"   128-bit accesses per thread    (1, 2, 4)
  *   "norm_nt", "dx_nt", "reduce_nt"   non-temporal access mask + 1: bit 0 loads, bit 1 stores
  * Notes on the fused kernels: blocks of a team exchange partial sums through the workspace and wait
@@ -246,7 +248,8 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  * the stream is being captured into a graph (the streaming kernels are captured instead). */
 bns_status bns_set_option(const char* name, int32_t value);
 /* Current value of an option (as set, 0 = automatic); also "last_path_forward" / "last_path_backward":
- * 1 if the last bns_forward / bns_backward took the streaming kernels, 2 if the fused one.
+ * 1 if the last bns_forward / bns_backward took the streaming kernels, 2 if the fused one, 3 if the
+ * one-launch kernel for small N x H x W x C tensors.
  * -1 for an unknown name. */
 int32_t bns_get_option(const char* name);
 

@@ -104,6 +104,7 @@ const TuningEntry kTuningTable[] = {
     {"split_statistics", &Tuning::split_statistics, 1, 0, false},
     {"nhwc_blocks", &Tuning::nhwc_blocks, kNhwcBlocksMax, 0, false},
     {"nhwc_ew_rows", &Tuning::nhwc_ew_rows, 1 << 20, 0, false},
+    {"nhwc_small", &Tuning::nhwc_small, 2, 0, false},
 };
 
 int stats_splits(const Dims& d, const IndexParams& ip, int cg) {
@@ -260,6 +261,12 @@ bns_status bns_forward(const bns_shape* shape, const bns_spec* spec, uint64_t se
     Partial* ws = static_cast<Partial*>(workspace);
     if (nhwc(d)) {
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
+        hipError_t se = hipSuccess;
+        if (launch_nhwc_small_forward(d, ip.shared, x, gamma, beta, eps, momentum, y, save_mean, save_invstd, running_mean,
+                                      running_var, st, &se)) {
+            g_last_path_forward.store(3);
+            return dev(se);
+        }
         g_last_path_forward.store(1);
         if (launch_nhwc_stats(d, ip.shared, x, ws, eps, momentum, save_mean, save_invstd, running_mean, running_var,
                               st) != hipSuccess)
@@ -352,6 +359,11 @@ bns_status bns_backward(const bns_shape* shape, const bns_spec* spec, uint64_t s
     Partial* ws = static_cast<Partial*>(workspace);
     if (nhwc(d)) {
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
+        hipError_t se = hipSuccess;
+        if (launch_nhwc_small_backward(d, ip.shared, x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta, st, &se)) {
+            g_last_path_backward.store(3);
+            return dev(se);
+        }
         g_last_path_backward.store(1);
         if (launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, ws, dgamma, dbeta, st) != hipSuccess) return BNS_EDEVICE;
         return dev(launch_nhwc_dx(d, ip.shared, x, dy, gamma, save_mean, save_invstd, dgamma, dbeta, dx, st));

@@ -35,6 +35,7 @@ struct Tuning {
     int fused_coop = 0;                     // 1: launch the fused kernels with hipLaunchCooperativeKernel
     int split_statistics = 0;               // 1: forward statistics always as partial sums + finalize
     int nhwc_blocks = 0;                    // blocks an N x H x W x C reduction aims for (default kNhwcBlocks)
+    int nhwc_small = 0;                     // 2: never take the one-launch kernels for small N x H x W x C tensors
     int nhwc_ew_rows = 0;                   // rows per row lane in its element-wise kernels (default kNhwcEwRows)
 };
 extern Tuning g_tuning;
@@ -121,6 +122,7 @@ constexpr int kNhwcFill = 2048;        // fewest blocks an element-wise launch a
 constexpr int kNhwcBlocksMax = 8192;   // largest value the "nhwc_blocks" override takes
 constexpr int kNhwcEwRows = 4;         // rows per row lane and block in the element-wise kernels
 constexpr int kNhwcMaxSplits = 2048;   // upper bound on blocks that share one channel's reduction
+constexpr int kNhwcSmallRows = 16;     // rows per row lane up to which one block walks all rows of its channels
 constexpr int kNhwcMaxLaneRows = 1024; // rows one thread accumulates in fp32 before the sums are combined
 size_t nhwc_partial_bytes(const Dims& d);
 hipError_t launch_nhwc_stats(const Dims& d, const bns_box& b, const void* x, Partial* partial, float eps, float momentum,
@@ -133,5 +135,12 @@ hipError_t launch_nhwc_reduce(const Dims& d, const void* x, const void* dy, cons
 hipError_t launch_nhwc_dx(const Dims& d, const bns_box& b, const void* x, const void* dy, const float* gamma,
                           const float* mean, const float* invstd, const float* dgamma, const float* dbeta, void* dx,
                           hipStream_t st);
+// Whole forward / backward in one launch for small tensors; false (nothing launched) when the tensor is not small.
+bool launch_nhwc_small_forward(const Dims& d, const bns_box& b, const void* x, const float* gamma, const float* beta,
+                               float eps, float momentum, void* y, float* save_mean, float* save_invstd,
+                               float* running_mean, float* running_var, hipStream_t st, hipError_t* err);
+bool launch_nhwc_small_backward(const Dims& d, const bns_box& b, const void* x, const void* dy, const float* gamma,
+                                const float* mean, const float* invstd, void* dx, float* dgamma, float* dbeta,
+                                hipStream_t st, hipError_t* err);
 
 }  // namespace bns

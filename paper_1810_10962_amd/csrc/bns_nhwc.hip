@@ -433,6 +433,231 @@ __global__ __launch_bounds__(kBlock) void nhwc_dx_kernel(const T* __restrict__ x
     }
 }
 
+// ---- small tensors: one launch per direction ---------------------------------------------------
+// A block owns TX * V channels and ALL rows, so nothing crosses blocks: pass 1 adds the block's columns
+// (the rows of S forward, all rows backward), one LDS step over the row lanes gives every thread the
+// totals of its columns, pass 2 walks all rows again (the tensor is small: that read comes from cache).
+// At most kNhwcSmallRows rows per row lane, so the fp32 sums are short.
+
+// On return a[], q[] hold the block totals of the thread's columns, the same bits in every row lane.
+template <int V>
+__device__ __forceinline__ void block_column_sums(float (&a)[V], float (&q)[V], float* lds, const Tiling& t,
+                                                  const Lane& l) {
+    const int stride = (1 << t.log2_tx) * V;
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        lds[l.ty * stride + l.tx * V + i] = a[i];
+        lds[(l.TY + l.ty) * stride + l.tx * V + i] = q[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        float sa = lds[l.tx * V + i], sq = lds[l.TY * stride + l.tx * V + i];
+        for (int r = 1; r < l.TY; ++r) {
+            sa += lds[r * stride + l.tx * V + i];
+            sq += lds[(l.TY + r) * stride + l.tx * V + i];
+        }
+        a[i] = sa;
+        q[i] = sq;
+    }
+}
+
+// Eq. 3, Eq. 8 and Eq. 1 in one launch.
+template <typename T, int V>
+__global__ __launch_bounds__(kBlock) void nhwc_small_forward_kernel(
+    const T* __restrict__ x, T* __restrict__ y, const float* __restrict__ gamma, const float* __restrict__ beta, RowSet S,
+    Tiling t, uint32_t M, float eps, float momentum, float* __restrict__ save_mean, float* __restrict__ save_invstd,
+    float* __restrict__ running_mean, float* __restrict__ running_var) {
+    __shared__ float lds[2 * kBlock * V];
+    const Lane l = lane_of(t);
+    const uint32_t TY = uint32_t(l.TY);
+    const size_t col = size_t(l.live ? l.cv : 0) * V;
+    float a[V], q[V], p[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) a[e] = q[e] = p[e] = 0.f;
+    if (l.live) {
+        Vec<T, V> pv[kPivotRows];
+#pragma unroll
+        for (int j = 0; j < kPivotRows; ++j)
+            pv[j].load(x + size_t(sampled_row(S, min(uint32_t(j), S.pivot_rows - 1u))) * t.C + col);
+#pragma unroll
+        for (int j = 0; j < kPivotRows; ++j)
+#pragma unroll
+            for (int e = 0; e < V; ++e) p[e] += uint32_t(j) < S.pivot_rows ? pv[j].f[e] : 0.f;
+#pragma unroll
+        for (int e = 0; e < V; ++e) p[e] = coarse(p[e] * S.inv_pivot_rows);
+        uint32_t i = uint32_t(l.ty);
+        for (; i + 3u * TY < S.rows; i += 4u * TY) {
+            Vec<T, V> v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u].load(x + size_t(sampled_row(S, i + uint32_t(u) * TY)) * t.C + col);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    const float dlt = v[u].f[e] - p[e];
+                    a[e] += dlt;
+                    q[e] = fmaf(dlt, dlt, q[e]);
+                }
+        }
+        for (; i < S.rows; i += TY) {
+            Vec<T, V> v;
+            v.load(x + size_t(sampled_row(S, i)) * t.C + col);
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const float dlt = v.f[e] - p[e];
+                a[e] += dlt;
+                q[e] = fmaf(dlt, dlt, q[e]);
+            }
+        }
+    }
+    block_column_sums<V>(a, q, lds, t, l);
+    if (!l.live) return;
+    float mu[V], sc[V], be[V];
+    const double s = double(S.rows), al = double(momentum);
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        const int c = l.cv * V + e;
+        const double m1 = double(a[e]) / s;
+        const double mean = double(p[e]) + m1;
+        double var = double(q[e]) / s - m1 * m1;      // biased (1/s), Eq. 3
+        if (var < 0.0) var = 0.0;
+        mu[e] = float(mean);
+        const float r = float(1.0 / sqrt(var + double(eps)));
+        sc[e] = gamma[c] * r;
+        be[e] = beta[c];
+        if (l.ty == 0) {
+            save_mean[c] = mu[e];
+            save_invstd[c] = r;
+            if (running_mean) running_mean[c] = float((1.0 - al) * double(running_mean[c]) + al * mean);     // Eq. 8
+            if (running_var) running_var[c] = float((1.0 - al) * double(running_var[c]) + al * var);
+        }
+    }
+    uint32_t r = uint32_t(l.ty);
+    for (; r + 3u * TY < M; r += 4u * TY) {
+        Vec<T, V> v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u].load(x + size_t(r + uint32_t(u) * TY) * t.C + col);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) v[u].f[e] = fmaf(v[u].f[e] - mu[e], sc[e], be[e]);
+            v[u].store_nt(y + size_t(r + uint32_t(u) * TY) * t.C + col);
+        }
+    }
+    for (; r < M; r += TY) {
+        Vec<T, V> v;
+        v.load(x + size_t(r) * t.C + col);
+#pragma unroll
+        for (int e = 0; e < V; ++e) v.f[e] = fmaf(v.f[e] - mu[e], sc[e], be[e]);
+        v.store_nt(y + size_t(r) * t.C + col);
+    }
+}
+
+// The sums of Eq. 5 and Eq. 6 in one launch.
+template <typename T, int V>
+__global__ __launch_bounds__(kBlock) void nhwc_small_backward_kernel(
+    const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx, const float* __restrict__ gamma,
+    const float* __restrict__ mean, const float* __restrict__ invstd, float* __restrict__ dgamma,
+    float* __restrict__ dbeta, RowBox B, Tiling t, uint32_t M, float inv_s) {
+    __shared__ float lds[2 * kBlock * V];
+    const Lane l = lane_of(t);
+    const uint32_t TY = uint32_t(l.TY);
+    const size_t col = size_t(l.live ? l.cv : 0) * V;
+    float a[V], q[V], mu[V], rs[V], ga[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) a[e] = q[e] = mu[e] = rs[e] = ga[e] = 0.f;
+    if (l.live) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            mu[e] = mean[l.cv * V + e];
+            rs[e] = invstd[l.cv * V + e];
+            ga[e] = gamma[l.cv * V + e];
+        }
+        uint32_t r = uint32_t(l.ty);
+        for (; r + TY < M; r += 2u * TY) {
+            Vec<T, V> g[2], v[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const size_t off = size_t(r + uint32_t(u) * TY) * t.C + col;
+                g[u].load(dy + off);
+                v[u].load(x + off);
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    a[e] += g[u].f[e];
+                    q[e] = fmaf(g[u].f[e], v[u].f[e] - mu[e], q[e]);
+                }
+        }
+        for (; r < M; r += TY) {
+            const size_t off = size_t(r) * t.C + col;
+            Vec<T, V> g, v;
+            g.load(dy + off);
+            v.load(x + off);
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                a[e] += g.f[e];
+                q[e] = fmaf(g.f[e], v.f[e] - mu[e], q[e]);
+            }
+        }
+    }
+    block_column_sums<V>(a, q, lds, t, l);
+    if (!l.live) return;
+    float k1[V], k2[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        const int c = l.cv * V + e;
+        const float db = a[e];
+        const float dg = float(double(q[e]) * double(rs[e]));
+        if (l.ty == 0) {
+            dbeta[c] = db;
+            dgamma[c] = dg;
+        }
+        ga[e] *= rs[e];                                  // a = gamma r
+        k1[e] = ga[e] * inv_s * (dg * rs[e]);
+        k2[e] = ga[e] * inv_s * db;
+    }
+    uint32_t r = uint32_t(l.ty);
+    for (; r + TY < M; r += 2u * TY) {
+        Vec<T, V> g[2], v[2];
+        bool in[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint32_t row = r + uint32_t(u) * TY;
+            g[u].load(dy + size_t(row) * t.C + col);
+            in[u] = row_in(B, row);
+            if (in[u]) v[u].load(x + size_t(row) * t.C + col);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (in[u]) {
+#pragma unroll
+                for (int e = 0; e < V; ++e) g[u].f[e] = fmaf(ga[e], g[u].f[e], -fmaf(k1[e], v[u].f[e] - mu[e], k2[e]));
+            } else {
+#pragma unroll
+                for (int e = 0; e < V; ++e) g[u].f[e] *= ga[e];
+            }
+            g[u].store_nt(dx + size_t(r + uint32_t(u) * TY) * t.C + col);
+        }
+    }
+    for (; r < M; r += TY) {
+        Vec<T, V> g;
+        g.load(dy + size_t(r) * t.C + col);
+        if (row_in(B, r)) {
+            Vec<T, V> v;
+            v.load(x + size_t(r) * t.C + col);
+#pragma unroll
+            for (int e = 0; e < V; ++e) g.f[e] = fmaf(ga[e], g.f[e], -fmaf(k1[e], v.f[e] - mu[e], k2[e]));
+        } else {
+#pragma unroll
+            for (int e = 0; e < V; ++e) g.f[e] *= ga[e];
+        }
+        g.store_nt(dx + size_t(r) * t.C + col);
+    }
+}
+
 inline uint32_t ceil_div_u(uint32_t a, uint32_t b) { return uint32_t((uint64_t(a) + b - 1) / b); }
 
 inline int column_vec(const Dims& d) { return (d.dtype == BNS_BF16 && d.C % 8 == 0) ? 8 : (d.C % 4 == 0) ? 4 : 1; }
@@ -491,6 +716,37 @@ RowSet make_rowset(const Dims& d, const bns_box& b) {
     s.pivot_rows = s.rows < uint32_t(kPivotRows) ? s.rows : uint32_t(kPivotRows);
     s.inv_pivot_rows = 1.0f / float(s.pivot_rows);
     return s;
+}
+
+RowBox make_rowbox(const Dims& d, const bns_box& b) {
+    RowBox B;
+    B.n0 = uint32_t(b.n0);
+    B.n1 = uint32_t(b.n0 + b.n_cnt);
+    B.h0 = uint32_t(b.h0);
+    B.h1 = uint32_t(b.h0 + b.h_cnt);
+    B.w0 = uint32_t(b.w0);
+    B.w1 = uint32_t(b.w0 + b.w_cnt);
+    B.hw_div = make_fastdiv(uint32_t(d.HW));
+    B.w_div = make_fastdiv(uint32_t(d.W));
+    return B;
+}
+
+// Tiling of the one-launch kernels: column lanes for 128 contiguous bytes of a row, every other lane
+// on rows, one block per tile of channels.  False when a row lane would get more than kNhwcSmallRows.
+bool small_tiling(const Dims& d, Tiling* t) {
+    if (g_tuning.nhwc_small == 2) return false;
+    const int V = column_vec(d);
+    t->C = d.C;
+    t->CV = d.C / V;
+    const int want = 128 / (V * (d.dtype == BNS_F32 ? 4 : 2));
+    int l = 0;
+    while ((1 << l) < t->CV && (1 << l) < want) ++l;
+    t->log2_tx = l;
+    t->splits = 1;
+    const uint32_t M = uint32_t(d.N) * uint32_t(d.HW);
+    t->rows_per_block = M;
+    const uint32_t TY = uint32_t(kBlock >> l);
+    return ceil_div_u(M, TY) <= uint32_t(kNhwcSmallRows);
 }
 
 template <int V>
@@ -566,15 +822,7 @@ hipError_t launch_nhwc_dx(const Dims& d, const bns_box& b, const void* x, const 
                           hipStream_t st) {
     const uint32_t M = uint32_t(d.N) * uint32_t(d.HW);
     const Tiling t = make_tiling(d, M, 0, true);
-    RowBox B;
-    B.n0 = uint32_t(b.n0);
-    B.n1 = uint32_t(b.n0 + b.n_cnt);
-    B.h0 = uint32_t(b.h0);
-    B.h1 = uint32_t(b.h0 + b.h_cnt);
-    B.w0 = uint32_t(b.w0);
-    B.w1 = uint32_t(b.w0 + b.w_cnt);
-    B.hw_div = make_fastdiv(uint32_t(d.HW));
-    B.w_div = make_fastdiv(uint32_t(d.W));
+    const RowBox B = make_rowbox(d, b);
     const double s = double(b.n_cnt) * double(b.h_cnt) * double(b.w_cnt);
     return dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
@@ -584,6 +832,43 @@ hipError_t launch_nhwc_dx(const Dims& d, const bns_box& b, const void* x, const 
                            float(1.0 / s));
         return hipGetLastError();
     });
+}
+
+bool launch_nhwc_small_forward(const Dims& d, const bns_box& b, const void* x, const float* gamma, const float* beta,
+                               float eps, float momentum, void* y, float* save_mean, float* save_invstd,
+                               float* running_mean, float* running_var, hipStream_t st, hipError_t* err) {
+    Tiling t;
+    if (!small_tiling(d, &t)) return false;
+    const RowSet S = make_rowset(d, b);
+    const uint32_t M = uint32_t(d.N) * uint32_t(d.HW);
+    *err = dispatch_nhwc(d, [&](auto ty, auto vt) {
+        using T = decltype(ty);
+        constexpr int V = decltype(vt)::value;
+        hipLaunchKernelGGL((nhwc_small_forward_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st,
+                           static_cast<const T*>(x), static_cast<T*>(y), gamma, beta, S, t, M, eps, momentum, save_mean,
+                           save_invstd, running_mean, running_var);
+        return hipGetLastError();
+    });
+    return true;
+}
+
+bool launch_nhwc_small_backward(const Dims& d, const bns_box& b, const void* x, const void* dy, const float* gamma,
+                                const float* mean, const float* invstd, void* dx, float* dgamma, float* dbeta,
+                                hipStream_t st, hipError_t* err) {
+    Tiling t;
+    if (!small_tiling(d, &t)) return false;
+    const RowBox B = make_rowbox(d, b);
+    const uint32_t M = uint32_t(d.N) * uint32_t(d.HW);
+    const double s = double(b.n_cnt) * double(b.h_cnt) * double(b.w_cnt);
+    *err = dispatch_nhwc(d, [&](auto ty, auto vt) {
+        using T = decltype(ty);
+        constexpr int V = decltype(vt)::value;
+        hipLaunchKernelGGL((nhwc_small_backward_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st,
+                           static_cast<const T*>(x), static_cast<const T*>(dy), static_cast<T*>(dx), gamma, mean, invstd,
+                           dgamma, dbeta, B, t, M, float(1.0 / s));
+        return hipGetLastError();
+    });
+    return true;
 }
 
 }  // namespace bns

@@ -12,6 +12,15 @@ from parity import assert_parity, oracle_boxes, oracle_reference, scaled_err
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=["auto", "streaming"])
+def kernel_choice(request):
+    """Every test runs twice: with the default choice (small tensors take the one-launch kernels) and with the
+    streaming kernels forced for every size."""
+    bns.bns_set_option("nhwc_small", 0 if request.param == "auto" else 2)
+    yield request.param
+    bns.bns_set_option("nhwc_small", 0)
+
+
 def _announce(msg):
     print(f"[gpu-case] nhwc {msg}", flush=True)
 
@@ -258,3 +267,15 @@ def test_hip_graph_capture_and_replay():
         got = buf.results()
         for k in eager:
             assert (got[k] == eager[k]).all(), f"replay {replay}: {k}"
+
+
+def test_small_tensors_take_one_launch_per_direction(kernel_choice):
+    wl = workloads.WORKLOADS["micro_a_fs"].replace(layout="nhwc")
+    inp = workloads.make_inputs(wl)
+    res = bns.run_workload(wl, inp)
+    want = 3 if kernel_choice == "auto" else 1
+    assert bns.bns_get_option("last_path_forward") == want and bns.bns_get_option("last_path_backward") == want
+    assert_parity(res, oracle_reference(wl, inp), wl, what="micro_a_fs nhwc", inp=inp)
+    big = workloads.WORKLOADS["cifar_fs"].replace(layout="nhwc", N=16)
+    bns.run_workload(big, workloads.make_inputs(big))
+    assert bns.bns_get_option("last_path_forward") == 1 and bns.bns_get_option("last_path_backward") == 1
