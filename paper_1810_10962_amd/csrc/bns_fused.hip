@@ -133,6 +133,8 @@ struct FusedArgs {
     int32_t c0, cg;
     int32_t T, num_teams;
     uint32_t tot;   // vectors per channel: N * HW / V
+    uint32_t s_cnt; // |S| per channel
+    FastDiv patch_div, pw_div;   // h_cnt * w_cnt and w_cnt of S: sampled element q -> (n, ph, pw)
     uint32_t stamp0;
     float eps, momentum, inv_s;
     double s;       // |S| per channel
@@ -255,9 +257,21 @@ __device__ __forceinline__ bool in_hw(const bns_box& b, uint32_t h, uint32_t w) 
 }
 
 // ---------------------------------------------------------------------------------------
+// sampled elements a thread reads ahead of its vectors (more: in a loop after them); registers decide how many
+constexpr int patch_loads(int kmax) { return kmax >= 50 ? 2 : 4; }
+
+// Offset of sampled element q of a channel from its first sampled element.
+__device__ __forceinline__ size_t patch_offset(const FusedArgs& A, uint32_t q, size_t nstride) {
+    const uint32_t n = fdiv(q, A.patch_div);
+    const uint32_t r = q - n * A.patch_div.d;
+    const uint32_t ph = fdiv(r, A.pw_div);
+    return n * nstride + size_t(ph) * A.W + (r - ph * A.pw_div.d);
+}
+
 // Forward: Eq. 3 + Eq. 8 + Eq. 1 with x read once
 // ---------------------------------------------------------------------------------------
-template <typename T, int V, int KMAX, int NT>
+// PATCH: S is a patch of each plane (host guarantee: h_cnt * w_cnt < H * W); else S is whole planes.
+template <typename T, int V, int KMAX, int NT, bool PATCH>
 __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
     typedef RawVec<T, V> RV;
     __shared__ float red[2 * (NT / kWave)];
@@ -282,8 +296,23 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
         const bns_box b = box_of_channel(A.ip, c);
         const T* xc = x + size_t(c) * A.HW;
         T* yc = y + size_t(c) * A.HW;
-        const float pivot = load_scalar<T>(xc + size_t(b.n0) * nstride + size_t(b.h0) * A.W + b.w0);
-        const bool full_hw = b.h_cnt * b.w_cnt == A.HW;
+        const T* first = xc + size_t(b.n0) * nstride + size_t(b.h0) * A.W + b.w0;       // first sampled element
+        const float pivot = load_scalar<T>(first);
+
+        // A patch of each plane (Feature Sampling): the sampled elements are few and scattered inside the
+        // vectors, so they are read on their own, element q = (n, ph, pw) by thread q mod (T * NT), BEFORE the
+        // vectors of the channel.  Loads return in order, so the statistics and the exchange then run while
+        // the vectors are still on their way, and no vector has to be masked element by element.
+        constexpr int kPatchLoads = patch_loads(KMAX);
+        float pe[PATCH ? kPatchLoads : 1];
+        const uint32_t q0 = uint32_t(j) * NT + threadIdx.x;
+        if constexpr (PATCH) {
+#pragma unroll
+            for (int m = 0; m < kPatchLoads; ++m) {
+                const uint32_t q = q0 + uint32_t(m) * step;
+                pe[m] = q < A.s_cnt ? load_scalar<T>(first + patch_offset(A, q, nstride)) : pivot;
+            }
+        }
 
         typename RV::raw_t v[KMAX];
         const uint32_t ia = opaque(beg + threadIdx.x);
@@ -296,42 +325,36 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
             }
         }
         float s1 = 0.f, s2 = 0.f;
-        const uint32_t ib = opaque(beg + threadIdx.x);
+        if constexpr (!PATCH) {                                     // whole planes of some samples: from the registers
+            const uint32_t ib = opaque(beg + threadIdx.x);
 #pragma unroll
-        for (int k = 0; k < KMAX; ++k) {
-            const uint32_t i = ib + uint32_t(k) * step;
-            if (i < end) {
-                const uint32_t n = fdiv(i, A.hwv_div);
-                if (n >= uint32_t(b.n0) && n < uint32_t(b.n0 + b.n_cnt)) {
-                    float f[V];
-                    RV::unpack(v[k], f);
-                    if (full_hw) {
+            for (int k = 0; k < KMAX; ++k) {
+                const uint32_t i = ib + uint32_t(k) * step;
+                if (i < end) {
+                    const uint32_t n = fdiv(i, A.hwv_div);
+                    if (n >= uint32_t(b.n0) && n < uint32_t(b.n0 + b.n_cnt)) {
+                        float f[V];
+                        RV::unpack(v[k], f);
 #pragma unroll
                         for (int e = 0; e < V; ++e) {
                             const float d = f[e] - pivot;
                             s1 += d;
                             s2 = fmaf(d, d, s2);
                         }
-                    } else {
-                        const uint32_t e0 = (i - n * hwv) * V;
-                        if (e0 + V > uint32_t(b.h0) * A.W && e0 < uint32_t(b.h0 + b.h_cnt) * A.W) {
-                            uint32_t h = fdiv(e0, A.w_div);
-                            uint32_t w = e0 - h * uint32_t(A.W);
-#pragma unroll
-                            for (int e = 0; e < V; ++e) {
-                                if (in_hw(b, h, w)) {
-                                    const float d = f[e] - pivot;
-                                    s1 += d;
-                                    s2 = fmaf(d, d, s2);
-                                }
-                                if (++w == uint32_t(A.W)) {
-                                    w = 0;
-                                    ++h;
-                                }
-                            }
-                        }
                     }
                 }
+            }
+        } else {
+#pragma unroll
+            for (int m = 0; m < kPatchLoads; ++m) {                 // padded with the pivot: d = 0
+                const float d = pe[m] - pivot;
+                s1 += d;
+                s2 = fmaf(d, d, s2);
+            }
+            for (uint32_t q = q0 + uint32_t(kPatchLoads) * step; q < A.s_cnt; q += step) {
+                const float d = load_scalar<T>(first + patch_offset(A, q, nstride)) - pivot;
+                s1 += d;
+                s2 = fmaf(d, d, s2);
             }
         }
         block_allsum2<NT>(s1, s2, red);
@@ -504,11 +527,12 @@ constexpr Variant kVariants[] = {{64, 1}, {128, 2}, {256, 4}, {512, 8}, {512, 16
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 template <typename T, int V>
-const void* kernel_ptr(bool backward, int variant) {
-#define BNS_CASE(I, NT_, K_)                                                                        \
-    case I:                                                                                         \
-        return backward ? reinterpret_cast<const void*>(&fused_backward_kernel<T, V, K_, NT_>)      \
-                        : reinterpret_cast<const void*>(&fused_forward_kernel<T, V, K_, NT_>);
+const void* kernel_ptr(int kind, int variant) {       // kind 0: forward, whole planes; 1: backward; 2: forward, patches
+#define BNS_CASE(I, NT_, K_)                                                                                  \
+    case I:                                                                                                   \
+        return kind == 1   ? reinterpret_cast<const void*>(&fused_backward_kernel<T, V, K_, NT_>)             \
+               : kind == 2 ? reinterpret_cast<const void*>(&fused_forward_kernel<T, V, K_, NT_, true>)        \
+                           : reinterpret_cast<const void*>(&fused_forward_kernel<T, V, K_, NT_, false>);
     switch (variant) {
         BNS_CASE(0, 64, 1)
         BNS_CASE(1, 128, 2)
@@ -522,17 +546,17 @@ const void* kernel_ptr(bool backward, int variant) {
     return nullptr;
 }
 
-const void* kernel_for(const Dims& d, bool backward, int variant) {
-    if (d.dtype == BNS_F32) return d.vec == 4 ? kernel_ptr<float, 4>(backward, variant) : kernel_ptr<float, 1>(backward, variant);
-    if (d.vec == 8) return kernel_ptr<bf16_t, 8>(backward, variant);
-    if (d.vec == 4) return kernel_ptr<bf16_t, 4>(backward, variant);
-    return kernel_ptr<bf16_t, 1>(backward, variant);
+const void* kernel_for(const Dims& d, int kind, int variant) {
+    if (d.dtype == BNS_F32) return d.vec == 4 ? kernel_ptr<float, 4>(kind, variant) : kernel_ptr<float, 1>(kind, variant);
+    if (d.vec == 8) return kernel_ptr<bf16_t, 8>(kind, variant);
+    if (d.vec == 4) return kernel_ptr<bf16_t, 4>(kind, variant);
+    return kernel_ptr<bf16_t, 1>(kind, variant);
 }
 
 struct DeviceInfo {
     int cus = 0;
     int coop = 0;
-    int blocks_per_cu[2][5][kNumVariants];  // [backward][type/vec combo][variant], 0 = not queried yet
+    int blocks_per_cu[3][5][kNumVariants];  // [kernel kind][type/vec combo][variant], 0 = not queried yet
 };
 DeviceInfo g_dev[16];
 std::mutex g_dev_mutex;   // guards g_dev: launches may come from several host threads
@@ -568,6 +592,7 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     const uint32_t hwv = uint32_t(d.HW / d.vec);
     const uint32_t tot = uint32_t(d.N) * hwv;
     const int combo = combo_index(d);
+    const int kind = backward ? 1 : (ip.shared.h_cnt * ip.shared.w_cnt == d.HW ? 0 : 2);
 
     // Choice of variant and team size, from sweeps on MI355X (64x256x56x56 fp32/bf16, 128x64x32x32,
     // 130x128x28x28):
@@ -587,10 +612,10 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     auto plan_for = [&](int v, Plan* out) -> hipError_t {
         const Variant& va = kVariants[v];
         out->v = -1;
-        int& bpc = di.blocks_per_cu[backward ? 1 : 0][combo][v];
+        int& bpc = di.blocks_per_cu[kind][combo][v];
         if (bpc == 0) {
             int nb = 0;
-            const hipError_t oe = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel_for(d, backward, v), va.nt, 0);
+            const hipError_t oe = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel_for(d, kind, v), va.nt, 0);
             if (oe != hipSuccess) return oe;
             bpc = nb > 0 ? nb : -1;
         }
@@ -693,6 +718,9 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     A.momentum = momentum;
     const bns_box& b = ip.shared;
     A.s = double(b.n_cnt) * double(b.h_cnt) * double(b.w_cnt);
+    A.s_cnt = uint32_t(b.n_cnt) * uint32_t(b.h_cnt) * uint32_t(b.w_cnt);
+    A.patch_div = make_fastdiv(uint32_t(b.h_cnt) * uint32_t(b.w_cnt));
+    A.pw_div = make_fastdiv(uint32_t(b.w_cnt));
     A.inv_s = float(1.0 / A.s);
 
     const int grid = A.num_teams * bestT;
@@ -703,9 +731,9 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     }
     void* params[] = {&A};
     if (g_tuning.fused_coop)
-        return hipLaunchCooperativeKernel(kernel_for(d, backward, best), dim3(grid), dim3(kVariants[best].nt), params,
+        return hipLaunchCooperativeKernel(kernel_for(d, kind, best), dim3(grid), dim3(kVariants[best].nt), params,
                                           0, st);
-    return hipLaunchKernel(kernel_for(d, backward, best), dim3(grid), dim3(kVariants[best].nt), params, 0, st);
+    return hipLaunchKernel(kernel_for(d, kind, best), dim3(grid), dim3(kVariants[best].nt), params, 0, st);
 }
 
 }  // namespace bns
