@@ -38,6 +38,10 @@ MEASURED_TRAFFIC = {
     ("imagenet_bs", "normalize"): 411248852,
     ("imagenet_bs", "dx"): 436968405,
     ("imagenet_bs", "reduce"): 411114431,
+    # profiles/imagenet_bs_nhwc_f32_hbm_traffic.md
+    ("imagenet_bs_nhwc", "normalize"): 411111929,
+    ("imagenet_bs_nhwc", "dx"): 436805623,
+    ("imagenet_bs_nhwc", "reduce"): 412120265,
 }
 
 
