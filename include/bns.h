@@ -77,8 +77,8 @@ typedef enum { BNS_NCHW = 0, BNS_NHWC = 1 } bns_layout; /* memory order of x, y,
 /* Tensor extents.  For VDN, N counts virtual + real samples (virtual first).
  * Limits: N <= 65535, C <= 2^24, H*W < 2^31, N*H*W < 2^31, C*H*W < 2^31.
  * BNS_NHWC: every channel shares one location set there, so Feature Sampling with
- * fs_per_channel = 1 and the bns_*_mixed calls return BNS_EUNSUPPORTED; the other modes, both
- * storage types and every stage call are available (streaming kernels only). */
+ * fs_per_channel = 1 returns BNS_EUNSUPPORTED; the other modes, the bns_*_mixed calls, both storage
+ * types and every stage call are available. */
 typedef struct {
     int32_t N, C, H, W;
     int32_t dtype;  /* bns_dtype */

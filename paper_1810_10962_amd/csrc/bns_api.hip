@@ -76,7 +76,7 @@ inline size_t tensor_bytes(const Dims& d) { return size_t(d.N) * d.C * d.HW * el
 inline size_t partial_bytes(const Dims& d) { return (size_t(d.C) * kMaxSplits * sizeof(Partial) + 255) & ~size_t(255); }
 inline bool nhwc(const Dims& d) { return d.layout == BNS_NHWC; }
 inline size_t workspace_need(const Dims& d) {
-    if (nhwc(d)) return nhwc_partial_bytes(d);
+    if (nhwc(d)) return 2 * nhwc_partial_bytes(d);   // [sums S][sums V]
     return 2 * partial_bytes(d) + kSlotBytes;   // [sums S][sums V][slots]
 }
 // N x H x W x C: one location set for all channels
@@ -405,7 +405,6 @@ bns_status check_mixed(const bns_shape* shape, const bns_spec* spec, int32_t n_v
     bns_status s = check_shape(shape, d);
     if (s != BNS_OK) return s;
     if (!spec || n_v < 1 || n_v >= shape->N) return BNS_EINVAL;
-    if (nhwc(*d)) return BNS_EUNSUPPORTED;
     if (!(mix_beta >= 0.f && mix_beta <= 1.f)) return BNS_EINVAL;
     if (spec->mode == BNS_VDN) return BNS_EINVAL;            // the real part needs a sampling strategy
     bns_shape real = *shape;
@@ -438,8 +437,15 @@ bns_status bns_forward_mixed(const bns_shape* shape, const bns_spec* spec, uint6
     if (overlap(x, tensor_bytes(d), y, tensor_bytes(d))) return BNS_EINVAL;
     if (!(eps >= 0.f) || !(momentum >= 0.f && momentum <= 1.f)) return BNS_EINVAL;
     if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
+    if ((s = check_layout(d, spec)) != BNS_OK) return s;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const IndexParams ip_s = make_index_params_mixed(*shape, *spec, seed, n_v);
+    if (nhwc(d)) {
+        if (launch_nhwc_stats_mixed(d, ip_s.shared, n_v, x, static_cast<Partial*>(workspace), mix_beta, eps, momentum,
+                                    save_mean, save_invstd, save_mean_parts, running_mean, running_var, st) != hipSuccess)
+            return BNS_EDEVICE;
+        return dev(launch_nhwc_normalize(d, x, gamma, beta, save_mean, save_invstd, y, st));
+    }
     const IndexParams ip_v = make_index_params_virtual(*shape, n_v);
     Partial* ws_s = static_cast<Partial*>(workspace);
     Partial* ws_v = reinterpret_cast<Partial*>(static_cast<char*>(workspace) + partial_bytes(d));
@@ -466,8 +472,16 @@ bns_status bns_backward_mixed(const bns_shape* shape, const bns_spec* spec, uint
     const size_t tb = tensor_bytes(d);
     if (overlap(dx, tb, x, tb) || overlap(dx, tb, dy, tb)) return BNS_EINVAL;
     if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
+    if ((s = check_layout(d, spec)) != BNS_OK) return s;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const IndexParams ip_s = make_index_params_mixed(*shape, *spec, seed, n_v);
+    if (nhwc(d)) {
+        if (launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, static_cast<Partial*>(workspace), dgamma, dbeta, st) !=
+            hipSuccess)
+            return BNS_EDEVICE;
+        return dev(launch_nhwc_dx_mixed(d, ip_s.shared, n_v, mix_beta, x, dy, gamma, save_invstd, dgamma, dbeta,
+                                        save_mean_parts, dx, st));
+    }
     s = reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, static_cast<Partial*>(workspace), 0, d.C, st);
     if (s != BNS_OK) return s;
     const bns_box& b = ip_s.shared;

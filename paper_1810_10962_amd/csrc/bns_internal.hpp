@@ -135,6 +135,14 @@ hipError_t launch_nhwc_reduce(const Dims& d, const void* x, const void* dy, cons
 hipError_t launch_nhwc_dx(const Dims& d, const bns_box& b, const void* x, const void* dy, const float* gamma,
                           const float* mean, const float* invstd, const float* dgamma, const float* dbeta, void* dx,
                           hipStream_t st);
+// Eq. 4 in this layout: statistics of the sampled real set and of the first n_v samples, blended; dx with
+// per-set weights.  `partial` then holds two regions of nhwc_partial_bytes(d).
+hipError_t launch_nhwc_stats_mixed(const Dims& d, const bns_box& b, int n_v, const void* x, Partial* partial,
+                                   float mix_beta, float eps, float momentum, float* save_mean, float* save_invstd,
+                                   float* mean_parts, float* running_mean, float* running_var, hipStream_t st);
+hipError_t launch_nhwc_dx_mixed(const Dims& d, const bns_box& b, int n_v, float mix_beta, const void* x, const void* dy,
+                                const float* gamma, const float* invstd, const float* dgamma, const float* dbeta,
+                                const float* mean_parts, void* dx, hipStream_t st);
 // Whole forward / backward in one launch for small tensors; false (nothing launched) when the tensor is not small.
 bool launch_nhwc_small_forward(const Dims& d, const bns_box& b, const void* x, const float* gamma, const float* beta,
                                float eps, float momentum, void* y, float* save_mean, float* save_invstd,

@@ -264,6 +264,18 @@ __device__ __forceinline__ bool sum_splits(const Partial* __restrict__ partial, 
     return true;
 }
 
+// The pivot of channel c, the same expression as in nhwc_stats_partial_kernel.
+template <typename T>
+__device__ __forceinline__ float column_pivot(const T* __restrict__ x, const RowSet& S, int C, int c) {
+    float pv[kPivotRows], psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < kPivotRows; ++j)
+        pv[j] = load_scalar<T>(x + size_t(sampled_row(S, min(uint32_t(j), S.pivot_rows - 1u))) * C + c);
+#pragma unroll
+    for (int j = 0; j < kPivotRows; ++j) psum += uint32_t(j) < S.pivot_rows ? pv[j] : 0.f;
+    return coarse(psum * S.inv_pivot_rows);
+}
+
 template <typename T>
 __global__ __launch_bounds__(kBlock) void nhwc_stats_finalize_kernel(
     const T* __restrict__ x, const Partial* __restrict__ partial, RowSet S, int C, int splits, float eps, float momentum,
@@ -273,13 +285,7 @@ __global__ __launch_bounds__(kBlock) void nhwc_stats_finalize_kernel(
     int c;
     double s1, s2;
     if (!sum_splits(partial, C, splits, lds, c, s1, s2)) return;
-    float pv[kPivotRows], psum = 0.f;
-#pragma unroll
-    for (int j = 0; j < kPivotRows; ++j)
-        pv[j] = load_scalar<T>(x + size_t(sampled_row(S, min(uint32_t(j), S.pivot_rows - 1u))) * C + c);
-#pragma unroll
-    for (int j = 0; j < kPivotRows; ++j) psum += uint32_t(j) < S.pivot_rows ? pv[j] : 0.f;
-    const double pivot = double(coarse(psum * S.inv_pivot_rows));
+    const double pivot = double(column_pivot(x, S, C, c));
     const double s = double(S.rows);
     const double m1 = s1 / s;
     const double mean = pivot + m1;
@@ -288,6 +294,41 @@ __global__ __launch_bounds__(kBlock) void nhwc_stats_finalize_kernel(
     save_mean[c] = float(mean);
     save_invstd[c] = float(1.0 / sqrt(var + double(eps)));
     const double al = double(momentum);                       // Eq. 8
+    if (running_mean) running_mean[c] = float((1.0 - al) * double(running_mean[c]) + al * mean);
+    if (running_var) running_var[c] = float((1.0 - al) * double(running_var[c]) + al * var);
+}
+
+// "VDN + sampling" (Eq. 4): the sums of the sampled real set S and of the virtual set V (the first n_v
+// samples), each into its own E and Var by Eq. 3, then the blend.  Two passes of sum_splits over the same
+// LDS, every thread taking part in both.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void nhwc_stats_finalize_mixed_kernel(
+    const T* __restrict__ x, const Partial* __restrict__ partial_s, int splits_s, const Partial* __restrict__ partial_v,
+    int splits_v, RowSet S, RowSet Vs, int C, float mix_beta, float eps, float momentum, float* __restrict__ save_mean,
+    float* __restrict__ save_invstd, float* __restrict__ mean_parts, float* __restrict__ running_mean,
+    float* __restrict__ running_var) {
+    __shared__ double lds[2 * kBlock];
+    int c;
+    double a1 = 0.0, a2 = 0.0, v1 = 0.0, v2 = 0.0;
+    const bool lead_s = sum_splits(partial_s, C, splits_s, lds, c, a1, a2);
+    __syncthreads();                                            // the leaders have read their sums
+    const bool lead_v = sum_splits(partial_v, C, splits_v, lds, c, v1, v2);
+    if (!lead_s || !lead_v) return;
+    const double ss = double(S.rows), sv = double(Vs.rows);
+    const double ms = a1 / ss, mv = v1 / sv;
+    const double e_s = double(column_pivot(x, S, C, c)) + ms;
+    const double e_v = double(column_pivot(x, Vs, C, c)) + mv;
+    double var_s = a2 / ss - ms * ms, var_v = v2 / sv - mv * mv;
+    if (var_s < 0.0) var_s = 0.0;
+    if (var_v < 0.0) var_v = 0.0;
+    const double bm = double(mix_beta);
+    const double mean = bm * e_v + (1.0 - bm) * e_s;            // Eq. 4, X = E
+    const double var = bm * var_v + (1.0 - bm) * var_s;         // Eq. 4, X = Var
+    save_mean[c] = float(mean);
+    save_invstd[c] = float(1.0 / sqrt(var + double(eps)));
+    mean_parts[c] = float(e_v);
+    mean_parts[C + c] = float(e_s);
+    const double al = double(momentum);                         // Eq. 8
     if (running_mean) running_mean[c] = float((1.0 - al) * double(running_mean[c]) + al * mean);
     if (running_var) running_var[c] = float((1.0 - al) * double(running_var[c]) + al * var);
 }
@@ -425,6 +466,53 @@ __global__ __launch_bounds__(kBlock) void nhwc_dx_kernel(const T* __restrict__ x
             v.load_nt(x + size_t(r) * t.C + col);
 #pragma unroll
             for (int e = 0; e < V; ++e) g.f[e] = fmaf(a[e], g.f[e], -fmaf(k1[e], v.f[e] - mu[e], k2[e]));
+        } else {
+#pragma unroll
+            for (int e = 0; e < V; ++e) g.f[e] *= a[e];
+        }
+        g.store_nt(dx + size_t(r) * t.C + col);
+    }
+}
+
+// Backward of Eq. 4: rows of the first n_v samples belong to the virtual set (weight w_v = mix_beta / s_v,
+// centre E[x_v]), rows of S to the sampled real set (w_s = (1 - mix_beta) / s_s, centre E[x_s]):
+//   dx = a g - a w (dbeta + r dgamma (x - E_set)),   dx = a g elsewhere.
+template <typename T, int V>
+__global__ __launch_bounds__(kBlock) void nhwc_dx_mixed_kernel(
+    const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx, const float* __restrict__ gamma,
+    const float* __restrict__ invstd, const float* __restrict__ dgamma, const float* __restrict__ dbeta,
+    const float* __restrict__ centre_v, const float* __restrict__ centre_s, RowBox B, uint32_t virtual_rows, float w_v,
+    float w_s, Tiling t, uint32_t M) {
+    const Lane l = lane_of(t);
+    if (!l.live) return;
+    const uint32_t r0 = uint32_t(l.k) * t.rows_per_block;
+    const uint32_t r1 = min(r0 + t.rows_per_block, M);
+    const uint32_t TY = uint32_t(l.TY);
+    float a[V], cv_[V], cs_[V], k1[V], k2[V];          // k1, k2 per unit weight
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        const int c = l.cv * V + e;
+        const float r = invstd[c];
+        a[e] = gamma[c] * r;
+        cv_[e] = centre_v[c];
+        cs_[e] = centre_s[c];
+        k1[e] = a[e] * (dgamma[c] * r);
+        k2[e] = a[e] * dbeta[c];
+    }
+    const size_t col = size_t(l.cv) * V;
+    for (uint32_t r = r0 + uint32_t(l.ty); r < r1; r += TY) {
+        Vec<T, V> g;
+        g.load_nt(dy + size_t(r) * t.C + col);
+        const bool virt = r < virtual_rows;
+        if (virt || row_in(B, r)) {
+            Vec<T, V> v;
+            v.load_nt(x + size_t(r) * t.C + col);
+            const float w = virt ? w_v : w_s;
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const float centre = virt ? cv_[e] : cs_[e];
+                g.f[e] = fmaf(a[e], g.f[e], -w * fmaf(k1[e], v.f[e] - centre, k2[e]));
+            }
         } else {
 #pragma unroll
             for (int e = 0; e < V; ++e) g.f[e] *= a[e];
@@ -869,6 +957,50 @@ bool launch_nhwc_small_backward(const Dims& d, const bns_box& b, const void* x, 
         return hipGetLastError();
     });
     return true;
+}
+
+// Eq. 4 forward statistics: `partial` holds two regions of nhwc_partial_bytes(d) each (set S, then set V).
+hipError_t launch_nhwc_stats_mixed(const Dims& d, const bns_box& b, int n_v, const void* x, Partial* partial,
+                                   float mix_beta, float eps, float momentum, float* save_mean, float* save_invstd,
+                                   float* mean_parts, float* running_mean, float* running_var, hipStream_t st) {
+    const RowSet S = make_rowset(d, b);
+    const bns_box vb{0, n_v, 0, d.H, 0, d.W};
+    const RowSet Vs = make_rowset(d, vb);
+    const Tiling ts = make_tiling(d, S.rows), tv = make_tiling(d, Vs.rows);
+    Partial* partial_v = reinterpret_cast<Partial*>(reinterpret_cast<char*>(partial) + nhwc_partial_bytes(d));
+    return dispatch_nhwc(d, [&](auto ty, auto vt) {
+        using T = decltype(ty);
+        constexpr int V = decltype(vt)::value;
+        hipLaunchKernelGGL((nhwc_stats_partial_kernel<T, V>), dim3(grid_of(ts)), dim3(kBlock), 0, st,
+                           static_cast<const T*>(x), partial, S, ts);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((nhwc_stats_partial_kernel<T, V>), dim3(grid_of(tv)), dim3(kBlock), 0, st,
+                           static_cast<const T*>(x), partial_v, Vs, tv);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        hipLaunchKernelGGL((nhwc_stats_finalize_mixed_kernel<T>), dim3(ceil_div_u(uint32_t(d.C), kFinCh)), dim3(kBlock), 0,
+                           st, static_cast<const T*>(x), partial, ts.splits, partial_v, tv.splits, S, Vs, d.C, mix_beta, eps,
+                           momentum, save_mean, save_invstd, mean_parts, running_mean, running_var);
+        return hipGetLastError();
+    });
+}
+
+hipError_t launch_nhwc_dx_mixed(const Dims& d, const bns_box& b, int n_v, float mix_beta, const void* x, const void* dy,
+                                const float* gamma, const float* invstd, const float* dgamma, const float* dbeta,
+                                const float* mean_parts, void* dx, hipStream_t st) {
+    const uint32_t M = uint32_t(d.N) * uint32_t(d.HW);
+    const Tiling t = make_tiling(d, M, 0, true);
+    const RowBox B = make_rowbox(d, b);
+    const float w_s = float((1.0 - double(mix_beta)) / (double(b.n_cnt) * double(b.h_cnt) * double(b.w_cnt)));
+    const float w_v = float(double(mix_beta) / (double(n_v) * double(d.HW)));
+    return dispatch_nhwc(d, [&](auto ty, auto vt) {
+        using T = decltype(ty);
+        constexpr int V = decltype(vt)::value;
+        hipLaunchKernelGGL((nhwc_dx_mixed_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st, static_cast<const T*>(x),
+                           static_cast<const T*>(dy), static_cast<T*>(dx), gamma, invstd, dgamma, dbeta, mean_parts,
+                           mean_parts + d.C, B, uint32_t(n_v) * uint32_t(d.HW), w_v, w_s, t, M);
+        return hipGetLastError();
+    });
 }
 
 }  // namespace bns

@@ -7,7 +7,7 @@ import torch
 from oracle import bns_oracle as oracle
 from paper_1810_10962_amd import bns, workloads
 from paper_1810_10962_amd.workloads import BS, FS, FULL, NS, VDN, Workload
-from parity import assert_parity, oracle_boxes, oracle_reference, scaled_err
+from parity import assert_parity, oracle_boxes, oracle_boxes_mixed, oracle_reference, scaled_err
 
 pytestmark = pytest.mark.gpu
 
@@ -279,3 +279,39 @@ def test_small_tensors_take_one_launch_per_direction(kernel_choice):
     big = workloads.WORKLOADS["cifar_fs"].replace(layout="nhwc", N=16)
     bns.run_workload(big, workloads.make_inputs(big))
     assert bns.bns_get_option("last_path_forward") == 1 and bns.bns_get_option("last_path_backward") == 1
+
+
+MIXED_MODES = [
+    ("full", dict(mode=FULL)),
+    ("ns", dict(mode=NS, n_s=2)),
+    ("bs", dict(mode=BS, n_s=2)),
+    ("fs", dict(mode=FS, patch_h=3, patch_w=2)),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mname,mkw", MIXED_MODES, ids=[m[0] for m in MIXED_MODES])
+@pytest.mark.parametrize("shape", [(6, 16, 8, 8), (5, 7, 7, 7), (9, 36, 6, 6), (12, 4, 40, 52)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_vdn_plus_sampling_small_shapes(shape, mname, mkw, dtype):
+    """Eq. 4 in this layout: virtual samples in front, the strategy applied to the real ones, several blends."""
+    N, C_, H, W = shape
+    for epoch, (n_v, mix_beta) in enumerate(((1, 0.5), (2, 0.3), (2, 1.0), (1, 0.0))):
+        wl = Workload(name=f"mix_{mname}", N=N, C=C_, H=H, W=W, dtype=dtype, layout="nhwc", n_v=n_v, mix_beta=mix_beta,
+                      data_seed=300 + epoch, sampling_seed=41, layer_id=6, epoch=epoch, **mkw)
+        inp, res = _run(wl)
+        bv, bs = oracle_boxes_mixed(wl)
+        assert (res["boxes"] == bs).all()
+        assert_parity(res, oracle_reference(wl, inp), wl,
+                      what=f"nhwc mixed {shape} {mname} {dtype} n_v={n_v} beta={mix_beta}", inp=inp)
+
+
+@pytest.mark.parametrize("name", ["vdn_fs_mix", "vdn_bs_mix"])
+def test_vdn_plus_sampling_benchmark_shape(name):
+    wl = workloads.WORKLOADS[name].replace(layout="nhwc")
+    inp, res = _run(wl)
+    errs = assert_parity(res, oracle_reference(wl, inp), wl, what=f"nhwc {name}", inp=inp)
+    _announce(f"{name} scaled errors {errs}")
+    nchw = bns.run_workload(wl.replace(layout="nchw"), inp)
+    for k in ("save_mean", "save_invstd", "save_mean_parts", "dgamma", "dbeta"):
+        assert scaled_err(res[k], nchw[k]) <= 2e-5, k
