@@ -229,6 +229,8 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  *                    (BNS_EUNSUPPORTED if a channel does not fit); 0: whichever is faster for the shape
  *   "fused_variant"  1..7: block size / registers-per-thread variant of the fused kernels
  *   "fused_coop"     1: launch the fused kernels with hipLaunchCooperativeKernel
+ *   "fused_keep_x"   the fused backward kernel keeps x in registers beside dy instead of reading it again
+ *                    on S: 1 always, 2 never; 0: when S is the whole tensor or a patch of every plane
  *   "split_statistics"  1: the streaming forward statistics always run as partial sums + finalize
  *                    (by default one 1024-thread block per channel does both when a channel has few
  *                    sampled points)

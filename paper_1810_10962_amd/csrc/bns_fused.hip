@@ -397,8 +397,10 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
 // ---------------------------------------------------------------------------------------
 // Backward: Eq. 5 sums + Eq. 6 with dy read once
 // ---------------------------------------------------------------------------------------
-template <typename T, int V, int KMAX, int NT>
-__global__ __launch_bounds__(NT) void fused_backward_kernel(FusedArgs A) {
+// KEEPX: x stays in registers next to dy (KMAX vectors of each), so nothing is read twice; worth its
+// registers when most of the channel lies in S (full BN).
+template <typename T, int V, int KMAX, int NT, bool KEEPX>
+__global__ __launch_bounds__(NT, (KEEPX && NT == 512 && KMAX <= 8) ? 4 : 1) void fused_backward_kernel(FusedArgs A) {
     typedef RawVec<T, V> RV;
     __shared__ float red[2 * (NT / kWave)];
     __shared__ float team_lds[2 * kMaxTeam];
@@ -437,8 +439,33 @@ __global__ __launch_bounds__(NT) void fused_backward_kernel(FusedArgs A) {
             }
         }
         float s1 = 0.f, s2 = 0.f;
+        typename RV::raw_t xk[KEEPX ? KMAX : 1];
         constexpr int XB = (KMAX >= 50 || (V == 8 && KMAX > 16)) ? 2 : 4;        // x vectors in flight per thread (register budget)
         const uint32_t ib = opaque(beg + threadIdx.x);
+        if constexpr (KEEPX) {
+#pragma unroll
+            for (int k = 0; k < KMAX; ++k) {
+                const uint32_t i = ib + uint32_t(k) * step;
+                if (i < end) {
+                    const uint32_t n = fdiv(i, A.hwv_div);
+                    xk[k] = RV::ld(xc + n * nstride + size_t(i - n * hwv) * V);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < KMAX; ++k) {
+                const uint32_t i = ib + uint32_t(k) * step;
+                if (i < end) {
+                    float fg[V], fx[V];
+                    RV::unpack(g[k], fg);
+                    RV::unpack(xk[k], fx);
+#pragma unroll
+                    for (int e = 0; e < V; ++e) {
+                        s1 += fg[e];
+                        s2 = fmaf(fg[e], fx[e] - mu, s2);
+                    }
+                }
+            }
+        } else {
 #pragma unroll
         for (int k0 = 0; k0 < KMAX; k0 += XB) {
             typename RV::raw_t xv[XB];
@@ -464,6 +491,7 @@ __global__ __launch_bounds__(NT) void fused_backward_kernel(FusedArgs A) {
                     }
                 }
             }
+        }
         }
         block_allsum2<NT>(s1, s2, red);
         double t1, t2;
@@ -493,7 +521,12 @@ __global__ __launch_bounds__(NT) void fused_backward_kernel(FusedArgs A) {
                                      e0 + V > uint32_t(b.h0) * A.W && e0 < uint32_t(b.h0 + b.h_cnt) * A.W;
                 if (touches) {
                     float fx[V];
-                    RV::unpack(RV::ld(xc + n * nstride + size_t(off) * V), fx);
+                    if constexpr (KEEPX) {
+                        opaque_raw(xk[k]);
+                        RV::unpack(xk[k], fx);
+                    } else {
+                        RV::unpack(RV::ld(xc + n * nstride + size_t(off) * V), fx);
+                    }
                     uint32_t h = fdiv(e0, A.w_div);
                     uint32_t w = e0 - h * uint32_t(A.W);
 #pragma unroll
@@ -527,10 +560,12 @@ constexpr Variant kVariants[] = {{64, 1}, {128, 2}, {256, 4}, {512, 8}, {512, 16
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 template <typename T, int V>
-const void* kernel_ptr(int kind, int variant) {       // kind 0: forward, whole planes; 1: backward; 2: forward, patches
+// kind 0: forward, whole planes; 1: backward; 2: forward, patches; 3: backward with x kept in registers
+const void* kernel_ptr(int kind, int variant) {
 #define BNS_CASE(I, NT_, K_)                                                                                  \
     case I:                                                                                                   \
-        return kind == 1   ? reinterpret_cast<const void*>(&fused_backward_kernel<T, V, K_, NT_>)             \
+        return kind == 1   ? reinterpret_cast<const void*>(&fused_backward_kernel<T, V, K_, NT_, false>)      \
+               : kind == 3 ? reinterpret_cast<const void*>(&fused_backward_kernel<T, V, K_, NT_, true>)       \
                : kind == 2 ? reinterpret_cast<const void*>(&fused_forward_kernel<T, V, K_, NT_, true>)        \
                            : reinterpret_cast<const void*>(&fused_forward_kernel<T, V, K_, NT_, false>);
     switch (variant) {
@@ -556,7 +591,7 @@ const void* kernel_for(const Dims& d, int kind, int variant) {
 struct DeviceInfo {
     int cus = 0;
     int coop = 0;
-    int blocks_per_cu[3][5][kNumVariants];  // [kernel kind][type/vec combo][variant], 0 = not queried yet
+    int blocks_per_cu[4][5][kNumVariants];  // [kernel kind][type/vec combo][variant], 0 = not queried yet
 };
 DeviceInfo g_dev[16];
 std::mutex g_dev_mutex;   // guards g_dev: launches may come from several host threads
@@ -592,7 +627,7 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     const uint32_t hwv = uint32_t(d.HW / d.vec);
     const uint32_t tot = uint32_t(d.N) * hwv;
     const int combo = combo_index(d);
-    const int kind = backward ? 1 : (ip.shared.h_cnt * ip.shared.w_cnt == d.HW ? 0 : 2);
+    int kind = backward ? 1 : (ip.shared.h_cnt * ip.shared.w_cnt == d.HW ? 0 : 2);
 
     // Choice of variant and team size, from sweeps on MI355X (64x256x56x56 fp32/bf16, 128x64x32x32,
     // 130x128x28x28):
@@ -650,23 +685,31 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
         out->rounds = best_rounds;
         return hipSuccess;
     };
+    // candidate A among the variants 0 .. last of the current kernel kind
+    auto candidate = [&](int last, Plan* out) -> hipError_t {
+        long best_key = -1;
+        out->v = -1;
+        for (int v = 0; v <= last; ++v) {
+            Plan p;
+            const hipError_t pe = plan_for(v, &p);
+            if (pe != hipSuccess) return pe;
+            if (p.v < 0) continue;
+            const long key = p.rounds * 100000 + (p.T == 1 ? 0 : p.T <= 64 ? 1 : p.T) * 8 + v;
+            if (out->v < 0 || key < best_key) {
+                *out = p;
+                best_key = key;
+            }
+        }
+        return hipSuccess;
+    };
     Plan chosen;
     if (g_tuning.fused_variant > 0) {
         if ((e = plan_for(g_tuning.fused_variant - 1, &chosen)) != hipSuccess) return e;
     } else {
-        long best_key = -1;
-        for (int v = 0; v < kNumVariants; ++v) {
-            Plan p;
-            if ((e = plan_for(v, &p)) != hipSuccess) return e;
-            if (p.v < 0) continue;
-            const long key = p.rounds * 100000 + (p.T == 1 ? 0 : p.T <= 64 ? 1 : p.T) * 8 + v;
-            if (chosen.v < 0 || key < best_key) {
-                chosen = p;
-                best_key = key;
-            }
-        }
+        if ((e = candidate(kNumVariants - 1, &chosen)) != hipSuccess) return e;
         const bns_box& sb = ip.shared;
         const bool everything = !ip.per_channel && sb.n_cnt == d.N && sb.h_cnt == d.H && sb.w_cnt == d.W;
+        const bool patch = sb.h_cnt * sb.w_cnt != d.HW;
         constexpr int kTwoPerUnit = 4;                                       // {512, 16}
         if (chosen.v > kTwoPerUnit && (backward || everything)) {
             Plan p;
@@ -675,6 +718,22 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
         }
         if (chosen.v >= 0 && !backward && !everything && chosen.rounds > 1 && g_tuning.path != 2)
             return hipErrorNotSupported;
+        // Backward needs x a second time on S.  When that is most of the channel (full BN), or a patch of
+        // every plane (the second read then fetches scattered pieces of lines), both tensors stay on chip:
+        // up to (512 threads, 8 + 8 vectors), the register cost of (512, 16).  Measured at 64x256x56x56 fp32:
+        // full BN 153 -> 130 us, Feature Sampling 134 -> 127; 128x64x32x32 Feature Sampling 30 -> 22.
+        // Whole planes of a few samples (Batch Sampling, VDN) re-read little and lose more to the larger teams.
+        constexpr int kKeepXLast = 3;                                        // {512, 8}
+        const bool keep_x = g_tuning.fused_keep_x == 1 || (g_tuning.fused_keep_x == 0 && (everything || patch));
+        if (backward && keep_x) {
+            kind = 3;
+            Plan p;
+            if ((e = candidate(kKeepXLast, &p)) != hipSuccess) return e;
+            if (p.v >= 0)
+                chosen = p;
+            else
+                kind = 1;
+        }
     }
     if (chosen.v < 0) return hipErrorNotSupported;
     const int best = chosen.v, bestT = chosen.T, best_blocks = chosen.blocks;

@@ -32,6 +32,7 @@ struct Tuning {
     int path = 0;                           // 0: fused kernels when a channel fits on chip, else streaming;
                                             // 1: streaming kernels only; 2: fused only (error if it cannot)
     int fused_variant = 0;                  // 1..7 forces a (block size, registers) variant of the fused kernels
+    int fused_keep_x = 0;                   // backward keeps x in registers next to dy: 1 always, 2 never, 0 when it pays
     int fused_coop = 0;                     // 1: launch the fused kernels with hipLaunchCooperativeKernel
     int split_statistics = 0;               // 1: forward statistics always as partial sums + finalize
     int nhwc_blocks = 0;                    // blocks an N x H x W x C reduction aims for (default kNhwcBlocks)
