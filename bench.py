@@ -325,9 +325,13 @@ def main():
             full = variants.get(name.replace("_bs", "_full").replace("_fs", "_full"))
             if full:
                 v["speedup_vs_full_bn"] = round(full["us_per_step"] / v["us_per_step"], 4)
+                if full.get("streaming_us") and v.get("streaming_us"):
+                    # both sides with the streaming kernels only: the two-pass cost model of the paper (App. C.1)
+                    v["speedup_vs_full_bn_streaming_kernels"] = round(full["streaming_us"] / v["streaming_us"], 4)
         out["variants"] = variants
         if wl.name in variants and "speedup_vs_full_bn" in variants[wl.name]:
             out["speedup_vs_full_bn"] = variants[wl.name]["speedup_vs_full_bn"]
+            out["speedup_vs_full_bn_streaming_kernels"] = variants[wl.name].get("speedup_vs_full_bn_streaming_kernels")
         others = {}
         for name in ("tiny_bs", "cifar_fs", "vdn", "micro_a_fs", "micro_a_full", "micro_b_fs", "micro_b_full"):
             v = workloads.WORKLOADS[name]
