@@ -559,13 +559,20 @@ struct Variant {
 constexpr Variant kVariants[] = {{64, 1}, {128, 2}, {256, 4}, {512, 8}, {512, 16}, {512, 32}, {512, 50}};
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
-template <typename T, int V>
 // kind 0: forward, whole planes; 1: backward; 2: forward, patches; 3: backward with x kept in registers
+// (built for the variants of up to kKeepXMaxVectors vectors per tensor only: beyond, the registers run out)
+constexpr int kKeepXMaxVectors = 8;
+template <typename T, int V>
 const void* kernel_ptr(int kind, int variant) {
 #define BNS_CASE(I, NT_, K_)                                                                                  \
     case I:                                                                                                   \
+        if (kind == 3) {                                                                                      \
+            if constexpr (K_ <= kKeepXMaxVectors)                                                             \
+                return reinterpret_cast<const void*>(&fused_backward_kernel<T, V, K_, NT_, true>);            \
+            else                                                                                              \
+                return nullptr;                                                                               \
+        }                                                                                                     \
         return kind == 1   ? reinterpret_cast<const void*>(&fused_backward_kernel<T, V, K_, NT_, false>)      \
-               : kind == 3 ? reinterpret_cast<const void*>(&fused_backward_kernel<T, V, K_, NT_, true>)       \
                : kind == 2 ? reinterpret_cast<const void*>(&fused_forward_kernel<T, V, K_, NT_, true>)        \
                            : reinterpret_cast<const void*>(&fused_forward_kernel<T, V, K_, NT_, false>);
     switch (variant) {
@@ -648,6 +655,7 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
         const Variant& va = kVariants[v];
         out->v = -1;
         int& bpc = di.blocks_per_cu[kind][combo][v];
+        if (bpc == 0 && kernel_for(d, kind, v) == nullptr) bpc = -1;        // flavour not built for this variant
         if (bpc == 0) {
             int nb = 0;
             const hipError_t oe = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel_for(d, kind, v), va.nt, 0);
