@@ -712,7 +712,12 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     };
     Plan chosen;
     if (g_tuning.fused_variant > 0) {
-        if ((e = plan_for(g_tuning.fused_variant - 1, &chosen)) != hipSuccess) return e;
+        if (backward && g_tuning.fused_keep_x == 1) {        // both forced: the keep-x flavour of that variant, if built
+            kind = 3;
+            if ((e = plan_for(g_tuning.fused_variant - 1, &chosen)) != hipSuccess) return e;
+            if (chosen.v < 0) kind = 1;
+        }
+        if (chosen.v < 0 && (e = plan_for(g_tuning.fused_variant - 1, &chosen)) != hipSuccess) return e;
     } else {
         if ((e = candidate(kNumVariants - 1, &chosen)) != hipSuccess) return e;
         const bns_box& sb = ip.shared;

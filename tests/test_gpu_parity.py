@@ -307,6 +307,43 @@ def test_fused_kernels_every_variant(variant, shape, mkw, dtype, kernel_path):
         assert (res[k] == again[k]).all(), f"{k}: fused kernels are not bit-identical from run to run"
 
 
+@pytest.mark.parametrize("variant,shape,mkw", [
+    (1, (16, 300, 16, 16), dict(mode=BS, n_s=4)),                      # 64-thread blocks, large teams, several rounds
+    (1, (16, 300, 16, 16), dict(mode=FS, patch_h=5, patch_w=7)),
+    (2, (5, 7, 7, 7), dict(mode=FULL)),                                # scalar path, unaligned planes
+    (3, (64, 96, 28, 28), dict(mode=FS, patch_h=7, patch_w=9, fs_per_channel=1)),
+    (4, (32, 40, 56, 56), dict(mode=FULL)),
+    (4, (32, 300, 28, 28), dict(mode=VDN, n_s=3)),                     # several rounds
+])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_fused_backward_with_x_kept_on_chip(variant, shape, mkw, dtype, kernel_path):
+    """The backward flavour that keeps x in registers beside dy, forced for every variant it is built for
+    and for location sets the automatic choice would not give it."""
+    if kernel_path != "auto":
+        pytest.skip("forced-fused test runs once")
+    N, C_, H, W = shape
+    wl = Workload(name=f"keepx_v{variant}", N=N, C=C_, H=H, W=W, dtype=dtype, data_seed=6, sampling_seed=12,
+                  layer_id=3, epoch=variant, **mkw)
+    inp = workloads.make_inputs(wl)
+    try:
+        bns.bns_set_option("path", 2)
+        bns.bns_set_option("fused_variant", variant)
+        bns.bns_set_option("fused_keep_x", 1)
+        _, res = _run(wl, inp)
+        again = bns.run_workload(wl, inp)
+        bns.bns_set_option("fused_keep_x", 2)
+        plain = bns.run_workload(wl, inp)
+    finally:
+        bns.bns_set_option("fused_keep_x", 0)
+        bns.bns_set_option("fused_variant", 0)
+        bns.bns_set_option("path", 0)
+    assert_parity(res, oracle_reference(wl, inp), wl, what=f"keep-x variant {variant} {shape} {dtype}", inp=inp)
+    for k in res:
+        assert (res[k] == again[k]).all(), f"{k}: not bit-identical from run to run"
+    for k in res:       # the flavour that reads x again: same function, team sizes (hence rounding order) may differ
+        assert scaled_err(res[k], plain[k]) <= (2e-5 if k not in ("y", "dx") or dtype == "f32" else 1e-2), k
+
+
 def test_running_statistics_over_iterations_and_null_running_buffers():
     wl = workloads.WORKLOADS["tiny_bs"]
     inp = workloads.make_inputs(wl)
