@@ -333,12 +333,17 @@ def main():
             out["speedup_vs_full_bn"] = variants[wl.name]["speedup_vs_full_bn"]
             out["speedup_vs_full_bn_streaming_kernels"] = variants[wl.name].get("speedup_vs_full_bn_streaming_kernels")
         others = {}
-        for name in ("tiny_bs", "cifar_fs", "vdn", "micro_a_fs", "micro_a_full", "micro_b_fs", "micro_b_full"):
+        for name in ("tiny_bs", "cifar_fs", "vdn", "vdn_fs_mix", "vdn_bs_mix", "micro_a_fs", "micro_a_full", "micro_b_fs",
+                     "micro_b_full"):
             v = workloads.WORKLOADS[name]
             vin = workloads.make_inputs(v)
             vb = v.elements * 4
             vds = DeviceSet(v, vin, max(2, min(8, int(np.ceil(1.5e9 / (4 * vb))))), torch, bns)
-            vr = sampling_ratio(v, bns.bns_sample_index(vds.bufs[0].shape, vds.bufs[0].spec, v.sampling_seed))
+            if v.n_v and v.mode != workloads.VDN:         # Eq. 4: the virtual samples and the sampled real set
+                vr = sampling_ratio(v, bns.bns_sample_index_mixed(vds.bufs[0].shape, vds.bufs[0].spec, v.sampling_seed,
+                                                                  v.n_v)) + v.n_v / v.N
+            else:
+                vr = sampling_ratio(v, bns.bns_sample_index(vds.bufs[0].shape, vds.bufs[0].spec, v.sampling_seed))
             vsec = time_steps(vds, K, W, torch)
             va = algorithmic_bytes(v, vr)["fwd+bwd"]
             others[name] = dict(shape="x".join(map(str, v.shape)), label=v.label(), us_per_step=round(vsec * 1e6, 2),

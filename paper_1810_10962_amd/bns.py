@@ -314,9 +314,16 @@ class Buffers:
             _check(_lib.bns_forward(*self._fwd_args, self._stream_ptr()), "bns_forward")
             return
         if self.n_v:
-            bns_forward_mixed(self.shape, self.spec, self.seed, self.n_v, self.wl.mix_beta, self.x, self.gamma,
-                              self.beta, self.wl.eps, self.wl.momentum, self.y, self.save_mean, self.save_invstd,
-                              self.save_mean_parts, self.running_mean, self.running_var, self.workspace)
+            # same call as bns_forward_mixed(...), marshalled once
+            if self._fwd_args is None:
+                ws = self.workspace
+                self._fwd_args = (C.byref(self.shape), C.byref(self.spec), C.c_uint64(self.seed), C.c_int32(self.n_v),
+                                  C.c_float(self.wl.mix_beta), _ptr(self.x), _ptr(self.gamma), _ptr(self.beta),
+                                  C.c_float(self.wl.eps), C.c_float(self.wl.momentum), _ptr(self.y),
+                                  _ptr(self.save_mean), _ptr(self.save_invstd), _ptr(self.save_mean_parts),
+                                  _ptr(self.running_mean), _ptr(self.running_var), _ptr(ws),
+                                  C.c_size_t(ws.numel() * ws.element_size()))
+            _check(_lib.bns_forward_mixed(*self._fwd_args, self._stream_ptr()), "bns_forward_mixed")
             return
         bns_forward(self.shape, self.spec, self.seed, self.x, self.gamma, self.beta, self.wl.eps, self.wl.momentum,
                     self.y, self.save_mean, self.save_invstd, self.running_mean, self.running_var, self.workspace)
@@ -332,9 +339,14 @@ class Buffers:
             _check(_lib.bns_backward(*self._bwd_args, self._stream_ptr()), "bns_backward")
             return
         if self.n_v:
-            bns_backward_mixed(self.shape, self.spec, self.seed, self.n_v, self.wl.mix_beta, self.x, self.dy,
-                               self.gamma, self.save_mean, self.save_invstd, self.save_mean_parts, self.dx,
-                               self.dgamma, self.dbeta, self.workspace)
+            if self._bwd_args is None:
+                ws = self.workspace
+                self._bwd_args = (C.byref(self.shape), C.byref(self.spec), C.c_uint64(self.seed), C.c_int32(self.n_v),
+                                  C.c_float(self.wl.mix_beta), _ptr(self.x), _ptr(self.dy), _ptr(self.gamma),
+                                  _ptr(self.save_mean), _ptr(self.save_invstd), _ptr(self.save_mean_parts),
+                                  _ptr(self.dx), _ptr(self.dgamma), _ptr(self.dbeta), _ptr(ws),
+                                  C.c_size_t(ws.numel() * ws.element_size()))
+            _check(_lib.bns_backward_mixed(*self._bwd_args, self._stream_ptr()), "bns_backward_mixed")
             return
         bns_backward(self.shape, self.spec, self.seed, self.x, self.dy, self.gamma, self.save_mean,
                      self.save_invstd, self.dx, self.dgamma, self.dbeta, self.workspace)

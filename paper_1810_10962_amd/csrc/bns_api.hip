@@ -447,6 +447,31 @@ bns_status bns_forward_mixed(const bns_shape* shape, const bns_spec* spec, uint6
             return BNS_EDEVICE;
         return dev(launch_nhwc_normalize(d, x, gamma, beta, save_mean, save_invstd, y, st));
     }
+    if (g_tuning.path != 1) {
+        FusedIo io;
+        io.x = x;
+        io.out = y;
+        io.gamma = gamma;
+        io.beta = beta;
+        io.save_mean = save_mean;
+        io.save_invstd = save_invstd;
+        io.running_mean = running_mean;
+        io.running_var = running_var;
+        FusedMix mix;
+        mix.n_v = n_v;
+        mix.mix_beta = mix_beta;
+        mix.mean_parts = save_mean_parts;
+        const hipError_t fe = launch_fused(d, ip_s, false, io, eps, momentum,
+                                           static_cast<char*>(workspace) + 2 * partial_bytes(d), kSlotBytes, 0, d.C, st,
+                                           &mix);
+        if (fe == hipSuccess) {
+            g_last_path_forward.store(2);
+            return BNS_OK;
+        }
+        if (fe != hipErrorNotSupported) return BNS_EDEVICE;
+        if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
+    }
+    g_last_path_forward.store(1);
     const IndexParams ip_v = make_index_params_virtual(*shape, n_v);
     Partial* ws_s = static_cast<Partial*>(workspace);
     Partial* ws_v = reinterpret_cast<Partial*>(static_cast<char*>(workspace) + partial_bytes(d));
@@ -483,6 +508,30 @@ bns_status bns_backward_mixed(const bns_shape* shape, const bns_spec* spec, uint
         return dev(launch_nhwc_dx_mixed(d, ip_s.shared, n_v, mix_beta, x, dy, gamma, save_invstd, dgamma, dbeta,
                                         save_mean_parts, dx, st));
     }
+    if (g_tuning.path != 1) {
+        FusedIo io;
+        io.x = x;
+        io.dy = dy;
+        io.out = dx;
+        io.gamma = gamma;
+        io.save_mean = const_cast<float*>(save_mean);
+        io.save_invstd = const_cast<float*>(save_invstd);
+        io.dgamma = dgamma;
+        io.dbeta = dbeta;
+        FusedMix mix;
+        mix.n_v = n_v;
+        mix.mix_beta = mix_beta;
+        mix.mean_parts = const_cast<float*>(save_mean_parts);
+        const hipError_t fe = launch_fused(d, ip_s, true, io, 0.f, 0.f, static_cast<char*>(workspace) + 2 * partial_bytes(d),
+                                           kSlotBytes, 0, d.C, st, &mix);
+        if (fe == hipSuccess) {
+            g_last_path_backward.store(2);
+            return BNS_OK;
+        }
+        if (fe != hipErrorNotSupported) return BNS_EDEVICE;
+        if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
+    }
+    g_last_path_backward.store(1);
     s = reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, static_cast<Partial*>(workspace), 0, d.C, st);
     if (s != BNS_OK) return s;
     const bns_box& b = ip_s.shared;

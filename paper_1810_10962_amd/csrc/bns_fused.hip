@@ -134,6 +134,12 @@ struct FusedArgs {
     int32_t T, num_teams;
     uint32_t tot;   // vectors per channel: N * HW / V
     uint32_t s_cnt; // |S| per channel
+    // "VDN + sampling" (Eq. 4), the MIXED flavours: samples [0, n_v) are the virtual set, `ip` describes the
+    // sampled real set; mean_parts = [E_v per channel][E_s per channel] (forward: written; backward: read)
+    int32_t n_v;
+    float mix_beta, w_v, w_s;       // backward weights: mix_beta / s_v and (1 - mix_beta) / s_s
+    double s_v;                     // n_v * HW
+    float* mean_parts;
     FastDiv patch_div, pw_div;   // h_cnt * w_cnt and w_cnt of S: sampled element q -> (n, ph, pw)
     uint32_t stamp0;
     float eps, momentum, inv_s;
@@ -271,7 +277,9 @@ __device__ __forceinline__ size_t patch_offset(const FusedArgs& A, uint32_t q, s
 // Forward: Eq. 3 + Eq. 8 + Eq. 1 with x read once
 // ---------------------------------------------------------------------------------------
 // PATCH: S is a patch of each plane (host guarantee: h_cnt * w_cnt < H * W); else S is whole planes.
-template <typename T, int V, int KMAX, int NT, bool PATCH>
+// MIXED: Eq. 4 -- a second pair of sums over the virtual set (samples [0, n_v), always whole planes, taken
+// from the registers), a second exchange, and the blend of the two (E, Var) pairs.
+template <typename T, int V, int KMAX, int NT, bool PATCH, bool MIXED>
 __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
     typedef RawVec<T, V> RV;
     __shared__ float red[2 * (NT / kWave)];
@@ -357,15 +365,51 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
                 s2 = fmaf(d, d, s2);
             }
         }
+        float v1 = 0.f, v2 = 0.f, pivot_v = 0.f;
+        if constexpr (MIXED) {                                      // the virtual set: planes of samples [0, n_v)
+            pivot_v = load_scalar<T>(xc);
+            const uint32_t id = opaque(beg + threadIdx.x);
+#pragma unroll
+            for (int k = 0; k < KMAX; ++k) {
+                const uint32_t i = id + uint32_t(k) * step;
+                if (i < end && fdiv(i, A.hwv_div) < uint32_t(A.n_v)) {
+                    float f[V];
+                    RV::unpack(v[k], f);
+#pragma unroll
+                    for (int e = 0; e < V; ++e) {
+                        const float d = f[e] - pivot_v;
+                        v1 += d;
+                        v2 = fmaf(d, d, v2);
+                    }
+                }
+            }
+        }
         block_allsum2<NT>(s1, s2, red);
         double t1, t2;
-        team_allsum2<NT>(A, team * A.T, j, it, s1, s2, t1, t2, team_lds, bc);
+        team_allsum2<NT>(A, team * A.T, j, MIXED ? 2u * it : it, s1, s2, t1, t2, team_lds, bc);
 
         // Eq. 3 (every thread computes the same values from the same totals)
         const double m1 = t1 / A.s;
-        const double mean = double(pivot) + m1;
+        double mean = double(pivot) + m1;
         double var = t2 / A.s - m1 * m1;
         if (!(var >= 0.0)) var = (var != var) ? var : 0.0;      // clamp rounding; keep NaN visible
+        if constexpr (MIXED) {
+            __syncthreads();                                    // red[] is read by every thread of the first sum
+            block_allsum2<NT>(v1, v2, red);
+            double u1, u2;
+            team_allsum2<NT>(A, team * A.T, j, 2u * it + 1u, v1, v2, u1, u2, team_lds, bc);
+            const double mv = u1 / A.s_v;
+            const double e_v = double(pivot_v) + mv;
+            double var_v = u2 / A.s_v - mv * mv;
+            if (!(var_v >= 0.0)) var_v = (var_v != var_v) ? var_v : 0.0;
+            if (j == 0 && threadIdx.x == 0) {
+                A.mean_parts[c] = float(e_v);
+                A.mean_parts[A.C + c] = float(mean);
+            }
+            const double bm = double(A.mix_beta);
+            mean = bm * e_v + (1.0 - bm) * mean;                // Eq. 4, X = E
+            var = bm * var_v + (1.0 - bm) * var;                // Eq. 4, X = Var
+        }
         const float mu = float(mean);
         const float r = float(1.0 / sqrt(var + double(A.eps)));
         if (j == 0 && threadIdx.x == 0) {
@@ -399,7 +443,9 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
 // ---------------------------------------------------------------------------------------
 // KEEPX: x stays in registers next to dy (KMAX vectors of each), so nothing is read twice; worth its
 // registers when most of the channel lies in S (full BN).
-template <typename T, int V, int KMAX, int NT, bool KEEPX>
+// MIXED: backward of Eq. 4 -- vectors of samples [0, n_v) belong to the virtual set (weight w_v, centre E_v,
+// every element), vectors that touch the box to the sampled real set (w_s, centre E_s, masked by the box).
+template <typename T, int V, int KMAX, int NT, bool KEEPX, bool MIXED>
 __global__ __launch_bounds__(NT, (KEEPX && NT == 512 && KMAX <= 8) ? 4 : 1) void fused_backward_kernel(FusedArgs A) {
     typedef RawVec<T, V> RV;
     __shared__ float red[2 * (NT / kWave)];
@@ -504,8 +550,13 @@ __global__ __launch_bounds__(NT, (KEEPX && NT == 512 && KMAX <= 8) ? 4 : 1) void
             A.dgamma[c] = dgamma;
         }
         const float a = ga * r;
-        const float k1 = a * A.inv_s * dbeta;
-        const float k2 = a * A.inv_s * dgamma * r;
+        const float wgt_s = MIXED ? A.w_s : A.inv_s;
+        const float k1 = a * wgt_s * dbeta;
+        const float k2 = a * wgt_s * dgamma * r;
+        const float k1v = MIXED ? a * A.w_v * dbeta : 0.f;
+        const float k2v = MIXED ? a * A.w_v * dgamma * r : 0.f;
+        const float centre_s = MIXED ? A.mean_parts[A.C + c] : mu;
+        const float centre_v = MIXED ? A.mean_parts[c] : mu;
         const uint32_t ic = opaque(beg + threadIdx.x);
 #pragma unroll
         for (int k = 0; k < KMAX; ++k) {
@@ -517,8 +568,9 @@ __global__ __launch_bounds__(NT, (KEEPX && NT == 512 && KMAX <= 8) ? 4 : 1) void
                 float f[V];
                 opaque_raw(g[k]);
                 RV::unpack(g[k], f);
-                const bool touches = n >= uint32_t(b.n0) && n < uint32_t(b.n0 + b.n_cnt) &&
-                                     e0 + V > uint32_t(b.h0) * A.W && e0 < uint32_t(b.h0 + b.h_cnt) * A.W;
+                const bool virt = MIXED && n < uint32_t(A.n_v);
+                const bool touches = virt || (n >= uint32_t(b.n0) && n < uint32_t(b.n0 + b.n_cnt) &&
+                                              e0 + V > uint32_t(b.h0) * A.W && e0 < uint32_t(b.h0 + b.h_cnt) * A.W);
                 if (touches) {
                     float fx[V];
                     if constexpr (KEEPX) {
@@ -531,7 +583,9 @@ __global__ __launch_bounds__(NT, (KEEPX && NT == 512 && KMAX <= 8) ? 4 : 1) void
                     uint32_t w = e0 - h * uint32_t(A.W);
 #pragma unroll
                     for (int e = 0; e < V; ++e) {
-                        const float corr = in_hw(b, h, w) ? fmaf(k2, fx[e] - mu, k1) : 0.f;
+                        const float corr = virt             ? fmaf(k2v, fx[e] - centre_v, k1v)
+                                           : in_hw(b, h, w) ? fmaf(k2, fx[e] - centre_s, k1)
+                                                            : 0.f;
                         f[e] = fmaf(a, f[e], -corr);
                         if (++w == uint32_t(A.W)) {
                             w = 0;
@@ -559,22 +613,40 @@ struct Variant {
 constexpr Variant kVariants[] = {{64, 1}, {128, 2}, {256, 4}, {512, 8}, {512, 16}, {512, 32}, {512, 50}};
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
-// kind 0: forward, whole planes; 1: backward; 2: forward, patches; 3: backward with x kept in registers
-// (built for the variants of up to kKeepXMaxVectors vectors per tensor only: beyond, the registers run out)
+// Kernel kind = backward | flavour << 1 | mixed << 2.  Flavour: forward, statistics from separately read
+// patch elements; backward, x kept in registers (built for the variants of up to kKeepXMaxVectors vectors
+// per tensor only: beyond, the registers run out).  Mixed: Eq. 4 (built for vector accesses and up to
+// kMixedMaxVectors vectors per thread; other shapes take the streaming kernels).
 constexpr int kKeepXMaxVectors = 8;
+constexpr int kMixedMaxVectors = 16;
 template <typename T, int V>
 const void* kernel_ptr(int kind, int variant) {
 #define BNS_CASE(I, NT_, K_)                                                                                  \
     case I:                                                                                                   \
         if (kind == 3) {                                                                                      \
             if constexpr (K_ <= kKeepXMaxVectors)                                                             \
-                return reinterpret_cast<const void*>(&fused_backward_kernel<T, V, K_, NT_, true>);            \
+                return reinterpret_cast<const void*>(&fused_backward_kernel<T, V, K_, NT_, true, false>);     \
             else                                                                                              \
                 return nullptr;                                                                               \
         }                                                                                                     \
-        return kind == 1   ? reinterpret_cast<const void*>(&fused_backward_kernel<T, V, K_, NT_, false>)      \
-               : kind == 2 ? reinterpret_cast<const void*>(&fused_forward_kernel<T, V, K_, NT_, true>)        \
-                           : reinterpret_cast<const void*>(&fused_forward_kernel<T, V, K_, NT_, false>);
+        if (kind >= 4) {                                                                                      \
+            if constexpr (K_ <= kMixedMaxVectors && V > 1) {                                                  \
+                if (kind == 7) {                                                                              \
+                    if constexpr (K_ <= kKeepXMaxVectors)                                                     \
+                        return reinterpret_cast<const void*>(&fused_backward_kernel<T, V, K_, NT_, true, true>); \
+                    else                                                                                      \
+                        return nullptr;                                                                       \
+                }                                                                                             \
+                return kind == 5   ? reinterpret_cast<const void*>(&fused_backward_kernel<T, V, K_, NT_, false, true>) \
+                       : kind == 6 ? reinterpret_cast<const void*>(&fused_forward_kernel<T, V, K_, NT_, true, true>)   \
+                                   : reinterpret_cast<const void*>(&fused_forward_kernel<T, V, K_, NT_, false, true>); \
+            } else {                                                                                          \
+                return nullptr;                                                                               \
+            }                                                                                                 \
+        }                                                                                                     \
+        return kind == 1   ? reinterpret_cast<const void*>(&fused_backward_kernel<T, V, K_, NT_, false, false>) \
+               : kind == 2 ? reinterpret_cast<const void*>(&fused_forward_kernel<T, V, K_, NT_, true, false>)   \
+                           : reinterpret_cast<const void*>(&fused_forward_kernel<T, V, K_, NT_, false, false>);
     switch (variant) {
         BNS_CASE(0, 64, 1)
         BNS_CASE(1, 128, 2)
@@ -598,7 +670,7 @@ const void* kernel_for(const Dims& d, int kind, int variant) {
 struct DeviceInfo {
     int cus = 0;
     int coop = 0;
-    int blocks_per_cu[4][5][kNumVariants];  // [kernel kind][type/vec combo][variant], 0 = not queried yet
+    int blocks_per_cu[8][5][kNumVariants];  // [kernel kind][type/vec combo][variant], 0 = not queried yet
 };
 DeviceInfo g_dev[16];
 std::mutex g_dev_mutex;   // guards g_dev: launches may come from several host threads
@@ -615,7 +687,8 @@ std::atomic<uint32_t> g_stamp{1};
 // Plans and launches one fused pass over channels [c0, c0 + cg).  Returns hipErrorNotSupported
 // when the channel does not fit on chip (the caller then takes the streaming kernels).
 hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, const FusedIo& io, float eps,
-                        float momentum, void* slots, size_t slot_bytes, int c0, int cg, hipStream_t st) {
+                        float momentum, void* slots, size_t slot_bytes, int c0, int cg, hipStream_t st,
+                        const FusedMix* mix) {
     int devid = 0;
     hipError_t e = hipGetDevice(&devid);
     if (e != hipSuccess) return e;
@@ -634,7 +707,7 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     const uint32_t hwv = uint32_t(d.HW / d.vec);
     const uint32_t tot = uint32_t(d.N) * hwv;
     const int combo = combo_index(d);
-    int kind = backward ? 1 : (ip.shared.h_cnt * ip.shared.w_cnt == d.HW ? 0 : 2);
+    int kind = (backward ? 1 : (ip.shared.h_cnt * ip.shared.w_cnt == d.HW ? 0 : 2)) | (mix ? 4 : 0);
 
     // Choice of variant and team size, from sweeps on MI355X (64x256x56x56 fp32/bf16, 128x64x32x32,
     // 130x128x28x28):
@@ -713,9 +786,9 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     Plan chosen;
     if (g_tuning.fused_variant > 0) {
         if (backward && g_tuning.fused_keep_x == 1) {        // both forced: the keep-x flavour of that variant, if built
-            kind = 3;
+            kind |= 2;
             if ((e = plan_for(g_tuning.fused_variant - 1, &chosen)) != hipSuccess) return e;
-            if (chosen.v < 0) kind = 1;
+            if (chosen.v < 0) kind &= ~2;
         }
         if (chosen.v < 0 && (e = plan_for(g_tuning.fused_variant - 1, &chosen)) != hipSuccess) return e;
     } else {
@@ -729,7 +802,8 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
             if ((e = plan_for(kTwoPerUnit, &p)) != hipSuccess) return e;
             if (p.v >= 0) chosen = p;
         }
-        if (chosen.v >= 0 && !backward && !everything && chosen.rounds > 1 && g_tuning.path != 2)
+        // (Eq. 4 has no such alternative: its streaming forward is four launches)
+        if (chosen.v >= 0 && !backward && !everything && chosen.rounds > 1 && g_tuning.path != 2 && !mix)
             return hipErrorNotSupported;
         // Backward needs x a second time on S.  When that is most of the channel (full BN), or a patch of
         // every plane (the second read then fetches scattered pieces of lines), both tensors stay on chip:
@@ -739,13 +813,13 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
         constexpr int kKeepXLast = 3;                                        // {512, 8}
         const bool keep_x = g_tuning.fused_keep_x == 1 || (g_tuning.fused_keep_x == 0 && (everything || patch));
         if (backward && keep_x) {
-            kind = 3;
+            kind |= 2;
             Plan p;
             if ((e = candidate(kKeepXLast, &p)) != hipSuccess) return e;
             if (p.v >= 0)
                 chosen = p;
             else
-                kind = 1;
+                kind &= ~2;
         }
     }
     if (chosen.v < 0) return hipErrorNotSupported;
@@ -785,12 +859,24 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     if (A.num_teams > cg) A.num_teams = cg;
     A.tot = tot;
     const uint32_t rounds = uint32_t((cg + A.num_teams - 1) / A.num_teams);
-    A.stamp0 = g_stamp.fetch_add(rounds + 1);
+    A.stamp0 = g_stamp.fetch_add((mix ? 2u : 1u) * rounds + 1u);   // Eq. 4 forward exchanges twice per round
     A.eps = eps;
     A.momentum = momentum;
     const bns_box& b = ip.shared;
     A.s = double(b.n_cnt) * double(b.h_cnt) * double(b.w_cnt);
     A.s_cnt = uint32_t(b.n_cnt) * uint32_t(b.h_cnt) * uint32_t(b.w_cnt);
+    A.n_v = 0;
+    A.mix_beta = A.w_v = A.w_s = 0.f;
+    A.s_v = 1.0;
+    A.mean_parts = nullptr;
+    if (mix) {
+        A.n_v = mix->n_v;
+        A.mix_beta = mix->mix_beta;
+        A.s_v = double(mix->n_v) * double(d.HW);
+        A.w_v = float(double(mix->mix_beta) / A.s_v);
+        A.w_s = float((1.0 - double(mix->mix_beta)) / A.s);
+        A.mean_parts = mix->mean_parts;
+    }
     A.patch_div = make_fastdiv(uint32_t(b.h_cnt) * uint32_t(b.w_cnt));
     A.pw_div = make_fastdiv(uint32_t(b.w_cnt));
     A.inv_s = float(1.0 / A.s);

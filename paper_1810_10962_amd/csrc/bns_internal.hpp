@@ -107,8 +107,15 @@ struct FusedIo {
 };
 constexpr size_t kSlotBytes = 256 * 1024;   // stamped exchange slots of the fused kernels
 // hipErrorNotSupported: the channel does not fit on chip (take the streaming kernels instead).
+// mix != nullptr: "VDN + sampling" (Eq. 4); `ip` then describes the sampled real set.
+struct FusedMix {
+    int32_t n_v = 0;
+    float mix_beta = 0.f;
+    float* mean_parts = nullptr;     // [E_v per channel][E_s per channel]: forward writes, backward reads
+};
 hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, const FusedIo& io, float eps,
-                        float momentum, void* slots, size_t slot_bytes, int c0, int cg, hipStream_t st);
+                        float momentum, void* slots, size_t slot_bytes, int c0, int cg, hipStream_t st,
+                        const FusedMix* mix = nullptr);
 
 hipError_t launch_index_boxes(const IndexParams& ip, int C, bns_box* boxes, hipStream_t st);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);

@@ -398,8 +398,6 @@ MIXED_MODES = [
                          ids=lambda s: "x".join(map(str, s)))
 def test_vdn_plus_sampling_small_shapes(shape, mname, mkw, dtype, kernel_path):
     """Eq. 4: statistics blended from the virtual samples and the sampled real samples."""
-    if kernel_path != "auto":
-        pytest.skip("the mixed statistics have one kernel path")
     N, C_, H, W = shape
     for n_v, mix in ((1, 0.5), (2, 0.3), (2, 1.0), (1, 0.0)):
         wl = Workload(name=f"mix_{mname}", N=N, C=C_, H=H, W=W, dtype=dtype, n_v=n_v, mix_beta=mix, data_seed=40 + n_v,
@@ -411,12 +409,47 @@ def test_vdn_plus_sampling_small_shapes(shape, mname, mkw, dtype, kernel_path):
                       inp=inp)
 
 
+@pytest.mark.parametrize("variant,shape,mkw", [
+    (1, (16, 300, 16, 16), dict(mode=BS, n_s=4)),                      # 64-thread blocks, large teams, several rounds
+    (1, (16, 300, 16, 16), dict(mode=FS, patch_h=5, patch_w=7)),
+    (2, (9, 36, 6, 6), dict(mode=FULL)),
+    (3, (64, 96, 28, 28), dict(mode=FS, patch_h=7, patch_w=9, fs_per_channel=1)),
+    (4, (32, 40, 56, 56), dict(mode=NS, n_s=5)),
+    (5, (32, 300, 28, 28), dict(mode=BS, n_s=3)),                      # several rounds, two exchanges per round
+    (5, (34, 24, 56, 56), dict(mode=FS, patch_h=14, patch_w=14)),
+])
+@pytest.mark.parametrize("keep_x", [2, 1])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_vdn_plus_sampling_fused_variants(variant, shape, mkw, dtype, keep_x, kernel_path):
+    """Eq. 4 through the single-launch kernels, every variant they are built for, backward with and without x
+    kept on chip (the latter exists up to variant 4)."""
+    if kernel_path != "auto":
+        pytest.skip("forced-fused test runs once")
+    N, C_, H, W = shape
+    wl = Workload(name=f"mix_fused_v{variant}", N=N, C=C_, H=H, W=W, dtype=dtype, n_v=2, mix_beta=0.5, data_seed=7,
+                  sampling_seed=14, layer_id=4, epoch=variant, **mkw)
+    inp = workloads.make_inputs(wl)
+    try:
+        bns.bns_set_option("path", 2)
+        bns.bns_set_option("fused_variant", variant)
+        bns.bns_set_option("fused_keep_x", keep_x)
+        _, res = _run(wl, inp)
+        again = bns.run_workload(wl, inp)
+    finally:
+        bns.bns_set_option("fused_keep_x", 0)
+        bns.bns_set_option("fused_variant", 0)
+        bns.bns_set_option("path", 0)
+    assert_parity(res, oracle_reference(wl, inp), wl, what=f"mixed fused variant {variant} {shape} {dtype}", inp=inp)
+    for k in res:
+        assert (res[k] == again[k]).all(), f"{k}: not bit-identical from run to run"
+
+
 @pytest.mark.parametrize("name", ["vdn_fs_mix", "vdn_bs_mix"])
 def test_vdn_plus_sampling_benchmark_shape(name, kernel_path):
-    if kernel_path != "auto":
-        pytest.skip("the mixed statistics have one kernel path")
     wl = workloads.WORKLOADS[name]
     inp, res = _run(wl)
+    want = 2 if kernel_path == "auto" else 1         # this shape fits on chip: one launch per direction by default
+    assert bns.bns_get_option("last_path_forward") == want and bns.bns_get_option("last_path_backward") == want
     errs = assert_parity(res, oracle_reference(wl, inp), wl, what=name, inp=inp)
     _announce(f"{name} scaled errors {errs}")
     again = bns.run_workload(wl, inp)
