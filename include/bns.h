@@ -186,7 +186,9 @@ bns_status bns_backward_dx(const bns_shape* shape, const bns_spec* spec, uint64_
  * holds E[x_v] for every channel, then E[x_s] for every channel: the backward pass centres the
  * variance terms on them.  Everything else as bns_forward.
  * Errors as bns_forward, plus BNS_EINVAL for n_v outside [1, N-1], mix_beta outside [0, 1],
- * mode VDN, or a spec that is invalid for N - n_v samples. */
+ * mode VDN, or a spec that is invalid for N - n_v samples.  Like bns_forward / bns_backward the two calls
+ * take the single-launch kernels when a channel fits on chip and the streaming kernels otherwise
+ * ("path" option, "last_path_forward" / "last_path_backward"). */
 bns_status bns_sample_index_mixed(const bns_shape* shape, const bns_spec* spec, uint64_t seed, int32_t n_v,
                                   bns_box* boxes /* HOST, C entries: the sampled REAL set */);
 bns_status bns_forward_mixed(const bns_shape* shape, const bns_spec* spec, uint64_t seed,

@@ -264,7 +264,7 @@ __device__ __forceinline__ bool in_hw(const bns_box& b, uint32_t h, uint32_t w) 
 
 // ---------------------------------------------------------------------------------------
 // sampled elements a thread reads ahead of its vectors (more: in a loop after them); registers decide how many
-constexpr int patch_loads(int kmax) { return kmax >= 50 ? 2 : 4; }
+constexpr int patch_loads(int kmax, bool mixed) { return (kmax >= 50 || (mixed && kmax >= 16)) ? 2 : 4; }
 
 // Offset of sampled element q of a channel from its first sampled element.
 __device__ __forceinline__ size_t patch_offset(const FusedArgs& A, uint32_t q, size_t nstride) {
@@ -311,7 +311,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
         // vectors, so they are read on their own, element q = (n, ph, pw) by thread q mod (T * NT), BEFORE the
         // vectors of the channel.  Loads return in order, so the statistics and the exchange then run while
         // the vectors are still on their way, and no vector has to be masked element by element.
-        constexpr int kPatchLoads = patch_loads(KMAX);
+        constexpr int kPatchLoads = patch_loads(KMAX, MIXED);
         float pe[PATCH ? kPatchLoads : 1];
         const uint32_t q0 = uint32_t(j) * NT + threadIdx.x;
         if constexpr (PATCH) {
@@ -809,9 +809,10 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
         // every plane (the second read then fetches scattered pieces of lines), both tensors stay on chip:
         // up to (512 threads, 8 + 8 vectors), the register cost of (512, 16).  Measured at 64x256x56x56 fp32:
         // full BN 153 -> 130 us, Feature Sampling 134 -> 127; 128x64x32x32 Feature Sampling 30 -> 22.
-        // Whole planes of a few samples (Batch Sampling, VDN) re-read little and lose more to the larger teams.
+        // Whole planes of a few samples (Batch Sampling, VDN) re-read little and lose more to the larger teams;
+        // Eq. 4 reads two sets again and gains (130x128x28x28, 2 virtual + 4 of 128 real samples: 39 -> 36 us).
         constexpr int kKeepXLast = 3;                                        // {512, 8}
-        const bool keep_x = g_tuning.fused_keep_x == 1 || (g_tuning.fused_keep_x == 0 && (everything || patch));
+        const bool keep_x = g_tuning.fused_keep_x == 1 || (g_tuning.fused_keep_x == 0 && (everything || patch || mix));
         if (backward && keep_x) {
             kind |= 2;
             Plan p;
