@@ -81,6 +81,11 @@ def load(reload: bool = False):
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} not found: build it with `python __graft_entry__.py` "
                           "(there is no CPU fallback)")
+    # PyTorch ships a HIP runtime of its own.  The device memory and streams this binding hands to the library
+    # come from it, so it has to be the one runtime in the process: loaded before libbns.so, whose dependency
+    # on libamdhip64 then resolves to it.  (The other order puts two runtimes side by side; launches then fail
+    # or crash.)
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     for name, (res, args) in _PROTOS.items():
         fn = getattr(lib, name)

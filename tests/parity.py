@@ -69,7 +69,7 @@ def scaled_err(got, ref, floor=0.0):
             floor = floor[None, :, None, None]
         rms = np.maximum(rms, floor)
     else:
-        rms = max(np.sqrt(np.mean(ref ** 2)), float(np.max(floor)))
+        rms = np.maximum(np.sqrt(np.mean(ref ** 2)), np.asarray(floor, dtype=np.float64))   # scalar or per channel
     return float(np.max(np.abs(got - ref) / (np.abs(ref) + rms + 1e-300)))
 
 
@@ -85,6 +85,21 @@ def direct_term_rms(inp, ref, channels=None):
     return np.sqrt(np.mean((a * inp["dy"][:, ch].astype(np.float64)) ** 2, axis=(0, 2, 3)))
 
 
+def summand_scale(inp, ref, channels=None):
+    """Per channel, sqrt(m) * RMS of the m summands of dbeta (dy) and of dgamma (dy * x^): the size such a
+    sum has when its terms do not happen to cancel.
+
+    dbeta and dgamma are sums of m signed terms.  With many channels the RMS over channels is that size;
+    with one channel (or a few) it is whatever the one sum came to, and a sum that lands near zero by
+    chance would be held to an absolute accuracy no fp32 summation of its terms has."""
+    ch = slice(None) if channels is None else np.asarray(channels)
+    dy = inp["dy"][:, ch].astype(np.float64)
+    xh = (inp["x"][:, ch].astype(np.float64) - ref["save_mean"][None, :, None, None]) * ref["save_invstd"][None, :, None, None]
+    m = dy.shape[0] * dy.shape[2] * dy.shape[3]
+    return dict(dbeta=np.sqrt(m * np.mean(dy ** 2, axis=(0, 2, 3))),
+                dgamma=np.sqrt(m * np.mean((dy * xh) ** 2, axis=(0, 2, 3))))
+
+
 def assert_parity(res, ref, wl, channels=None, what="", inp=None):
     tol_t = TOL_F32 if wl.dtype == "f32" else TOL_BF16
     errs = {}
@@ -95,7 +110,15 @@ def assert_parity(res, ref, wl, channels=None, what="", inp=None):
         assert g.shape == r.shape, (k, g.shape, r.shape)
         assert np.isfinite(g).all(), f"{what} {k}: non-finite output"
         tol = tol_t if k in ("y", "dx") else TOL_F32          # per-channel vectors are fp32 in every mode
-        floor = direct_term_rms(inp, ref, channels) if (k == "dx" and inp is not None) else 0.0
+        floor = 0.0
+        if inp is not None and k == "dx":
+            floor = direct_term_rms(inp, ref, channels)
+        elif inp is not None and k in ("dgamma", "dbeta"):
+            floor = summand_scale(inp, ref, channels)[k]
+        elif k in ("save_mean", "running_mean"):
+            # a mean is known to eps times the spread of what was averaged; with one or a few channels the RMS over
+            # channels can be a mean that happens to lie near zero
+            floor = (wl.momentum if k == "running_mean" else 1.0) / np.asarray(ref["save_invstd"], dtype=np.float64)
         errs[k] = scaled_err(g, r, floor)
         assert errs[k] <= tol, f"{what} {k}: scaled error {errs[k]:.3e} > {tol:g}"
     return errs

@@ -1,0 +1,74 @@
+"""Seeded random sweep over shapes, modes, storage types, layouts and kernel paths: every draw is one
+forward + backward through the C ABI against the oracle.  The hand-picked cases elsewhere cover the
+known corners; this one is for the corners nobody thought of (patches as wide as the plane, one
+sample, one channel, planes of a single vector, ...)."""
+import numpy as np
+import pytest
+
+from paper_1810_10962_amd import bns, workloads
+from paper_1810_10962_amd.workloads import BS, FS, FULL, NS, VDN, Workload
+from parity import assert_parity, oracle_boxes, oracle_boxes_mixed, oracle_reference
+
+pytestmark = pytest.mark.gpu
+
+
+def _draw(rng):
+    if rng.integers(0, 8) == 0:                 # now and then a channel that needs a team of blocks
+        N = int(rng.integers(16, 49))
+        C_ = int(rng.choice([8, 24, 40]))
+        H = W = int(rng.choice([14, 28, 56]))
+    else:
+        N = int(rng.integers(1, 14))
+        C_ = int(rng.choice([1, 2, 3, 4, 7, 8, 12, 16, 33, 40, 64, 130]))
+        H = int(rng.choice([1, 2, 3, 4, 6, 7, 8, 12, 14, 16, 20]))
+        W = int(rng.choice([1, 2, 3, 4, 6, 7, 8, 12, 14, 16, 28]))
+    dtype = str(rng.choice(["f32", "bf16"]))
+    layout = str(rng.choice(["nchw", "nhwc"]))
+    mixed = bool(rng.integers(0, 3) == 0) and N >= 3
+    n_v = int(rng.integers(1, min(3, N - 2) + 1)) if mixed else 0
+    real = N - n_v
+    modes = [FULL, NS, BS, FS] + ([] if mixed or N < 2 else [VDN])
+    mode = int(rng.choice(modes))
+    kw = dict(mode=mode)
+    if mode in (NS, BS):
+        kw["n_s"] = int(rng.integers(1, real + 1))
+    elif mode == VDN:
+        kw["n_s"] = int(rng.integers(1, N))
+    elif mode == FS:
+        kw["patch_h"] = int(rng.integers(1, H + 1))
+        kw["patch_w"] = int(rng.integers(1, W + 1))
+        kw["fs_per_channel"] = int(rng.integers(0, 2)) if layout == "nchw" else 0
+    path = int(rng.choice([0, 0, 1, 2]))
+    return Workload(name="rnd", N=N, C=C_, H=H, W=W, dtype=dtype, layout=layout, n_v=n_v,
+                    mix_beta=float(rng.choice([0.0, 0.25, 0.5, 1.0])), data_seed=int(rng.integers(0, 2 ** 31)),
+                    sampling_seed=int(rng.integers(0, 2 ** 62)), layer_id=int(rng.integers(0, 2 ** 32)),
+                    epoch=int(rng.integers(0, 2 ** 32)), eps=float(rng.choice([1e-5, 1e-3])),
+                    momentum=float(rng.choice([0.1, 0.3, 1.0])), **kw), path
+
+
+@pytest.mark.parametrize("chunk", range(20))
+def test_random_configurations(chunk):
+    rng = np.random.default_rng(20181026 + chunk)
+    done = fused_refused = 0
+    for i in range(40):
+        wl, path = _draw(rng)
+        print(f"[gpu-case] random {chunk}/{i}: {wl.shape} {wl.dtype} {wl.layout} mode={wl.mode} n_s={wl.n_s} "
+              f"patch={wl.patch_h}x{wl.patch_w} pc={wl.fs_per_channel} n_v={wl.n_v} beta={wl.mix_beta} path={path}",
+              flush=True)
+        inp = workloads.make_inputs(wl)
+        bns.bns_set_option("path", path)
+        try:
+            res = bns.run_workload(wl, inp)
+        except bns.BnsError as e:
+            # forcing the single-launch kernels is allowed to be refused (layout, scalar Eq. 4, channel too large)
+            assert path == 2 and e.status == bns.BNS_EUNSUPPORTED, (wl, path, e)
+            fused_refused += 1
+            continue
+        finally:
+            bns.bns_set_option("path", 0)
+        mixed = wl.n_v and wl.mode != VDN
+        boxes = oracle_boxes_mixed(wl)[1] if mixed else oracle_boxes(wl)
+        assert (res["boxes"] == boxes).all()
+        assert_parity(res, oracle_reference(wl, inp), wl, what=f"random {chunk}/{i} {wl}", inp=inp)
+        done += 1
+    assert done >= 25 and fused_refused <= 15
