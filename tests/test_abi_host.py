@@ -218,3 +218,22 @@ def test_layout_field_is_validated_and_nhwc_limits_are_reported():
     assert lib.bns_forward(C.byref(shape), C.byref(shared), 1, P(x), P(v), P(v + 128), C.c_float(1e-5), C.c_float(0.1),
                            P(y), P(v + 256), P(v + 384), None, None, P(ws),
                            bns.bns_workspace_bytes(shape, shared) - 1, None) == bns.BNS_EWORKSPACE
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/bns.h compiles as C99 with warnings as errors, and every declared function can be named from C."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    names = bns.declared_symbols()
+    src = tmp_path / "use_bns.c"
+    body = "\n".join(f"    table[{i}] = (void (*)(void)){n};" for i, n in enumerate(names))
+    src.write_text('#include "bns.h"\n'
+                   f"void (*table[{len(names)}])(void);\n"
+                   "void fill(void) {\n" + body + "\n}\n"
+                   "int sizes[3] = {sizeof(bns_shape), sizeof(bns_spec), sizeof(bns_box)};\n")
+    out = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(root, "include"),
+                          "-c", str(src), "-o", str(tmp_path / "use_bns.o")], capture_output=True, text=True)
+    assert out.returncode == 0, out.stderr
+    # the ctypes mirrors of the structs have the C sizes
+    assert C.sizeof(bns.bns_shape) == 24 and C.sizeof(bns.bns_spec) == 28 and C.sizeof(bns.bns_box) == 24
