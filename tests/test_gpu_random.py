@@ -69,6 +69,17 @@ def test_random_configurations(chunk):
         mixed = wl.n_v and wl.mode != VDN
         boxes = oracle_boxes_mixed(wl)[1] if mixed else oracle_boxes(wl)
         assert (res["boxes"] == boxes).all()
-        assert_parity(res, oracle_reference(wl, inp), wl, what=f"random {chunk}/{i} {wl}", inp=inp)
+        ref = oracle_reference(wl, inp)
+        assert_parity(res, ref, wl, what=f"random {chunk}/{i} {wl}", inp=inp)
+        if not mixed and i % 3 == 0:            # the four stage calls on fresh buffers give the same
+            buf = bns.Buffers(wl, inp)
+            bns.bns_forward_stats(buf.shape, buf.spec, buf.seed, buf.x, wl.eps, wl.momentum, buf.save_mean,
+                                  buf.save_invstd, buf.running_mean, buf.running_var, buf.workspace)
+            bns.bns_forward_normalize(buf.shape, buf.x, buf.gamma, buf.beta, buf.save_mean, buf.save_invstd, buf.y)
+            bns.bns_backward_reduce(buf.shape, buf.x, buf.dy, buf.save_mean, buf.save_invstd, buf.dgamma, buf.dbeta,
+                                    buf.workspace)
+            bns.bns_backward_dx(buf.shape, buf.spec, buf.seed, buf.x, buf.dy, buf.gamma, buf.save_mean,
+                                buf.save_invstd, buf.dgamma, buf.dbeta, buf.dx)
+            assert_parity(buf.results(), ref, wl, what=f"random {chunk}/{i} stages {wl}", inp=inp)
         done += 1
     assert done >= 25 and fused_refused <= 15
