@@ -7,6 +7,15 @@
 
 #include "bns_index.hpp"
 
+// Kernel launch whose status the following hipGetLastError() reports: the thread's last-error state may
+// still hold a failure of some earlier, unrelated runtime call (the caller's, the framework's), which must
+// not be taken for this launch's, so it is cleared first.
+#define BNS_LAUNCH(...)                  \
+    do {                                 \
+        (void)hipGetLastError();         \
+        hipLaunchKernelGGL(__VA_ARGS__); \
+    } while (0)
+
 namespace bns {
 
 constexpr int kMaxSplits = 64;  // upper bound on blocks that share one channel's reduction

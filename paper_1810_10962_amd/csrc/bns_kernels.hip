@@ -605,9 +605,9 @@ hipError_t launch_stats_partial(const Dims& d, const IndexParams& ip, const void
             const uint32_t hwv = uint32_t(d.HW / V);
             const uint32_t tot = uint32_t(b.n_cnt) * hwv;
             const uint32_t per_block = ceil_div(tot, uint32_t(splits));
-            hipLaunchKernelGGL((stats_partial_planes_kernel<T, V>), grid, dim3(kBlock), 0, st,
-                               static_cast<const T*>(x), partial, ip, d.C, d.HW, make_fastdiv(hwv), c0, splits,
-                               per_block);
+            BNS_LAUNCH((stats_partial_planes_kernel<T, V>), grid, dim3(kBlock), 0, st,
+                       static_cast<const T*>(x), partial, ip, d.C, d.HW, make_fastdiv(hwv), c0, splits,
+                       per_block);
             return hipGetLastError();
         });
     }
@@ -615,13 +615,13 @@ hipError_t launch_stats_partial(const Dims& d, const IndexParams& ip, const void
     const uint32_t tot = uint32_t(b.n_cnt) * patch;
     const uint32_t per_block = ceil_div(tot, uint32_t(splits));
     if (d.dtype == BNS_F32)
-        hipLaunchKernelGGL((stats_partial_patch_kernel<float>), grid, dim3(kBlock), 0, st,
-                           static_cast<const float*>(x), partial, ip, d.C, d.W, d.HW, make_fastdiv(patch),
-                           make_fastdiv(uint32_t(b.w_cnt)), c0, splits, per_block);
+        BNS_LAUNCH((stats_partial_patch_kernel<float>), grid, dim3(kBlock), 0, st,
+                   static_cast<const float*>(x), partial, ip, d.C, d.W, d.HW, make_fastdiv(patch),
+                   make_fastdiv(uint32_t(b.w_cnt)), c0, splits, per_block);
     else
-        hipLaunchKernelGGL((stats_partial_patch_kernel<bf16_t>), grid, dim3(kBlock), 0, st,
-                           static_cast<const bf16_t*>(x), partial, ip, d.C, d.W, d.HW, make_fastdiv(patch),
-                           make_fastdiv(uint32_t(b.w_cnt)), c0, splits, per_block);
+        BNS_LAUNCH((stats_partial_patch_kernel<bf16_t>), grid, dim3(kBlock), 0, st,
+                   static_cast<const bf16_t*>(x), partial, ip, d.C, d.W, d.HW, make_fastdiv(patch),
+                   make_fastdiv(uint32_t(b.w_cnt)), c0, splits, per_block);
     return hipGetLastError();
 }
 
@@ -642,14 +642,14 @@ bool launch_stats_one_block(const Dims& d, const IndexParams& ip, const void* x,
         using T = decltype(t);
         constexpr int V = decltype(vt)::value;
         if (planes)
-            hipLaunchKernelGGL((stats_one_block_kernel<T, V, true>), grid, blk, 0, st, static_cast<const T*>(x), ip, d.C,
-                               d.W, d.HW, make_fastdiv(hwv), make_fastdiv(patch), make_fastdiv(uint32_t(b.w_cnt)), c0,
-                               eps, momentum, save_mean, save_invstd, running_mean, running_var);
+            BNS_LAUNCH((stats_one_block_kernel<T, V, true>), grid, blk, 0, st, static_cast<const T*>(x), ip, d.C,
+                       d.W, d.HW, make_fastdiv(hwv), make_fastdiv(patch), make_fastdiv(uint32_t(b.w_cnt)), c0,
+                       eps, momentum, save_mean, save_invstd, running_mean, running_var);
         else
-            hipLaunchKernelGGL((stats_one_block_kernel<T, V, false>), grid, blk, 0, st, static_cast<const T*>(x), ip,
-                               d.C, d.W, d.HW, make_fastdiv(hwv), make_fastdiv(patch),
-                               make_fastdiv(uint32_t(b.w_cnt)), c0, eps, momentum, save_mean, save_invstd, running_mean,
-                               running_var);
+            BNS_LAUNCH((stats_one_block_kernel<T, V, false>), grid, blk, 0, st, static_cast<const T*>(x), ip,
+                       d.C, d.W, d.HW, make_fastdiv(hwv), make_fastdiv(patch),
+                       make_fastdiv(uint32_t(b.w_cnt)), c0, eps, momentum, save_mean, save_invstd, running_mean,
+                       running_var);
         return hipGetLastError();
     });
     return true;
@@ -660,13 +660,13 @@ hipError_t launch_stats_finalize(const Dims& d, const IndexParams& ip, const voi
                                  float* save_invstd, float* running_mean, float* running_var, hipStream_t st) {
     const dim3 grid(ceil_div(uint32_t(cg), kBlock / kWave));
     if (d.dtype == BNS_F32)
-        hipLaunchKernelGGL((stats_finalize_kernel<float>), grid, dim3(kBlock), 0, st,
-                           static_cast<const float*>(x), partial, ip, d.C, d.W, d.HW, splits, c0, cg, eps, momentum,
-                           save_mean, save_invstd, running_mean, running_var);
+        BNS_LAUNCH((stats_finalize_kernel<float>), grid, dim3(kBlock), 0, st,
+                   static_cast<const float*>(x), partial, ip, d.C, d.W, d.HW, splits, c0, cg, eps, momentum,
+                   save_mean, save_invstd, running_mean, running_var);
     else
-        hipLaunchKernelGGL((stats_finalize_kernel<bf16_t>), grid, dim3(kBlock), 0, st,
-                           static_cast<const bf16_t*>(x), partial, ip, d.C, d.W, d.HW, splits, c0, cg, eps, momentum,
-                           save_mean, save_invstd, running_mean, running_var);
+        BNS_LAUNCH((stats_finalize_kernel<bf16_t>), grid, dim3(kBlock), 0, st,
+                   static_cast<const bf16_t*>(x), partial, ip, d.C, d.W, d.HW, splits, c0, cg, eps, momentum,
+                   save_mean, save_invstd, running_mean, running_var);
     return hipGetLastError();
 }
 
@@ -677,14 +677,14 @@ hipError_t launch_stats_finalize_mixed(const Dims& d, const IndexParams& ip_s, c
                                        float* running_var, hipStream_t st) {
     const dim3 grid(ceil_div(uint32_t(d.C), kBlock / kWave));
     if (d.dtype == BNS_F32)
-        hipLaunchKernelGGL((stats_finalize_mixed_kernel<float>), grid, dim3(kBlock), 0, st,
-                           static_cast<const float*>(x), partial_s, splits_s, partial_v, splits_v, ip_s, ip_v, d.C, d.W,
-                           d.HW, mix_beta, eps, momentum, save_mean, save_invstd, mean_parts, running_mean, running_var);
+        BNS_LAUNCH((stats_finalize_mixed_kernel<float>), grid, dim3(kBlock), 0, st,
+                   static_cast<const float*>(x), partial_s, splits_s, partial_v, splits_v, ip_s, ip_v, d.C, d.W,
+                   d.HW, mix_beta, eps, momentum, save_mean, save_invstd, mean_parts, running_mean, running_var);
     else
-        hipLaunchKernelGGL((stats_finalize_mixed_kernel<bf16_t>), grid, dim3(kBlock), 0, st,
-                           static_cast<const bf16_t*>(x), partial_s, splits_s, partial_v, splits_v, ip_s, ip_v, d.C,
-                           d.W, d.HW, mix_beta, eps, momentum, save_mean, save_invstd, mean_parts, running_mean,
-                           running_var);
+        BNS_LAUNCH((stats_finalize_mixed_kernel<bf16_t>), grid, dim3(kBlock), 0, st,
+                   static_cast<const bf16_t*>(x), partial_s, splits_s, partial_v, splits_v, ip_s, ip_v, d.C,
+                   d.W, d.HW, mix_beta, eps, momentum, save_mean, save_invstd, mean_parts, running_mean,
+                   running_var);
     return hipGetLastError();
 }
 
@@ -700,9 +700,9 @@ hipError_t launch_normalize(const Dims& d, const void* x, const float* gamma, co
             const uint32_t hwv = uint32_t(d.HW / V);
             const uint32_t run_vectors = uint32_t(cg) * hwv;
             const dim3 grid(ceil_div(run_vectors, kBlock * U), uint32_t(d.N));
-            hipLaunchKernelGGL((normalize_kernel<T, V, U, NT>), grid, dim3(kBlock), 0, st, static_cast<const T*>(x),
-                               static_cast<T*>(y), gamma, beta, mean, invstd, d.C, d.HW, make_fastdiv(hwv), c0,
-                               run_vectors, var_eps);
+            BNS_LAUNCH((normalize_kernel<T, V, U, NT>), grid, dim3(kBlock), 0, st, static_cast<const T*>(x),
+                       static_cast<T*>(y), gamma, beta, mean, invstd, d.C, d.HW, make_fastdiv(hwv), c0,
+                       run_vectors, var_eps);
             return hipGetLastError();
         });
     });
@@ -720,9 +720,9 @@ hipError_t launch_reduce_partial(const Dims& d, const void* x, const void* dy, c
             const uint32_t tot = uint32_t(d.N) * hwv;
             const uint32_t per_block = ceil_div(tot, uint32_t(splits));
             const dim3 grid(uint32_t(cg) * uint32_t(splits));
-            hipLaunchKernelGGL((reduce_partial_kernel<T, V, U, NT>), grid, dim3(kBlock), 0, st,
-                               static_cast<const T*>(x), static_cast<const T*>(dy), mean, partial, d.C, d.HW,
-                               make_fastdiv(hwv), c0, splits, per_block, tot);
+            BNS_LAUNCH((reduce_partial_kernel<T, V, U, NT>), grid, dim3(kBlock), 0, st,
+                       static_cast<const T*>(x), static_cast<const T*>(dy), mean, partial, d.C, d.HW,
+                       make_fastdiv(hwv), c0, splits, per_block, tot);
             return hipGetLastError();
         });
     });
@@ -731,8 +731,8 @@ hipError_t launch_reduce_partial(const Dims& d, const void* x, const void* dy, c
 hipError_t launch_reduce_finalize(const Dims& d, const Partial* partial, int splits, int c0, int cg,
                                   const float* invstd, float* dgamma, float* dbeta, hipStream_t st) {
     (void)d;
-    hipLaunchKernelGGL(reduce_finalize_kernel, dim3(ceil_div(uint32_t(cg), kBlock / kWave)), dim3(kBlock), 0, st, partial,
-                       splits, c0, cg, invstd, dgamma, dbeta);
+    BNS_LAUNCH(reduce_finalize_kernel, dim3(ceil_div(uint32_t(cg), kBlock / kWave)), dim3(kBlock), 0, st, partial,
+               splits, c0, cg, invstd, dgamma, dbeta);
     return hipGetLastError();
 }
 
@@ -757,17 +757,17 @@ hipError_t launch_dx(const Dims& d, const IndexParams& ip, const void* x, const 
             const uint32_t hwv = uint32_t(d.HW / V);
             const uint32_t run_vectors = uint32_t(cg) * hwv;
             const dim3 grid(ceil_div(run_vectors, kBlock * U), uint32_t(d.N));
-            hipLaunchKernelGGL((dx_kernel<T, V, U, NT>), grid, dim3(kBlock), 0, st, static_cast<const T*>(x),
-                               static_cast<const T*>(dy), static_cast<T*>(dx), gamma, mean, invstd, dgamma, dbeta,
-                               ip, d.C, d.W, d.HW, make_fastdiv(hwv), make_fastdiv(uint32_t(d.W)), c0, run_vectors,
-                               sets);
+            BNS_LAUNCH((dx_kernel<T, V, U, NT>), grid, dim3(kBlock), 0, st, static_cast<const T*>(x),
+                       static_cast<const T*>(dy), static_cast<T*>(dx), gamma, mean, invstd, dgamma, dbeta,
+                       ip, d.C, d.W, d.HW, make_fastdiv(hwv), make_fastdiv(uint32_t(d.W)), c0, run_vectors,
+                       sets);
             return hipGetLastError();
         });
     });
 }
 
 hipError_t launch_index_boxes(const IndexParams& ip, int C, bns_box* boxes, hipStream_t st) {
-    hipLaunchKernelGGL(index_boxes_kernel, dim3(ceil_div(uint32_t(C), kBlock)), dim3(kBlock), 0, st, ip, C, boxes);
+    BNS_LAUNCH(index_boxes_kernel, dim3(ceil_div(uint32_t(C), kBlock)), dim3(kBlock), 0, st, ip, C, boxes);
     return hipGetLastError();
 }
 
@@ -775,8 +775,8 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st)
     const size_t n16 = bytes / 16;
     if (n16 == 0) return hipSuccess;
     const size_t blocks = (n16 + kBlock * 4 - 1) / (kBlock * 4);
-    hipLaunchKernelGGL(copy_kernel, dim3(uint32_t(blocks)), dim3(kBlock), 0, st, static_cast<const uint4*>(src),
-                       static_cast<uint4*>(dst), n16);
+    BNS_LAUNCH(copy_kernel, dim3(uint32_t(blocks)), dim3(kBlock), 0, st, static_cast<const uint4*>(src),
+               static_cast<uint4*>(dst), n16);
     return hipGetLastError();
 }
 

@@ -864,13 +864,13 @@ hipError_t launch_nhwc_stats(const Dims& d, const bns_box& b, const void* x, Par
     return dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
         constexpr int V = decltype(vt)::value;
-        hipLaunchKernelGGL((nhwc_stats_partial_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st,
-                           static_cast<const T*>(x), partial, S, t);
+        BNS_LAUNCH((nhwc_stats_partial_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st,
+                   static_cast<const T*>(x), partial, S, t);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((nhwc_stats_finalize_kernel<T>), dim3(ceil_div_u(uint32_t(d.C), kFinCh)), dim3(kBlock), 0, st,
-                           static_cast<const T*>(x), partial, S, d.C, t.splits, eps, momentum, save_mean, save_invstd,
-                           running_mean, running_var);
+        BNS_LAUNCH((nhwc_stats_finalize_kernel<T>), dim3(ceil_div_u(uint32_t(d.C), kFinCh)), dim3(kBlock), 0, st,
+                   static_cast<const T*>(x), partial, S, d.C, t.splits, eps, momentum, save_mean, save_invstd,
+                   running_mean, running_var);
         return hipGetLastError();
     });
 }
@@ -882,8 +882,8 @@ hipError_t launch_nhwc_normalize(const Dims& d, const void* x, const float* gamm
     return dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
         constexpr int V = decltype(vt)::value;
-        hipLaunchKernelGGL((nhwc_normalize_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st, static_cast<const T*>(x),
-                           static_cast<T*>(y), gamma, beta, mean, invstd, t, M, var_eps);
+        BNS_LAUNCH((nhwc_normalize_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st, static_cast<const T*>(x),
+                   static_cast<T*>(y), gamma, beta, mean, invstd, t, M, var_eps);
         return hipGetLastError();
     });
 }
@@ -895,12 +895,12 @@ hipError_t launch_nhwc_reduce(const Dims& d, const void* x, const void* dy, cons
     return dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
         constexpr int V = decltype(vt)::value;
-        hipLaunchKernelGGL((nhwc_reduce_partial_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st,
-                           static_cast<const T*>(x), static_cast<const T*>(dy), mean, partial, t, M);
+        BNS_LAUNCH((nhwc_reduce_partial_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st,
+                   static_cast<const T*>(x), static_cast<const T*>(dy), mean, partial, t, M);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(nhwc_reduce_finalize_kernel, dim3(ceil_div_u(uint32_t(d.C), kFinCh)), dim3(kBlock), 0, st,
-                           partial, d.C, t.splits, invstd, dgamma, dbeta);
+        BNS_LAUNCH(nhwc_reduce_finalize_kernel, dim3(ceil_div_u(uint32_t(d.C), kFinCh)), dim3(kBlock), 0, st,
+                   partial, d.C, t.splits, invstd, dgamma, dbeta);
         return hipGetLastError();
     });
 }
@@ -915,9 +915,9 @@ hipError_t launch_nhwc_dx(const Dims& d, const bns_box& b, const void* x, const 
     return dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
         constexpr int V = decltype(vt)::value;
-        hipLaunchKernelGGL((nhwc_dx_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st, static_cast<const T*>(x),
-                           static_cast<const T*>(dy), static_cast<T*>(dx), gamma, mean, invstd, dgamma, dbeta, B, t, M,
-                           float(1.0 / s));
+        BNS_LAUNCH((nhwc_dx_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st, static_cast<const T*>(x),
+                   static_cast<const T*>(dy), static_cast<T*>(dx), gamma, mean, invstd, dgamma, dbeta, B, t, M,
+                   float(1.0 / s));
         return hipGetLastError();
     });
 }
@@ -932,9 +932,9 @@ bool launch_nhwc_small_forward(const Dims& d, const bns_box& b, const void* x, c
     *err = dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
         constexpr int V = decltype(vt)::value;
-        hipLaunchKernelGGL((nhwc_small_forward_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st,
-                           static_cast<const T*>(x), static_cast<T*>(y), gamma, beta, S, t, M, eps, momentum, save_mean,
-                           save_invstd, running_mean, running_var);
+        BNS_LAUNCH((nhwc_small_forward_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st,
+                   static_cast<const T*>(x), static_cast<T*>(y), gamma, beta, S, t, M, eps, momentum, save_mean,
+                   save_invstd, running_mean, running_var);
         return hipGetLastError();
     });
     return true;
@@ -951,9 +951,9 @@ bool launch_nhwc_small_backward(const Dims& d, const bns_box& b, const void* x, 
     *err = dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
         constexpr int V = decltype(vt)::value;
-        hipLaunchKernelGGL((nhwc_small_backward_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st,
-                           static_cast<const T*>(x), static_cast<const T*>(dy), static_cast<T*>(dx), gamma, mean, invstd,
-                           dgamma, dbeta, B, t, M, float(1.0 / s));
+        BNS_LAUNCH((nhwc_small_backward_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st,
+                   static_cast<const T*>(x), static_cast<const T*>(dy), static_cast<T*>(dx), gamma, mean, invstd,
+                   dgamma, dbeta, B, t, M, float(1.0 / s));
         return hipGetLastError();
     });
     return true;
@@ -971,16 +971,16 @@ hipError_t launch_nhwc_stats_mixed(const Dims& d, const bns_box& b, int n_v, con
     return dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
         constexpr int V = decltype(vt)::value;
-        hipLaunchKernelGGL((nhwc_stats_partial_kernel<T, V>), dim3(grid_of(ts)), dim3(kBlock), 0, st,
-                           static_cast<const T*>(x), partial, S, ts);
+        BNS_LAUNCH((nhwc_stats_partial_kernel<T, V>), dim3(grid_of(ts)), dim3(kBlock), 0, st,
+                   static_cast<const T*>(x), partial, S, ts);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((nhwc_stats_partial_kernel<T, V>), dim3(grid_of(tv)), dim3(kBlock), 0, st,
-                           static_cast<const T*>(x), partial_v, Vs, tv);
+        BNS_LAUNCH((nhwc_stats_partial_kernel<T, V>), dim3(grid_of(tv)), dim3(kBlock), 0, st,
+                   static_cast<const T*>(x), partial_v, Vs, tv);
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        hipLaunchKernelGGL((nhwc_stats_finalize_mixed_kernel<T>), dim3(ceil_div_u(uint32_t(d.C), kFinCh)), dim3(kBlock), 0,
-                           st, static_cast<const T*>(x), partial, ts.splits, partial_v, tv.splits, S, Vs, d.C, mix_beta, eps,
-                           momentum, save_mean, save_invstd, mean_parts, running_mean, running_var);
+        BNS_LAUNCH((nhwc_stats_finalize_mixed_kernel<T>), dim3(ceil_div_u(uint32_t(d.C), kFinCh)), dim3(kBlock), 0,
+                   st, static_cast<const T*>(x), partial, ts.splits, partial_v, tv.splits, S, Vs, d.C, mix_beta, eps,
+                   momentum, save_mean, save_invstd, mean_parts, running_mean, running_var);
         return hipGetLastError();
     });
 }
@@ -996,9 +996,9 @@ hipError_t launch_nhwc_dx_mixed(const Dims& d, const bns_box& b, int n_v, float 
     return dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
         constexpr int V = decltype(vt)::value;
-        hipLaunchKernelGGL((nhwc_dx_mixed_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st, static_cast<const T*>(x),
-                           static_cast<const T*>(dy), static_cast<T*>(dx), gamma, invstd, dgamma, dbeta, mean_parts,
-                           mean_parts + d.C, B, uint32_t(n_v) * uint32_t(d.HW), w_v, w_s, t, M);
+        BNS_LAUNCH((nhwc_dx_mixed_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st, static_cast<const T*>(x),
+                   static_cast<const T*>(dy), static_cast<T*>(dx), gamma, invstd, dgamma, dbeta, mean_parts,
+                   mean_parts + d.C, B, uint32_t(n_v) * uint32_t(d.HW), w_v, w_s, t, M);
         return hipGetLastError();
     });
 }
