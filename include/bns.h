@@ -228,7 +228,8 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  *   "path"           1: only the streaming kernels (statistics / normalise / reduce / dx, several
  *                    launches per direction); 2: only the fused single-launch kernels, which keep a
  *                    channel in registers between its reduction and its element-wise pass
- *                    (BNS_EUNSUPPORTED if a channel does not fit); 0: whichever is faster for the shape
+ *                    (BNS_EUNSUPPORTED if a channel does not fit or the layout is N x H x W x C, which has
+ *                    none); 0: whichever is faster for the shape
  *   "fused_variant"  1..7: block size / registers-per-thread variant of the fused kernels
  *   "fused_coop"     1: launch the fused kernels with hipLaunchCooperativeKernel
  *   "fused_keep_x"   the fused backward kernel keeps x in registers beside dy instead of reading it again

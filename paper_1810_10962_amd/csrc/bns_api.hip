@@ -16,8 +16,8 @@ namespace {
 std::atomic<int32_t> g_splits_stats{0};
 std::atomic<int32_t> g_splits_reduce{0};
 std::atomic<int32_t> g_channel_group{0};
-std::atomic<int32_t> g_last_path_forward{0};    // what the last bns_forward / bns_backward launched:
-std::atomic<int32_t> g_last_path_backward{0};   // 1 = streaming kernels, 2 = fused single-launch kernel
+std::atomic<int32_t> g_last_path_forward{0};    // what the last forward / backward call launched: 1 = streaming kernels,
+std::atomic<int32_t> g_last_path_backward{0};   // 2 = fused single-launch kernel, 3 = one-launch kernel for small N x H x W x C tensors
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -442,6 +442,8 @@ bns_status bns_forward_mixed(const bns_shape* shape, const bns_spec* spec, uint6
     hipStream_t st = static_cast<hipStream_t>(stream);
     const IndexParams ip_s = make_index_params_mixed(*shape, *spec, seed, n_v);
     if (nhwc(d)) {
+        if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
+        g_last_path_forward.store(1);
         if (launch_nhwc_stats_mixed(d, ip_s.shared, n_v, x, static_cast<Partial*>(workspace), mix_beta, eps, momentum,
                                     save_mean, save_invstd, save_mean_parts, running_mean, running_var, st) != hipSuccess)
             return BNS_EDEVICE;
@@ -502,6 +504,8 @@ bns_status bns_backward_mixed(const bns_shape* shape, const bns_spec* spec, uint
     hipStream_t st = static_cast<hipStream_t>(stream);
     const IndexParams ip_s = make_index_params_mixed(*shape, *spec, seed, n_v);
     if (nhwc(d)) {
+        if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
+        g_last_path_backward.store(1);
         if (launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, static_cast<Partial*>(workspace), dgamma, dbeta, st) !=
             hipSuccess)
             return BNS_EDEVICE;
