@@ -28,6 +28,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <chrono>
 #include <mutex>
 
 #include "bns_device.hpp"
@@ -680,7 +681,17 @@ int combo_index(const Dims& d) {
     return d.vec == 8 ? 2 : d.vec == 4 ? 3 : 4;
 }
 
-std::atomic<uint32_t> g_stamp{1};
+// Exchange stamps count up from a start drawn when the library is loaded: a workspace whose memory still holds the
+// slots of an earlier instance of the library in the same process (unloaded and loaded again) then does not meet its
+// old stamps again.
+uint32_t first_stamp() {
+    uint64_t z = uint64_t(std::chrono::steady_clock::now().time_since_epoch().count()) ^
+                 (uint64_t(reinterpret_cast<uintptr_t>(&g_dev)) << 17);
+    z = (z ^ (z >> 30)) * 0xbf58476d1ce4e5b9ull;
+    z = (z ^ (z >> 27)) * 0x94d049bb133111ebull;
+    return uint32_t(z >> 32) | 1u;
+}
+std::atomic<uint32_t> g_stamp{first_stamp()};
 
 }  // namespace
 
