@@ -26,6 +26,15 @@
  *            stream).  Work is enqueued on it and the call returns without
  *            synchronising.  Calls that share a workspace must be ordered on
  *            one stream.
+ * Concurrency The single-launch ("fused") kernels size their grid to what the
+ *            device holds at once and let the blocks that share a channel wait
+ *            for each other.  If other kernels occupy the device at the same
+ *            time (another stream, another process), such a wait can last until
+ *            those finish; it is bounded (2^21 polls), after which the sums of
+ *            that channel are NaN and the kernel still ends: never a hang, and
+ *            never a silently wrong finite value.  Callers that overlap libbns
+ *            with other GPU work set the "path" option to 1: the streaming
+ *            kernels have no waits between blocks.
  * Aliasing   Outputs must not overlap inputs or each other (x is needed again
  *            by the backward pass; dx is written while dy is read).
  * Errors     Every call returns a bns_status.  Arguments are validated on the
@@ -232,6 +241,10 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  *                    none); 0: whichever is faster for the shape
  *   "fused_variant"  1..7: block size / registers-per-thread variant of the fused kernels
  *   "fused_coop"     1: launch the fused kernels with hipLaunchCooperativeKernel
+ *   "fused_spin_limit"  polls a block of a fused kernel waits for a team-mate's sums before it gives up
+ *                    (1..2^21, the default); "fused_mute" 1: no block publishes its sums, so every such wait
+ *                    expires -- the two together let a test reach the give-up path (NaN sums, the kernel
+ *                    ends normally) from the host
  *   "fused_keep_x"   the fused backward kernel keeps x in registers beside dy instead of reading it again
  *                    on S: 1 always, 2 never; 0: when S is the whole tensor or a patch of every plane
  *   "split_statistics"  1: the streaming forward statistics always run as partial sums + finalize

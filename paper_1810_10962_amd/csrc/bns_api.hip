@@ -101,6 +101,8 @@ const TuningEntry kTuningTable[] = {
     {"path", &Tuning::path, 2, 0, false},
     {"fused_variant", &Tuning::fused_variant, 7, 0, false},
     {"fused_coop", &Tuning::fused_coop, 1, 0, false},
+    {"fused_spin_limit", &Tuning::fused_spin_limit, 1 << 21, 0, false},
+    {"fused_mute", &Tuning::fused_mute, 1, 0, false},
     {"fused_keep_x", &Tuning::fused_keep_x, 2, 0, false},
     {"split_statistics", &Tuning::split_statistics, 1, 0, false},
     {"nhwc_blocks", &Tuning::nhwc_blocks, kNhwcBlocksMax, 0, false},

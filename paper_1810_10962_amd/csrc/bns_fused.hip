@@ -113,7 +113,7 @@ struct RawVec<bf16_t, 8> {
 };
 
 constexpr int kMaxTeam = 1024;            // members of a team (T)
-constexpr uint32_t kSpinLimit = 1u << 21; // polls before a missing team-mate is given up on
+constexpr uint32_t kSpinLimit = 1u << 21; // polls before a missing team-mate is given up on (default)
 
 struct FusedArgs {
     const void* x;
@@ -143,6 +143,8 @@ struct FusedArgs {
     float* mean_parts;
     FastDiv patch_div, pw_div;   // h_cnt * w_cnt and w_cnt of S: sampled element q -> (n, ph, pw)
     uint32_t stamp0;
+    uint32_t spin_limit;    // polls before a missing team-mate is given up on
+    int32_t mute;           // 1: members do not publish (host-forced give-up, for tests of that path)
     float eps, momentum, inv_s;
     double s;       // |S| per channel
 };
@@ -177,7 +179,7 @@ __device__ __forceinline__ void block_allsum2(float& a, float& b, float* red) {
 // team_publish: thread 0 writes this member's stamped pair.
 __device__ __forceinline__ void team_publish(const FusedArgs& A, int team_first_block, int j, uint32_t it, float a,
                                              float b) {
-    if (A.T == 1 || threadIdx.x != 0) return;
+    if (A.T == 1 || threadIdx.x != 0 || A.mute) return;
     const uint32_t stamp = A.stamp0 + it;
     unsigned long long* mine = A.slots + (size_t(it & 1u) * gridDim.x + size_t(team_first_block + j)) * 2;
     __hip_atomic_store(mine, (static_cast<unsigned long long>(stamp) << 32) | __float_as_uint(a), __ATOMIC_RELAXED,
@@ -200,7 +202,7 @@ __device__ __forceinline__ void team_collect(const FusedArgs& A, int team_first_
     for (int t = threadIdx.x; t < A.T; t += NT) {
         unsigned long long* theirs = base + size_t(team_first_block + t) * 2;
         float pa = __builtin_nanf(""), pb = __builtin_nanf("");
-        for (uint32_t spin = 0; spin < kSpinLimit; ++spin) {
+        for (uint32_t spin = 0; spin < A.spin_limit; ++spin) {
             const unsigned long long wa = __hip_atomic_load(theirs, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const unsigned long long wb = __hip_atomic_load(theirs + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (uint32_t(wa >> 32) == stamp && uint32_t(wb >> 32) == stamp) {
@@ -872,6 +874,8 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     A.tot = tot;
     const uint32_t rounds = uint32_t((cg + A.num_teams - 1) / A.num_teams);
     A.stamp0 = g_stamp.fetch_add((mix ? 2u : 1u) * rounds + 1u);   // Eq. 4 forward exchanges twice per round
+    A.spin_limit = g_tuning.fused_spin_limit > 0 ? uint32_t(g_tuning.fused_spin_limit) : kSpinLimit;
+    A.mute = g_tuning.fused_mute;
     A.eps = eps;
     A.momentum = momentum;
     const bns_box& b = ip.shared;

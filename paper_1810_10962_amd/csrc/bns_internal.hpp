@@ -43,6 +43,8 @@ struct Tuning {
     int fused_variant = 0;                  // 1..7 forces a (block size, registers) variant of the fused kernels
     int fused_keep_x = 0;                   // backward keeps x in registers next to dy: 1 always, 2 never, 0 when it pays
     int fused_coop = 0;                     // 1: launch the fused kernels with hipLaunchCooperativeKernel
+    int fused_spin_limit = 0;               // polls a team member waits for a team-mate before giving up (default 2^21)
+    int fused_mute = 0;                     // 1 (tests of the give-up path): no member publishes its sums
     int split_statistics = 0;               // 1: forward statistics always as partial sums + finalize
     int nhwc_blocks = 0;                    // blocks an N x H x W x C reduction aims for (default kNhwcBlocks)
     int nhwc_small = 0;                     // 2: never take the one-launch kernels for small N x H x W x C tensors

@@ -344,6 +344,45 @@ def test_fused_backward_with_x_kept_on_chip(variant, shape, mkw, dtype, kernel_p
         assert scaled_err(res[k], plain[k]) <= (2e-5 if k not in ("y", "dx") or dtype == "f32" else 1e-2), k
 
 
+def test_missing_team_mate_ends_in_nan_not_in_a_hang(kernel_path):
+    """The give-up path of the single-launch kernels, forced from the host: with publishing switched off every
+    wait for a team-mate's sums expires after `fused_spin_limit` polls.  The sums are then NaN (never a finite
+    wrong value), the kernels end normally, and the next ordinary call on the same buffers and workspace is right."""
+    if kernel_path != "auto":
+        pytest.skip("forced-fused test runs once")
+    wl = Workload(name="give_up", N=16, C=300, H=16, W=16, dtype="f32", mode=BS, n_s=4, data_seed=9, sampling_seed=15,
+                  layer_id=1, epoch=0)
+    inp = workloads.make_inputs(wl)
+    buf = bns.Buffers(wl, inp)
+
+    def forward_backward():
+        bns.bns_forward(buf.shape, buf.spec, buf.seed, buf.x, buf.gamma, buf.beta, wl.eps, wl.momentum, buf.y,
+                        buf.save_mean, buf.save_invstd, buf.running_mean, buf.running_var, buf.workspace)
+        bns.bns_backward(buf.shape, buf.spec, buf.seed, buf.x, buf.dy, buf.gamma, buf.save_mean, buf.save_invstd, buf.dx,
+                         buf.dgamma, buf.dbeta, buf.workspace)
+        torch.cuda.synchronize()
+        return buf.results()
+
+    try:
+        bns.bns_set_option("path", 2)
+        bns.bns_set_option("fused_variant", 1)           # 64-thread blocks: a channel takes a team of 16
+        bns.bns_set_option("fused_spin_limit", 64)
+        bns.bns_set_option("fused_mute", 1)
+        _announce("give-up path: no block publishes, 64 polls per wait")
+        bad = forward_backward()
+        bns.bns_set_option("fused_mute", 0)
+        bns.bns_set_option("fused_spin_limit", 0)
+        buf.running_mean.copy_(torch.from_numpy(inp["running_mean"].astype(np.float32)))
+        buf.running_var.copy_(torch.from_numpy(inp["running_var"].astype(np.float32)))
+        good = forward_backward()
+    finally:
+        for name in ("fused_mute", "fused_spin_limit", "fused_variant", "path"):
+            bns.bns_set_option(name, 0)
+    for k in ("y", "save_mean", "save_invstd", "running_mean", "running_var", "dx", "dgamma", "dbeta"):
+        assert np.isnan(bad[k]).all(), f"{k}: finite values after a wait that expired"
+    assert_parity(good, oracle_reference(wl, inp), wl, what="after the give-up run", inp=inp)
+
+
 def test_running_statistics_over_iterations_and_null_running_buffers():
     wl = workloads.WORKLOADS["tiny_bs"]
     inp = workloads.make_inputs(wl)
