@@ -119,6 +119,10 @@ def assert_parity(res, ref, wl, channels=None, what="", inp=None):
             # a mean is known to eps times the spread of what was averaged; with one or a few channels the RMS over
             # channels can be a mean that happens to lie near zero
             floor = (wl.momentum if k == "running_mean" else 1.0) / np.asarray(ref["save_invstd"], dtype=np.float64)
+        elif k == "running_var":
+            # a variance enters the method only as Var + eps (Eq. 1, and App. D for the moving average); where every
+            # channel's variance is exactly zero (one sampled point) the RMS over channels is zero as well
+            floor = wl.eps
         errs[k] = scaled_err(g, r, floor)
         assert errs[k] <= tol, f"{what} {k}: scaled error {errs[k]:.3e} > {tol:g}"
     return errs
