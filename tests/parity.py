@@ -85,6 +85,30 @@ def direct_term_rms(inp, ref, channels=None):
     return np.sqrt(np.mean((a * inp["dy"][:, ch].astype(np.float64)) ** 2, axis=(0, 2, 3)))
 
 
+def saved_mean_rounding_scale(wl, inp, ref, tol, channels=None):
+    """Per channel, the floor that admits the error the fp32 rounding of save_mean alone causes in dx.
+
+    The interface hands E to the backward pass as a float.  On S, Eq. 6 subtracts
+    gamma r^2 w dgamma (x_i - E), w = 1/s (for Eq. 4 the set's weight and its own centre), so an error
+    dE <= 2^-24 |E| in E moves dx_i by gamma r^2 w |dgamma| dE whatever the kernel does; with s of a few
+    points and far-away points outside S (large |dgamma|) that exceeds the tolerance times dx's own scale.
+    Twice the bound, divided by the tolerance, is the scale against which such an error still passes."""
+    ch = slice(None) if channels is None else np.asarray(channels)
+    centre = np.abs(np.asarray(ref["save_mean"], dtype=np.float64))
+    if wl.n_v and wl.mode != 4:
+        bv, bs = oracle_boxes_mixed(wl)
+        size = lambda b: (b[:, 1] * b[:, 3] * b[:, 5]).astype(np.float64)
+        w = np.maximum(wl.mix_beta / size(bv), (1.0 - wl.mix_beta) / size(bs))[ch]
+        parts = np.abs(np.asarray(ref["save_mean_parts"], dtype=np.float64)).reshape(2, -1)
+        centre = np.maximum(parts[0], parts[1])
+    else:
+        b = oracle_boxes(wl)[ch]
+        w = 1.0 / (b[:, 1] * b[:, 3] * b[:, 5]).astype(np.float64)
+    r = np.asarray(ref["save_invstd"], dtype=np.float64)
+    bound = np.abs(np.asarray(inp["gamma"], dtype=np.float64)[ch]) * r * r * w * np.abs(ref["dgamma"]) * 2.0 ** -24 * centre
+    return 2.0 * bound / tol
+
+
 def summand_scale(inp, ref, channels=None):
     """Per channel, sqrt(m) * RMS of the m summands of dbeta (dy) and of dgamma (dy * x^): the size such a
     sum has when its terms do not happen to cancel.
@@ -112,7 +136,7 @@ def assert_parity(res, ref, wl, channels=None, what="", inp=None):
         tol = tol_t if k in ("y", "dx") else TOL_F32          # per-channel vectors are fp32 in every mode
         floor = 0.0
         if inp is not None and k == "dx":
-            floor = direct_term_rms(inp, ref, channels)
+            floor = np.maximum(direct_term_rms(inp, ref, channels), saved_mean_rounding_scale(wl, inp, ref, tol, channels))
         elif inp is not None and k in ("dgamma", "dbeta"):
             floor = summand_scale(inp, ref, channels)[k]
         elif k in ("save_mean", "running_mean"):

@@ -18,7 +18,7 @@ def _draw(rng):
     if rng.integers(0, 8) == 0:                 # now and then a channel that needs a team of blocks
         N = int(rng.integers(16, 49))
         C_ = int(rng.choice([8, 24, 40]))
-        H = W = int(rng.choice([14, 28, 56]))
+        H = W = int(rng.choice([7, 14, 15, 28, 30, 56]))      # 7, 15: scalar accesses; 14, 30: 64-bit ones in bf16
     else:
         N = int(rng.integers(1, 14))
         C_ = int(rng.choice([1, 2, 3, 4, 7, 8, 12, 16, 33, 40, 64, 130]))
