@@ -21,7 +21,7 @@ def _draw(rng):
         H = W = int(rng.choice([7, 14, 15, 28, 30, 56]))      # 7, 15: scalar accesses; 14, 30: 64-bit ones in bf16
     else:
         N = int(rng.integers(1, 14))
-        C_ = int(rng.choice([1, 2, 3, 4, 7, 8, 12, 16, 33, 40, 64, 130]))
+        C_ = int(rng.choice([1, 2, 3, 4, 7, 8, 12, 16, 33, 40, 64, 130, 260, 515]))
         H = int(rng.choice([1, 2, 3, 4, 6, 7, 8, 12, 14, 16, 20]))
         W = int(rng.choice([1, 2, 3, 4, 6, 7, 8, 12, 14, 16, 28]))
     dtype = str(rng.choice(["f32", "bf16"]))
