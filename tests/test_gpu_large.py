@@ -10,7 +10,7 @@ import torch
 
 from oracle import bns_oracle as oracle
 from paper_1810_10962_amd import bns
-from paper_1810_10962_amd.workloads import BS, FS, Workload
+from paper_1810_10962_amd.workloads import BS, FS, FULL, NS, Workload
 from parity import assert_parity, oracle_boxes
 
 pytestmark = pytest.mark.gpu
@@ -101,6 +101,47 @@ def test_more_than_2_31_elements(kind, shape, mkw, dtype, layout):
                running_var=f["running_var"], dx=b["dx"], dgamma=b["dgamma"], dbeta=b["dbeta"])
     errs = assert_parity(res, ref, wl, what=f"large {layout} {shape}")
     print(f"[gpu-case] large scaled errors {errs}", flush=True)
+
+
+EXTENTS = [
+    ((3, 1 << 20, 2, 2), dict(mode=BS, n_s=2), "f32"),                    # a million channels of twelve points
+    ((2, (1 << 18) + 3, 1, 1), dict(mode=FULL), "bf16"),                  # s = m = 2, channel count not a multiple of anything
+    ((2, 4, 1, 1 << 20), dict(mode=FS, patch_h=1, patch_w=77777), "f32"), # one row of a million columns
+    ((2, 4, 1 << 20, 1), dict(mode=NS, n_s=1), "bf16"),                   # one column of a million rows
+    ((60000, 8, 2, 4), dict(mode=FS, patch_h=1, patch_w=3), "f32"),       # nearly the largest batch
+]
+
+
+@pytest.mark.parametrize("layout", ["nchw", "nhwc"])
+@pytest.mark.parametrize("shape,mkw,dtype", EXTENTS, ids=["x".join(map(str, c[0])) for c in EXTENTS])
+def test_one_extent_very_large_the_others_tiny(shape, mkw, dtype, layout):
+    """Extents near the documented limits with few elements in total, default kernel choice and streaming kernels."""
+    N, C_, H, W = shape
+    for path in (0, 1):
+        wl = Workload(name="extent", N=N, C=C_, H=H, W=W, dtype=dtype, layout=layout, data_seed=21, sampling_seed=22,
+                      layer_id=5, epoch=path, **mkw)
+        print(f"[gpu-case] extent {layout} {shape} {dtype} {mkw} path={path}", flush=True)
+        bns.bns_set_option("path", path)
+        try:
+            t = _device_case(wl)
+        finally:
+            bns.bns_set_option("path", 0)
+        ch = sorted({0, min(1, C_ - 1), C_ // 2, max(C_ - 2, 0), C_ - 1})
+        host = _channels_to_host(t, wl, ch, ("x", "dy", "y", "dx"))
+        vec = lambda k: t[k][ch].cpu().numpy()
+        inp = dict(x=host["x"], dy=host["dy"], gamma=vec("gamma"), beta=vec("beta"))
+        res = dict(y=host["y"], dx=host["dx"], **{k: vec(k) for k in ("save_mean", "save_invstd", "running_mean",
+                                                                      "running_var", "dgamma", "dbeta")})
+        del t
+        torch.cuda.empty_cache()
+        boxes = oracle_boxes(wl)[ch]
+        k = len(ch)
+        f = oracle.forward(inp["x"], inp["gamma"], inp["beta"], boxes, wl.eps, wl.momentum, np.zeros(k), np.ones(k))
+        b = oracle.backward(inp["x"], inp["dy"], inp["gamma"], f["mean"], f["var"], boxes, wl.eps)
+        ref = dict(y=f["y"], save_mean=f["mean"], save_invstd=f["invstd"], running_mean=f["running_mean"],
+                   running_var=f["running_var"], dx=b["dx"], dgamma=b["dgamma"], dbeta=b["dbeta"])
+        # the location set is shared by the channels, so the checked channels form a workload of their own
+        assert_parity(res, ref, wl.replace(C=k), what=f"extent {layout} {shape} path={path}", inp=inp)
 
 
 @pytest.mark.parametrize("layout", ["nchw", "nhwc"])
