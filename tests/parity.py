@@ -86,13 +86,14 @@ def direct_term_rms(inp, ref, channels=None):
 
 
 def saved_mean_rounding_scale(wl, inp, ref, tol, channels=None):
-    """Per channel, the floor that admits the error the fp32 rounding of save_mean alone causes in dx.
+    """Per channel, the floors for y and dx that admit the error the fp32 rounding of save_mean alone causes.
 
-    The interface hands E to the backward pass as a float.  On S, Eq. 6 subtracts
-    gamma r^2 w dgamma (x_i - E), w = 1/s (for Eq. 4 the set's weight and its own centre), so an error
-    dE <= 2^-24 |E| in E moves dx_i by gamma r^2 w |dgamma| dE whatever the kernel does; with s of a few
-    points and far-away points outside S (large |dgamma|) that exceeds the tolerance times dx's own scale.
-    Twice the bound, divided by the tolerance, is the scale against which such an error still passes."""
+    The interface hands E from the statistics to the normalisation and to the backward pass as a float, so
+    x - E carries an error dE <= 2^-24 |E| whatever the kernels do.  Eq. 1 turns it into gamma r dE in y.  On
+    S, Eq. 6 subtracts gamma r^2 w dgamma (x_i - E), w = 1/s (for Eq. 4 the set's weight and its own
+    centre), which moves dx_i by gamma r^2 w |dgamma| dE.  With few sampled points close together (large r)
+    and far-away points outside S (large |dgamma|) either can exceed the tolerance times the output's own
+    scale.  Twice the bound, divided by the tolerance, is the scale against which such an error still passes."""
     ch = slice(None) if channels is None else np.asarray(channels)
     centre = np.abs(np.asarray(ref["save_mean"], dtype=np.float64))
     if wl.n_v and wl.mode != 4:
@@ -100,13 +101,15 @@ def saved_mean_rounding_scale(wl, inp, ref, tol, channels=None):
         size = lambda b: (b[:, 1] * b[:, 3] * b[:, 5]).astype(np.float64)
         w = np.maximum(wl.mix_beta / size(bv), (1.0 - wl.mix_beta) / size(bs))[ch]
         parts = np.abs(np.asarray(ref["save_mean_parts"], dtype=np.float64)).reshape(2, -1)
-        centre = np.maximum(parts[0], parts[1])
+        centre_sets = np.maximum(parts[0], parts[1])
     else:
         b = oracle_boxes(wl)[ch]
         w = 1.0 / (b[:, 1] * b[:, 3] * b[:, 5]).astype(np.float64)
+        centre_sets = centre
     r = np.asarray(ref["save_invstd"], dtype=np.float64)
-    bound = np.abs(np.asarray(inp["gamma"], dtype=np.float64)[ch]) * r * r * w * np.abs(ref["dgamma"]) * 2.0 ** -24 * centre
-    return 2.0 * bound / tol
+    g = np.abs(np.asarray(inp["gamma"], dtype=np.float64)[ch])
+    return dict(y=2.0 * g * r * 2.0 ** -24 * centre / tol,
+                dx=2.0 * g * r * r * w * np.abs(ref["dgamma"]) * 2.0 ** -24 * centre_sets / tol)
 
 
 def summand_scale(inp, ref, channels=None):
@@ -136,7 +139,9 @@ def assert_parity(res, ref, wl, channels=None, what="", inp=None):
         tol = tol_t if k in ("y", "dx") else TOL_F32          # per-channel vectors are fp32 in every mode
         floor = 0.0
         if inp is not None and k == "dx":
-            floor = np.maximum(direct_term_rms(inp, ref, channels), saved_mean_rounding_scale(wl, inp, ref, tol, channels))
+            floor = np.maximum(direct_term_rms(inp, ref, channels), saved_mean_rounding_scale(wl, inp, ref, tol, channels)["dx"])
+        elif inp is not None and k == "y":
+            floor = saved_mean_rounding_scale(wl, inp, ref, tol, channels)["y"]
         elif inp is not None and k in ("dgamma", "dbeta"):
             floor = summand_scale(inp, ref, channels)[k]
         elif k in ("save_mean", "running_mean"):
