@@ -90,3 +90,45 @@ def test_random_configurations(chunk):
             assert_parity(buf.results(), ref, wl, what=f"random {chunk}/{i} stages {wl}", inp=inp)
         done += 1
     assert done >= 20 and fused_refused <= 20
+
+
+# Launch-choice overrides (include/bns.h, bns_set_option): documented ranges, extremes included.
+OVERRIDES = {
+    "norm_unroll": [0, 1, 2, 4], "dx_unroll": [0, 1, 2, 4], "reduce_unroll": [0, 1, 2, 4], "norm_nt": [0, 1, 2, 3, 4],
+    "dx_nt": [0, 1, 2, 3, 4], "reduce_nt": [0, 1, 2], "split_statistics": [0, 1], "splits_stats": [0, 1, 2, 7, 33, 64],
+    "splits_reduce": [0, 1, 3, 16, 64], "channel_group": [0, 1, 3, 16, 100], "nhwc_blocks": [0, 1, 7, 256, 3000, 8192],
+    "nhwc_ew_rows": [0, 1, 2, 9, 64, 5000, 1 << 20], "nhwc_small": [0, 2], "fused_variant": [0, 0, 1, 2, 3, 4, 5, 6, 7],
+    "fused_keep_x": [0, 1, 2], "fused_coop": [0, 1], "path": [0, 0, 1, 2],
+}
+
+
+@pytest.mark.parametrize("chunk", range(max(SWEEP_CHUNKS // 2, 1)))
+def test_random_launch_overrides_do_not_change_results(chunk):
+    """Random subsets of the launch-choice overrides at random values on random shapes: whatever kernels,
+    block counts and access widths they select, the results still match the oracle."""
+    rng = np.random.default_rng(SWEEP_SEED + 1000003 + chunk)
+    done = 0
+    for i in range(40):
+        wl, _ = _draw(rng)
+        opts = {k: int(rng.choice(v)) for k, v in OVERRIDES.items() if rng.integers(0, 3) == 0}
+        print(f"[gpu-case] overrides {chunk}/{i}: {wl.shape} {wl.dtype} {wl.layout} mode={wl.mode} n_s={wl.n_s} "
+              f"patch={wl.patch_h}x{wl.patch_w} pc={wl.fs_per_channel} n_v={wl.n_v} {opts}", flush=True)
+        inp = workloads.make_inputs(wl)
+        for k, v in opts.items():
+            bns.bns_set_option(k, v)
+        try:
+            res = bns.run_workload(wl, inp)
+        except bns.BnsError as e:
+            # a forced single-launch kernel (or variant of it) may not exist for the shape
+            assert e.status == bns.BNS_EUNSUPPORTED and (opts.get("path") == 2 or opts.get("fused_variant", 0) > 0), \
+                (wl, opts, e)
+            continue
+        finally:
+            for k in opts:
+                bns.bns_set_option(k, 0)
+        mixed = wl.n_v and wl.mode != VDN
+        boxes = oracle_boxes_mixed(wl)[1] if mixed else oracle_boxes(wl)
+        assert (res["boxes"] == boxes).all()
+        assert_parity(res, oracle_reference(wl, inp), wl, what=f"overrides {chunk}/{i} {wl} {opts}", inp=inp)
+        done += 1
+    assert done >= 20
