@@ -143,7 +143,7 @@ def time_directions(ds, steps, torch, bns):
         b.backward()
         e[2].record()
     torch.cuda.synchronize()
-    paths = {1: "streaming", 2: "fused"}
+    paths = {1: "streaming", 2: "fused", 3: "one-launch"}
     return dict(forward=float(np.mean([e[0].elapsed_time(e[1]) for e in evs])) * 1e-3,
                 backward=float(np.mean([e[1].elapsed_time(e[2]) for e in evs])) * 1e-3,
                 forward_path=paths.get(bns.bns_get_option("last_path_forward"), "?"),
@@ -319,6 +319,16 @@ def main():
                     variants[name][label] = None
                 finally:
                     bns.bns_set_option("path", 0)
+            # each direction on its own (event pairs around the calls), default choice and streaming kernels:
+            # the paper expects the forward pass to gain most (App. C.1)
+            for prefix, path in (("", 0), ("streaming_", 1)):
+                bns.bns_set_option("path", path)
+                try:
+                    d = time_directions(vds, max(K // 2, 10), torch, bns)
+                finally:
+                    bns.bns_set_option("path", 0)
+                variants[name][prefix + "forward_us"] = round(d["forward"] * 1e6, 2)
+                variants[name][prefix + "backward_us"] = round(d["backward"] * 1e6, 2)
             del vds
             torch.cuda.empty_cache()
         for name, v in variants.items():
@@ -328,10 +338,15 @@ def main():
                 if full.get("streaming_us") and v.get("streaming_us"):
                     # both sides with the streaming kernels only: the two-pass cost model of the paper (App. C.1)
                     v["speedup_vs_full_bn_streaming_kernels"] = round(full["streaming_us"] / v["streaming_us"], 4)
+                v["forward_speedup_vs_full_bn"] = round(full["forward_us"] / v["forward_us"], 4)
+                v["forward_speedup_vs_full_bn_streaming_kernels"] = round(
+                    full["streaming_forward_us"] / v["streaming_forward_us"], 4)
         out["variants"] = variants
         if wl.name in variants and "speedup_vs_full_bn" in variants[wl.name]:
             out["speedup_vs_full_bn"] = variants[wl.name]["speedup_vs_full_bn"]
             out["speedup_vs_full_bn_streaming_kernels"] = variants[wl.name].get("speedup_vs_full_bn_streaming_kernels")
+            out["forward_speedup_vs_full_bn_streaming_kernels"] = variants[wl.name][
+                "forward_speedup_vs_full_bn_streaming_kernels"]
         others = {}
         for name in ("tiny_bs", "cifar_fs", "vdn", "vdn_fs_mix", "vdn_bs_mix", "micro_a_fs", "micro_a_full", "micro_b_fs",
                      "micro_b_full"):
