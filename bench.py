@@ -196,7 +196,25 @@ def cpu_baseline(wl, inputs, res, budget_s=12.0):
         done += len(ch)
     r = sampling_ratio(wl, boxes)
     bytes_per_channel = algorithmic_bytes(wl, r)["fwd+bwd"] / wl.C
+
+    # The same channels again, groups of four handed to a pool of threads (numpy releases the interpreter lock
+    # inside its loops); the oracle itself is unchanged.
+    def one_group(ch):
+        x, dy = inputs["x"][:, ch], inputs["dy"][:, ch]
+        f = oracle.forward(x, inputs["gamma"][ch], inputs["beta"][ch], boxes[ch], wl.eps, wl.momentum,
+                           inputs["running_mean"][ch], inputs["running_var"][ch])
+        oracle.backward(x, dy, inputs["gamma"][ch], f["mean"], f["var"], boxes[ch], wl.eps)
+
+    threads = max(1, min(16, os.cpu_count() or 1))
+    groups = [np.asarray(order[i:i + 4]) for i in range(0, done, 4)]
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        t0 = time.perf_counter()
+        list(pool.map(one_group, groups))
+        spent_all = time.perf_counter() - t0
     return dict(value=round(bytes_per_channel * done / spent / 1e9, 4), unit="GB/s", cores=1, kind="oracle",
+                all_cores=dict(value=round(bytes_per_channel * done / spent_all / 1e9, 4), unit="GB/s", cores=threads,
+                               seconds=round(spent_all, 2)),
                 sample=f"{done} of {wl.C} channels of the same tensor, oracle forward+backward in fp64 (numpy, "
                        f"one thread), {spent:.1f} s", elements_per_s=round(wl.elements / wl.C * done / spent, 1),
                 max_scaled_error_vs_gpu={k: float(f"{v:.3e}") for k, v in worst.items()})
