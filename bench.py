@@ -144,8 +144,13 @@ def time_directions(ds, steps, torch, bns):
         e[2].record()
     torch.cuda.synchronize()
     paths = {1: "streaming", 2: "fused", 3: "one-launch"}
-    return dict(forward=float(np.mean([e[0].elapsed_time(e[1]) for e in evs])) * 1e-3,
-                backward=float(np.mean([e[1].elapsed_time(e[2]) for e in evs])) * 1e-3,
+    fwd = np.array([e[0].elapsed_time(e[1]) for e in evs]) * 1e-3
+    bwd = np.array([e[1].elapsed_time(e[2]) for e in evs]) * 1e-3
+    both = fwd + bwd
+    stat = lambda a: {"mean": round(float(a.mean()) * 1e6, 2), "median": round(float(np.median(a)) * 1e6, 2),
+                      "min": round(float(a.min()) * 1e6, 2)}
+    return dict(forward=float(fwd.mean()), backward=float(bwd.mean()),
+                spread_us={"forward": stat(fwd), "backward": stat(bwd), "forward+backward": stat(both)},
                 forward_path=paths.get(bns.bns_get_option("last_path_forward"), "?"),
                 backward_path=paths.get(bns.bns_get_option("last_path_backward"), "?"))
 
@@ -297,7 +302,8 @@ def main():
         "warm": {"us_per_step": round(warm_sec * 1e6, 2), "GBs": round(alg["fwd+bwd"] / warm_sec / 1e9, 1),
                  "note": "one buffer set reused every step (value and ms_per_step rotate over buffer_sets_rotated sets)"},
         "default_path": {"forward": dirs["forward_path"], "backward": dirs["backward_path"],
-                         "forward_us": round(dirs["forward"] * 1e6, 2), "backward_us": round(dirs["backward"] * 1e6, 2)},
+                         "forward_us": round(dirs["forward"] * 1e6, 2), "backward_us": round(dirs["backward"] * 1e6, 2),
+                         "event_pairs_us": dirs["spread_us"]},
         "streaming_stages_us": {k: round(v * 1e6, 2) for k, v in stages.items()},
         "streaming_stages_GBs": {k: round(alg[k] / stages[k] / 1e9, 1) for k in stages},
         "copy_reference": {"us": round(copy_s * 1e6, 2), "GBs": round(2 * tensor_bytes / copy_s / 1e9, 1)},
