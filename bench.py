@@ -42,6 +42,11 @@ MEASURED_TRAFFIC = {
     ("imagenet_bs_nhwc", "normalize"): 411111929,
     ("imagenet_bs_nhwc", "dx"): 436805623,
     ("imagenet_bs_nhwc", "reduce"): 412120265,
+    # profiles/feature_sampling_f32_hbm_traffic.md
+    ("imagenet_fs", "bwd"): 618586743,          # fused_backward_kernel, x kept on chip
+    ("imagenet_fs", "normalize"): 411222742,
+    ("imagenet_fs", "dx"): 463525848,
+    ("imagenet_fs", "reduce"): 411114419,
 }
 
 
