@@ -42,6 +42,12 @@ MEASURED_TRAFFIC = {
     ("imagenet_bs_nhwc", "normalize"): 411111929,
     ("imagenet_bs_nhwc", "dx"): 436805623,
     ("imagenet_bs_nhwc", "reduce"): 412120265,
+    # profiles/imagenet_bs_bf16_hbm_traffic.md
+    ("imagenet_bs_bf16", "bwd"): 321698909,     # fused_backward_kernel
+    ("imagenet_bs_bf16", "fwd"): 206160664,     # fused_forward_kernel
+    ("imagenet_bs_bf16", "normalize"): 205590313,
+    ("imagenet_bs_bf16", "dx"): 218472118,
+    ("imagenet_bs_bf16", "reduce"): 205601072,
     # profiles/feature_sampling_f32_hbm_traffic.md
     ("imagenet_fs", "bwd"): 618586743,          # fused_backward_kernel, x kept on chip
     ("imagenet_fs", "normalize"): 411222742,
