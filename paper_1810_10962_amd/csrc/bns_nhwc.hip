@@ -752,7 +752,11 @@ inline int column_vec(const Dims& d) { return (d.dtype == BNS_BF16 && d.C % 8 ==
 
 // Blocks: enough to fill the device a few times over.  Reductions (blocks > 0, or the reduction
 // default) keep at least four rows per row lane and a bounded number of partials per channel.
-Tiling make_tiling(const Dims& d, uint32_t rows, int blocks = 0, bool elementwise = false) {
+// split_bound (optional): the number of splits before the rows are dealt out evenly.  It never decreases when
+// `rows` or `blocks` grow, and the final t.splits never exceeds it -- unlike t.splits itself, which the
+// rounding of rows_per_block makes non-monotonic (924 rows -> 55 splits, 896 rows -> 56).
+Tiling make_tiling(const Dims& d, uint32_t rows, int blocks = 0, bool elementwise = false,
+                   uint32_t* split_bound = nullptr) {
     Tiling t;
     const int V = column_vec(d);
     t.C = d.C;
@@ -781,6 +785,7 @@ Tiling make_tiling(const Dims& d, uint32_t rows, int blocks = 0, bool elementwis
     }
     if (s < 1u) s = 1u;
     while (uint64_t(tiles) * s > 0x7FFFFFFFu) s = (s + 1u) / 2u;      // grid.x limit
+    if (split_bound) *split_bound = s;
     t.rows_per_block = ceil_div_u(rows, s);
     t.splits = int32_t(ceil_div_u(rows, t.rows_per_block));     // no empty blocks
     return t;
@@ -851,16 +856,25 @@ hipError_t dispatch_nhwc(const Dims& d, F&& f) {
 }  // namespace
 
 size_t nhwc_partial_bytes(const Dims& d) {
-    // the most splits make_tiling can choose for this shape: they grow with the row count and the block target
-    const Tiling t = make_tiling(d, uint32_t(d.N) * uint32_t(d.HW), kNhwcBlocksMax);
-    return (size_t(t.splits) * size_t(d.C) * sizeof(Partial) + 255) & ~size_t(255);
+    // the most splits make_tiling can choose for any row set of this shape and any block target
+    uint32_t bound = 1;
+    make_tiling(d, uint32_t(d.N) * uint32_t(d.HW), kNhwcBlocksMax, false, &bound);
+    return (size_t(bound) * size_t(d.C) * sizeof(Partial) + 255) & ~size_t(255);
 }
+
+namespace {
+// The partial sums of `t` must fit the workspace region the API sized with nhwc_partial_bytes.
+inline bool fits_region(const Dims& d, const Tiling& t) {
+    return size_t(t.splits) * size_t(d.C) * sizeof(Partial) <= nhwc_partial_bytes(d);
+}
+}  // namespace
 
 hipError_t launch_nhwc_stats(const Dims& d, const bns_box& b, const void* x, Partial* partial, float eps, float momentum,
                              float* save_mean, float* save_invstd, float* running_mean, float* running_var,
                              hipStream_t st) {
     const RowSet S = make_rowset(d, b);
     const Tiling t = make_tiling(d, S.rows);
+    if (!fits_region(d, t)) return hipErrorInvalidValue;
     return dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
         constexpr int V = decltype(vt)::value;
@@ -892,6 +906,7 @@ hipError_t launch_nhwc_reduce(const Dims& d, const void* x, const void* dy, cons
                               Partial* partial, float* dgamma, float* dbeta, hipStream_t st) {
     const uint32_t M = uint32_t(d.N) * uint32_t(d.HW);
     const Tiling t = make_tiling(d, M);
+    if (!fits_region(d, t)) return hipErrorInvalidValue;
     return dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
         constexpr int V = decltype(vt)::value;
@@ -967,6 +982,7 @@ hipError_t launch_nhwc_stats_mixed(const Dims& d, const bns_box& b, int n_v, con
     const bns_box vb{0, n_v, 0, d.H, 0, d.W};
     const RowSet Vs = make_rowset(d, vb);
     const Tiling ts = make_tiling(d, S.rows), tv = make_tiling(d, Vs.rows);
+    if (!fits_region(d, ts) || !fits_region(d, tv)) return hipErrorInvalidValue;
     Partial* partial_v = reinterpret_cast<Partial*>(reinterpret_cast<char*>(partial) + nhwc_partial_bytes(d));
     return dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);

@@ -306,6 +306,22 @@ def test_vdn_plus_sampling_small_shapes(shape, mname, mkw, dtype):
                       what=f"nhwc mixed {shape} {mname} {dtype} n_v={n_v} beta={mix_beta}", inp=inp)
 
 
+def test_row_subsets_that_split_into_more_blocks_than_the_whole_tensor():
+    """Dealing rows out evenly is not monotonic: the 924 rows of a 33x28x1 tensor go to 55 blocks, the 896 rows of
+    32 of its samples to 56.  The workspace regions must hold the larger count (the partial sums of the
+    sampled set once ran into the region of the virtual set), for Eq. 4 and for plain Batch Sampling."""
+    mixed = Workload(name="regions", N=33, C=260, H=28, W=1, mode=FULL, dtype="f32", layout="nhwc", n_v=1, mix_beta=0.5,
+                     data_seed=817383120, sampling_seed=2850669091811702665, layer_id=3462304091, epoch=2332354607)
+    inp, res = _run(mixed)
+    assert_parity(res, oracle_reference(mixed, inp), mixed, what="nhwc regions, Eq. 4", inp=inp)
+    virtual_large = mixed.replace(n_v=32, mix_beta=0.3)          # now the virtual set is the one with 56 blocks
+    inp, res = _run(virtual_large)
+    assert_parity(res, oracle_reference(virtual_large, inp), virtual_large, what="nhwc regions, large virtual set", inp=inp)
+    plain = mixed.replace(n_v=0, mode=BS, n_s=32)
+    inp, res = _run(plain)
+    assert_parity(res, oracle_reference(plain, inp), plain, what="nhwc regions, Batch Sampling", inp=inp)
+
+
 @pytest.mark.parametrize("name", ["vdn_fs_mix", "vdn_bs_mix"])
 def test_vdn_plus_sampling_benchmark_shape(name):
     wl = workloads.WORKLOADS[name].replace(layout="nhwc")
