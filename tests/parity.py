@@ -91,9 +91,11 @@ def saved_mean_rounding_scale(wl, inp, ref, tol, channels=None):
     The interface hands E from the statistics to the normalisation and to the backward pass as a float, so
     x - E carries an error dE <= 2^-24 |E| whatever the kernels do.  Eq. 1 turns it into gamma r dE in y.  On
     S, Eq. 6 subtracts gamma r^2 w dgamma (x_i - E), w = 1/s (for Eq. 4 the set's weight and its own
-    centre), which moves dx_i by gamma r^2 w |dgamma| dE.  With few sampled points close together (large r)
-    and far-away points outside S (large |dgamma|) either can exceed the tolerance times the output's own
-    scale.  Twice the bound, divided by the tolerance, is the scale against which such an error still passes."""
+    centre): dE moves the factor (x_i - E) by dE and, through the sum dgamma = r sum_j g_j (x_j - E) of Eq. 5, the
+    factor dgamma by r |dbeta| dE, so dx_i moves by up to gamma r^2 w (|dgamma| + |dbeta| max|x^|) dE.  With few
+    sampled points close together (large r) or far-away points outside S (large |dgamma|) either output can exceed
+    the tolerance times its own scale.  Twice the bound, divided by the tolerance, is the scale against which
+    such an error still passes.  dgamma itself moves by r |dbeta| dE (per-channel vectors: fp32 tolerance)."""
     ch = slice(None) if channels is None else np.asarray(channels)
     centre = np.abs(np.asarray(ref["save_mean"], dtype=np.float64))
     if wl.n_v and wl.mode != 4:
@@ -108,8 +110,11 @@ def saved_mean_rounding_scale(wl, inp, ref, tol, channels=None):
         centre_sets = centre
     r = np.asarray(ref["save_invstd"], dtype=np.float64)
     g = np.abs(np.asarray(inp["gamma"], dtype=np.float64)[ch])
+    xhat_max = np.max(np.abs(inp["x"][:, ch].astype(np.float64) - ref["save_mean"][None, :, None, None]), axis=(0, 2, 3)) * r
     return dict(y=2.0 * g * r * 2.0 ** -24 * centre / tol,
-                dx=2.0 * g * r * r * w * np.abs(ref["dgamma"]) * 2.0 ** -24 * centre_sets / tol)
+                dgamma=2.0 * r * np.abs(ref["dbeta"]) * 2.0 ** -24 * centre / TOL_F32,
+                dx=2.0 * g * r * r * w * (np.abs(ref["dgamma"]) * centre_sets + np.abs(ref["dbeta"]) * xhat_max * centre)
+                   * 2.0 ** -24 / tol)
 
 
 def summand_scale(inp, ref, channels=None):
@@ -144,6 +149,8 @@ def assert_parity(res, ref, wl, channels=None, what="", inp=None):
             floor = saved_mean_rounding_scale(wl, inp, ref, tol, channels)["y"]
         elif inp is not None and k in ("dgamma", "dbeta"):
             floor = summand_scale(inp, ref, channels)[k]
+            if k == "dgamma":
+                floor = np.maximum(floor, saved_mean_rounding_scale(wl, inp, ref, tol, channels)["dgamma"])
         elif k in ("save_mean", "running_mean"):
             # a mean is known to eps times the spread of what was averaged; with one or a few channels the RMS over
             # channels can be a mean that happens to lie near zero
