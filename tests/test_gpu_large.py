@@ -15,6 +15,8 @@ from parity import assert_parity, oracle_boxes
 
 pytestmark = pytest.mark.gpu
 
+GUARD = 1024      # elements behind every buffer the kernels write
+
 CASES = [
     # large planes: a channel is far too big for the single-launch kernels -> streaming kernels
     ("planes", (40, 1024, 240, 240), dict(mode=BS, n_s=5), "bf16"),
@@ -48,18 +50,31 @@ def _device_case(wl, structured=False):
     if structured:
         t["x"].clamp_(min=0).mul_(32).round_().div_(32)
         t["dy"].fill_(1.0 / 3.0)
-    t["y"], t["dx"] = torch.empty_like(t["x"]), torch.empty_like(t["x"])
+    guards = []
+
+    def guarded(numel, dtype, fill=None):
+        """`numel` elements followed by guard elements of a known value that no kernel may touch."""
+        whole = torch.empty(numel + GUARD, dtype=dtype, device=dev)
+        whole[numel:] = 85
+        if fill is not None:
+            whole[:numel] = fill
+        guards.append(whole[numel:])
+        return whole[:numel]
+
+    t["y"], t["dx"] = (guarded(t["x"].numel(), tdt).view(stored) for _ in range(2))
     for k in ("save_mean", "save_invstd", "dgamma", "dbeta"):
-        t[k] = torch.empty(C_, **f32)
-    t["running_mean"], t["running_var"] = torch.zeros(C_, **f32), torch.ones(C_, **f32)
+        t[k] = guarded(C_, torch.float32)
+    t["running_mean"], t["running_var"] = guarded(C_, torch.float32, 0.0), guarded(C_, torch.float32, 1.0)
     shp = bns.make_shape(N, C_, H, W, wl.dtype, wl.layout)
     spec = bns.make_spec(wl.mode, wl.n_s, wl.patch_h, wl.patch_w, 0, wl.layer_id, wl.epoch)
-    ws = torch.empty(bns.bns_workspace_bytes(shp, spec), dtype=torch.uint8, device=dev)
+    ws = guarded(bns.bns_workspace_bytes(shp, spec), torch.uint8)
     bns.bns_forward(shp, spec, wl.sampling_seed, t["x"], t["gamma"], t["beta"], wl.eps, wl.momentum, t["y"],
                     t["save_mean"], t["save_invstd"], t["running_mean"], t["running_var"], ws)
     bns.bns_backward(shp, spec, wl.sampling_seed, t["x"], t["dy"], t["gamma"], t["save_mean"], t["save_invstd"],
                      t["dx"], t["dgamma"], t["dbeta"], ws)
     torch.cuda.synchronize()
+    for g_ in guards:
+        assert bool((g_ == 85).all()), "a kernel wrote behind one of its buffers"
     assert (bns.bns_sample_index(shp, spec, wl.sampling_seed) == oracle_boxes(wl)).all()
     return t
 
