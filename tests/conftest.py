@@ -28,13 +28,15 @@ def read_golden(name):
 GUARD_BYTES = 4096
 WRITTEN_BUFFERS = ("workspace", "y", "dx", "save_mean", "save_invstd", "running_mean", "running_var", "dgamma", "dbeta",
                    "save_mean_parts")
+READ_BUFFERS = ("x", "dy", "gamma", "beta")
 
 
 @pytest.fixture(scope="session", autouse=True)
 def guard_bytes_behind_written_buffers():
     """GPU tests: every buffer of bns.Buffers that a kernel writes (outputs, statistics, the workspace, sized
     exactly as bns_workspace_bytes says) gets GUARD_BYTES of a known pattern behind it, and results() fails
-    if a kernel touched them."""
+    if a kernel touched them; every input has NaNs behind it, which a read past its end would carry into the
+    outputs that the parity checks then reject."""
     try:
         import torch
         if not torch.cuda.is_available():
@@ -59,6 +61,14 @@ def guard_bytes_behind_written_buffers():
             view.copy_(t)
             setattr(self, name, view)
             self._guards[name] = (big, nbytes)
+        for name in READ_BUFFERS:                        # inputs: NaN behind them, so a read past the end shows
+            t = getattr(self, name, None)
+            if t is None:
+                continue
+            big = torch.full((t.numel() + GUARD_BYTES // 2,), float("nan"), dtype=t.dtype, device=t.device)
+            view = big[:t.numel()].view(t.shape)
+            view.copy_(t)
+            setattr(self, name, view)
         self._fwd_args = self._bwd_args = None          # marshalled pointers are stale
 
     def results(self):
