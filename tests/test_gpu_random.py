@@ -9,7 +9,8 @@ import pytest
 
 from paper_1810_10962_amd import bns, workloads
 from paper_1810_10962_amd.workloads import BS, FS, FULL, NS, VDN, Workload
-from parity import assert_parity, oracle_boxes, oracle_boxes_mixed, oracle_reference
+from oracle import bns_oracle as oracle
+from parity import TOL_BF16, TOL_F32, assert_parity, oracle_boxes, oracle_boxes_mixed, oracle_reference, scaled_err
 
 pytestmark = pytest.mark.gpu
 
@@ -88,6 +89,18 @@ def test_random_configurations(chunk):
             bns.bns_backward_dx(buf.shape, buf.spec, buf.seed, buf.x, buf.dy, buf.gamma, buf.save_mean,
                                 buf.save_invstd, buf.dgamma, buf.dbeta, buf.dx)
             assert_parity(buf.results(), ref, wl, what=f"random {chunk}/{i} stages {wl}", inp=inp)
+        if i % 4 == 1:                          # App. D: the same tensor normalised with given moving averages
+            stats = np.random.default_rng(wl.data_seed)
+            rm = stats.standard_normal(wl.C).astype(np.float32)
+            rv = stats.uniform(0.0, 3.0, wl.C).astype(np.float32)
+            buf = bns.Buffers(wl, dict(inp, running_mean=rm, running_var=rv))
+            bns.bns_inference(buf.shape, buf.x, buf.gamma, buf.beta, buf.running_mean, buf.running_var, wl.eps, buf.y)
+            want = oracle.inference(inp["x"], inp["gamma"], inp["beta"], rm, rv, wl.eps)
+            # y against its own scale and the floor for the fp32 moving mean (see parity.saved_mean_rounding_scale)
+            tol = TOL_F32 if wl.dtype == "f32" else TOL_BF16
+            r = 1.0 / np.sqrt(rv.astype(np.float64) + wl.eps)
+            floor = 2.0 * np.abs(inp["gamma"].astype(np.float64)) * r * 2.0 ** -24 * np.abs(rm) / tol
+            assert scaled_err(buf.results()["y"], want, floor) <= tol, f"random {chunk}/{i} inference {wl}"
         done += 1
     assert done >= 20 and fused_refused <= 20
 
