@@ -26,6 +26,7 @@ def read_golden(name):
 
 
 GUARD_BYTES = 4096
+FRONT_BYTES = 4096 + 16      # guard in front; it also puts every buffer at the least alignment the interface allows
 WRITTEN_BUFFERS = ("workspace", "y", "dx", "save_mean", "save_invstd", "running_mean", "running_var", "dgamma", "dbeta",
                    "save_mean_parts")
 READ_BUFFERS = ("x", "dy", "gamma", "beta")
@@ -34,9 +35,9 @@ READ_BUFFERS = ("x", "dy", "gamma", "beta")
 @pytest.fixture(scope="session", autouse=True)
 def guard_bytes_behind_written_buffers():
     """GPU tests: every buffer of bns.Buffers that a kernel writes (outputs, statistics, the workspace, sized
-    exactly as bns_workspace_bytes says) gets GUARD_BYTES of a known pattern behind it, and results() fails
-    if a kernel touched them; every input has NaNs behind it, which a read past its end would carry into the
-    outputs that the parity checks then reject."""
+    exactly as bns_workspace_bytes says) lies between guard bytes of a known pattern, 16 bytes off any larger
+    alignment, and results() fails if a kernel touched the guards; every input lies between NaNs, which a read
+    outside it would carry into the outputs that the parity checks then reject."""
     try:
         import torch
         if not torch.cuda.is_available():
@@ -56,17 +57,19 @@ def guard_bytes_behind_written_buffers():
             if t is None:
                 continue
             nbytes = t.numel() * t.element_size()
-            big = torch.full((nbytes + (-nbytes) % 16 + GUARD_BYTES,), 0xA5, dtype=torch.uint8, device=t.device)
-            view = big[:nbytes].view(t.dtype).view(t.shape)
+            big = torch.full((FRONT_BYTES + nbytes + (-nbytes) % 16 + GUARD_BYTES,), 0xA5, dtype=torch.uint8,
+                             device=t.device)
+            view = big[FRONT_BYTES:FRONT_BYTES + nbytes].view(t.dtype).view(t.shape)
             view.copy_(t)
             setattr(self, name, view)
             self._guards[name] = (big, nbytes)
-        for name in READ_BUFFERS:                        # inputs: NaN behind them, so a read past the end shows
+        for name in READ_BUFFERS:                        # inputs: NaN around them, so a read outside them shows
             t = getattr(self, name, None)
             if t is None:
                 continue
-            big = torch.full((t.numel() + GUARD_BYTES // 2,), float("nan"), dtype=t.dtype, device=t.device)
-            view = big[:t.numel()].view(t.shape)
+            front = FRONT_BYTES // t.element_size()
+            big = torch.full((front + t.numel() + GUARD_BYTES // 2,), float("nan"), dtype=t.dtype, device=t.device)
+            view = big[front:front + t.numel()].view(t.shape)
             view.copy_(t)
             setattr(self, name, view)
         self._fwd_args = self._bwd_args = None          # marshalled pointers are stale
@@ -74,9 +77,9 @@ def guard_bytes_behind_written_buffers():
     def results(self):
         out = plain_results(self)
         for name, (big, nbytes) in self._guards.items():
-            tail = big[nbytes:]
-            assert bool((tail == 0xA5).all()), \
-                f"{int((tail != 0xA5).sum())} guard bytes behind {name} were overwritten"
+            around = torch.cat([big[:FRONT_BYTES], big[FRONT_BYTES + nbytes:]])
+            assert bool((around == 0xA5).all()), \
+                f"{int((around != 0xA5).sum())} guard bytes around {name} were overwritten"
         return out
 
     bns.Buffers.__init__, bns.Buffers.results = init, results
