@@ -383,6 +383,41 @@ def test_missing_team_mate_ends_in_nan_not_in_a_hang(kernel_path):
     assert_parity(good, oracle_reference(wl, inp), wl, what="after the give-up run", inp=inp)
 
 
+def test_host_threads_on_their_own_streams_with_the_streaming_kernels():
+    """Several host threads call the library at once, each on a stream of its own with buffers of its own.  The
+    streaming kernels have no waits between blocks, so they may share the device (the single-launch kernels
+    size their grid to the whole device; include/bns.h, Concurrency)."""
+    import threading
+    results, errors = {}, []
+
+    def worker(k):
+        try:
+            wl = Workload(name=f"thread{k}", N=6 + k, C=24 + 8 * k, H=12, W=8 + 4 * k, mode=(BS, FS, NS, FULL)[k % 4], n_s=2,
+                          patch_h=5, patch_w=3, dtype=("f32", "bf16")[k % 2], layout=("nchw", "nhwc")[(k // 2) % 2],
+                          data_seed=60 + k, sampling_seed=70 + k, layer_id=k, epoch=1)
+            inp = workloads.make_inputs(wl)
+            with torch.cuda.stream(torch.cuda.Stream()):
+                for _ in range(25):
+                    res = bns.run_workload(wl, inp)
+            results[k] = (wl, inp, res)
+        except Exception as e:          # noqa: BLE001  (reported below, in the main thread)
+            errors.append((k, repr(e)))
+
+    bns.bns_set_option("path", 1)
+    try:
+        threads = [threading.Thread(target=worker, args=(k,)) for k in range(8)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+    finally:
+        bns.bns_set_option("path", 0)
+    assert not errors, errors
+    assert len(results) == 8
+    for k, (wl, inp, res) in sorted(results.items()):
+        assert_parity(res, oracle_reference(wl, inp), wl, what=f"thread {k} {wl}", inp=inp)
+
+
 def test_running_statistics_over_iterations_and_null_running_buffers():
     wl = workloads.WORKLOADS["tiny_bs"]
     inp = workloads.make_inputs(wl)
