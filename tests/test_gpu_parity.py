@@ -597,7 +597,7 @@ def test_inference_mode(shape, dtype, kernel_path):
     assert scaled_err(got, ref) <= (1e-5 if dtype == "f32" else 1e-2)
 
 
-@pytest.mark.parametrize("name", ["micro_a_fs", "tiny_bs", "cifar_fs"])
+@pytest.mark.parametrize("name", ["micro_a_fs", "tiny_bs", "cifar_fs", "vdn_fs_mix", "vdn_bs_mix"])
 def test_hip_graph_capture_and_replay(name, kernel_path):
     """The library allocates nothing and never synchronises, so a forward + backward can be captured
     into a HIP graph.  Every replay is checked against the eager result, with eager work and
@@ -605,6 +605,8 @@ def test_hip_graph_capture_and_replay(name, kernel_path):
     wl = workloads.WORKLOADS[name]
     if name == "cifar_fs":
         wl = wl.replace(N=16)
+    if name.startswith("vdn_"):                         # Eq. 4: bns_forward_mixed / bns_backward_mixed
+        wl = wl.replace(C=32)
     inp = workloads.make_inputs(wl)
     eager = bns.run_workload(wl, inp)
     buf = bns.Buffers(wl, inp)
