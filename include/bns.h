@@ -227,6 +227,13 @@ bns_status bns_backward_mixed(const bns_shape* shape, const bns_spec* spec, uint
 bns_status bns_inference(const bns_shape* shape, const void* x, const float* gamma, const float* beta,
                          const float* running_mean, const float* running_var, float eps, void* y, void* stream);
 
+/* Weight of the new statistics in Eq. 8 at training iteration `iteration` (counted from 1): 1 at the first
+ * iteration, where the moving average starts as a copy of the statistics, alpha afterwards.  The value to
+ * pass as `momentum` to bns_forward / bns_forward_mixed.  HOST function, no device is touched; iteration 0
+ * is treated as the first.  (Appendix D reports a larger alpha than the customary 0.1 to work better for
+ * the noisier sampled statistics, so alpha is the caller's choice.) */
+float bns_moving_average_weight(uint64_t iteration, float alpha);
+
 /* Plain device-to-device copy of `bytes` bytes (a multiple of 16) with 128-bit accesses:
  * the "achievable bandwidth" yardstick that the benchmark reports beside the BN kernels,
  * and the known-size kernel that hardware traffic counters are calibrated against. */

@@ -174,6 +174,12 @@ def forward(x, gamma, beta, boxes, eps: float, momentum: float = 0.1,
     return out
 
 
+def moving_average_weight(iteration: int, alpha: float) -> float:
+    """Eq. 8, weight of the current statistics at iteration it (counted from 1): the moving average
+    is the statistics themselves at it = 1 and alpha * X + (1 - alpha) * X_ma afterwards."""
+    return 1.0 if iteration <= 1 else float(alpha)
+
+
 def inference(x, gamma, beta, moving_mean, moving_var, eps: float):
     """Validation-time normalisation (Appendix D): E and Var of Eq. 1 are replaced by the
     recorded moving averages of Eq. 8."""

@@ -67,6 +67,7 @@ _PROTOS = {
     "bns_backward_mixed": (C.c_int, [_SHP, _SPC, C.c_uint64, C.c_int32, C.c_float, _P, _P, _P, _P, _P, _P,
                                      _P, _P, _P, _P, C.c_size_t, _P]),
     "bns_inference": (C.c_int, [_SHP, _P, _P, _P, _P, _P, C.c_float, _P, _P]),
+    "bns_moving_average_weight": (C.c_float, [C.c_uint64, C.c_float]),
     "bns_copy_reference": (C.c_int, [_P, _P, C.c_size_t, _P]),
     "bns_set_option": (C.c_int, [C.c_char_p, C.c_int32]),
     "bns_get_option": (C.c_int32, [C.c_char_p]),
@@ -247,6 +248,10 @@ def bns_backward_mixed(shape, spec, seed, n_v, mix_beta, x, dy, gamma, save_mean
 def bns_inference(shape, x, gamma, beta, running_mean, running_var, eps, y):
     _check(load().bns_inference(C.byref(shape), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(running_mean),
                                 _ptr(running_var), C.c_float(eps), _ptr(y), _stream(x)), "bns_inference")
+
+
+def bns_moving_average_weight(iteration: int, alpha: float) -> float:
+    return float(load().bns_moving_average_weight(C.c_uint64(iteration), C.c_float(alpha)))
 
 
 def bns_copy_reference(dst, src):

@@ -550,6 +550,8 @@ bns_status bns_backward_mixed(const bns_shape* shape, const bns_spec* spec, uint
     return dev(launch_dx(d, ip_s, x, dy, gamma, save_mean, save_invstd, dgamma, dbeta, dx, 0, d.C, st, &sets));
 }
 
+float bns_moving_average_weight(uint64_t iteration, float alpha) { return iteration <= 1 ? 1.0f : alpha; }   // Eq. 8
+
 bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* stream) {
     if (!dst || !src || (bytes & 15u) || !aligned16(dst) || !aligned16(src)) return BNS_EINVAL;
     if ((bytes / 16 + 1023) / 1024 >= (size_t(1) << 31)) return BNS_EUNSUPPORTED;

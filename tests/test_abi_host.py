@@ -238,3 +238,13 @@ def test_header_is_plain_c(tmp_path):
     assert out.returncode == 0, out.stderr
     # the ctypes mirrors of the structs have the C sizes
     assert C.sizeof(bns.bns_shape) == 24 and C.sizeof(bns.bns_spec) == 28 and C.sizeof(bns.bns_box) == 24
+
+
+def test_moving_average_weight_is_eq8_and_matches_the_oracle():
+    from oracle import bns_oracle as oracle
+    assert bns.bns_moving_average_weight(1, 0.1) == 1.0                       # Eq. 8, it = 1: a copy
+    assert bns.bns_moving_average_weight(0, 0.25) == 1.0                      # nothing recorded yet either
+    for it in (2, 3, 1000, 2 ** 40):
+        for alpha in (0.0, 0.1, 0.7, 1.0):
+            got = bns.bns_moving_average_weight(it, alpha)
+            assert got == np.float32(alpha) == np.float32(oracle.moving_average_weight(it, alpha))

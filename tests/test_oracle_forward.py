@@ -143,3 +143,19 @@ def test_inference_is_torch_eval_batch_norm_and_continues_training_statistics():
     f = o.forward(x, gamma, beta, boxes, EPS, momentum=1.0, running_mean=rm, running_var=rv)
     np.testing.assert_allclose(o.inference(x, gamma, beta, f["running_mean"], f["running_var"], EPS), f["y"],
                                rtol=1e-12, atol=1e-13)
+
+
+def test_moving_average_weight_gives_the_unrolled_form_of_eq8():
+    """Eq. 8 unrolled by hand: X_ma(n) = (1-a)^(n-1) X_1 + a * sum_{j=2..n} (1-a)^(n-j) X_j, whatever the
+    moving average held before the first iteration."""
+    rng = np.random.default_rng(8)
+    for alpha in (0.1, 0.3, 0.7, 1.0):
+        xs = rng.standard_normal(9)
+        ma = 123.456                                  # must be forgotten at it = 1
+        for it, x_it in enumerate(xs, start=1):
+            a = o.moving_average_weight(it, alpha)
+            ma = a * x_it + (1.0 - a) * ma            # the update the forward pass applies
+            n = it
+            want = (1 - alpha) ** (n - 1) * xs[0] + alpha * sum((1 - alpha) ** (n - j) * xs[j - 1] for j in range(2, n + 1))
+            assert abs(ma - want) < 1e-12, (alpha, it)
+    assert o.moving_average_weight(1, 0.1) == 1.0 and o.moving_average_weight(2, 0.1) == 0.1

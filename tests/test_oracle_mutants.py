@@ -81,6 +81,13 @@ def _battery(o):
     ref = torch.nn.functional.batch_norm(torch.tensor(x), torch.tensor(rm), torch.tensor(rv), torch.tensor(gamma),
                                          torch.tensor(beta), training=False, eps=EPS)
     np.testing.assert_allclose(o.inference(x, gamma, beta, rm, rv, EPS), ref.numpy(), rtol=1e-12, atol=1e-13)
+    # Eq. 8 unrolled by hand: X_ma(n) = (1-a)^(n-1) X_1 + a sum_{j=2..n} (1-a)^(n-j) X_j
+    xs, alpha, ma = rng.standard_normal(5), 0.3, 99.0
+    for it, x_it in enumerate(xs, start=1):
+        a = o.moving_average_weight(it, alpha)
+        ma = a * x_it + (1.0 - a) * ma
+    want = (1 - alpha) ** 4 * xs[0] + alpha * sum((1 - alpha) ** (5 - j) * xs[j - 1] for j in range(2, 6))
+    assert abs(ma - want) < 1e-12
     # VDN + sampling (Eq. 4) against autograd through explicit slices
     n_v = 2
     for mode, kw, mix in [(o.BS, dict(n_s=2), 0.5), (o.FS, dict(patch_h=2, patch_w=3), 0.3), (o.FULL, {}, 0.7)]:
@@ -133,6 +140,8 @@ MUTANTS = [
     ("FS width drawn from height", "w0 = randint(0, W - patch_w,", "w0 = randint(0, H - patch_h,"),
     ("VDN takes the last samples", "elif mode in (NS, VDN):\n            nc = n_s", "elif mode in (NS, VDN):\n            nc = n_s\n            n0 = N - n_s"),
     ("inference: eps outside the root", "/ math.sqrt(float(moving_var[k]) + eps)", "/ (math.sqrt(float(moving_var[k])) + eps)"),
+    ("Eq. 8: first iteration averaged like the others", "return 1.0 if iteration <= 1 else float(alpha)", "return float(alpha)"),
+    ("Eq. 8: second iteration still a copy", "return 1.0 if iteration <= 1 else float(alpha)", "return 1.0 if iteration <= 2 else float(alpha)"),
     ("mixed: real samples not shifted", "boxes_s[:, 0] += n_v", "boxes_s[:, 0] += 0"),
     ("mixed: sampling sees the virtual samples", "real = sample_index(N - n_v, C, H, W, mode,", "real = sample_index(N, C, H, W, mode,"),
     ("mixed: weights swapped", "E[k] = mix_beta * E_v[k] + (1.0 - mix_beta) * E_s[k]", "E[k] = (1.0 - mix_beta) * E_v[k] + mix_beta * E_s[k]"),
