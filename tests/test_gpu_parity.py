@@ -472,10 +472,11 @@ def test_running_statistics_over_iterations_and_null_running_buffers():
     boxes = oracle_boxes(wl)
     rm, rv = inp["running_mean"].astype(np.float64), inp["running_var"].astype(np.float64)
     for it in range(4):
-        mom = 1.0 if it == 0 else wl.momentum                      # Eq. 8: first iteration copies
+        mom = bns.bns_moving_average_weight(it + 1, wl.momentum)   # Eq. 8: the first iteration copies
         bns.bns_forward(buf.shape, buf.spec, buf.seed, buf.x, buf.gamma, buf.beta, wl.eps, mom, buf.y, buf.save_mean,
                         buf.save_invstd, buf.running_mean, buf.running_var, buf.workspace)
-        f = oracle.forward(inp["x"], inp["gamma"], inp["beta"], boxes, wl.eps, mom, rm, rv)
+        f = oracle.forward(inp["x"], inp["gamma"], inp["beta"], boxes, wl.eps,
+                           oracle.moving_average_weight(it + 1, wl.momentum), rm, rv)
         rm, rv = f["running_mean"], f["running_var"]
     r = buf.results()
     np.testing.assert_allclose(r["running_mean"], rm, rtol=1e-5, atol=1e-6)
