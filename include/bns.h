@@ -159,6 +159,21 @@ bns_status bns_backward(const bns_shape* shape, const bns_spec* spec, uint64_t s
                         void* dx, float* dgamma, float* dbeta,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/* bns_backward for callers that cannot hand over a workspace they allocated: code recorded into a HIP graph
+ * whose buffers are fixed before the scratch size is known, tight serving or training loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results (bit for bit) and errors as bns_backward, without `workspace`:
+ * the partial sums and exchange slots live in a 4 MiB array built into the library's device code, one copy
+ * per GPU, held from the first use of the library on that GPU until the process ends.  The call allocates
+ * and frees nothing.  BNS_EWORKSPACE if bns_workspace_bytes(shape, spec) exceeds 4 MiB (N x C x H x W: more than
+ * 3840 channels).  All such calls on one GPU share the one array, which keeps what the last call left in it
+ * (nothing in it has to start at zero): they must be ordered on one stream, like calls that share a
+ * workspace; calls that overlap on a GPU race.  The first call on each GPU looks the array's address up and
+ * should be made outside stream capture. */
+bns_status bns_backward_builtin_workspace(const bns_shape* shape, const bns_spec* spec, uint64_t seed,
+                                          const void* x, const void* dy, const float* gamma,
+                                          const float* save_mean, const float* save_invstd,
+                                          void* dx, float* dgamma, float* dbeta, void* stream);
+
 /* The stages that the two calls above are made of, for callers that want to place
  * other work between them (and for per-kernel timing).  Same conventions.
  *

@@ -56,6 +56,7 @@ _PROTOS = {
     "bns_forward": (C.c_int, [_SHP, _SPC, C.c_uint64, _P, _P, _P, C.c_float, C.c_float,
                               _P, _P, _P, _P, _P, _P, C.c_size_t, _P]),
     "bns_backward": (C.c_int, [_SHP, _SPC, C.c_uint64, _P, _P, _P, _P, _P, _P, _P, _P, _P, C.c_size_t, _P]),
+    "bns_backward_builtin_workspace": (C.c_int, [_SHP, _SPC, C.c_uint64, _P, _P, _P, _P, _P, _P, _P, _P, _P]),
     "bns_forward_stats": (C.c_int, [_SHP, _SPC, C.c_uint64, _P, C.c_float, C.c_float, _P, _P, _P, _P,
                                     _P, C.c_size_t, _P]),
     "bns_forward_normalize": (C.c_int, [_SHP, _P, _P, _P, _P, _P, _P, _P]),
@@ -187,6 +188,13 @@ def bns_backward(shape, spec, seed, x, dy, gamma, save_mean, save_invstd, dx, dg
                                _ptr(save_mean), _ptr(save_invstd), _ptr(dx), _ptr(dgamma), _ptr(dbeta),
                                _ptr(workspace), C.c_size_t(workspace.numel() * workspace.element_size()),
                                _stream(x)), "bns_backward")
+
+
+def bns_backward_builtin_workspace(shape, spec, seed, x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta):
+    _check(load().bns_backward_builtin_workspace(C.byref(shape), C.byref(spec), C.c_uint64(seed), _ptr(x), _ptr(dy),
+                                                 _ptr(gamma), _ptr(save_mean), _ptr(save_invstd), _ptr(dx),
+                                                 _ptr(dgamma), _ptr(dbeta), _stream(x)),
+           "bns_backward_builtin_workspace")
 
 
 def bns_forward_stats(shape, spec, seed, x, eps, momentum, save_mean, save_invstd, running_mean, running_var,

@@ -11,6 +11,10 @@
 
 using namespace bns;
 
+// Built-in scratch memory of bns_backward_builtin_workspace (see there).
+constexpr size_t kBuiltinWorkspaceBytes = size_t(4) << 20;
+static __device__ __align__(256) unsigned char scratch[kBuiltinWorkspaceBytes];
+
 namespace {
 
 std::atomic<int32_t> g_splits_stats{0};
@@ -343,19 +347,29 @@ bns_status bns_backward_dx(const bns_shape* shape, const bns_spec* spec, uint64_
                          static_cast<hipStream_t>(stream)));
 }
 
-bns_status bns_backward(const bns_shape* shape, const bns_spec* spec, uint64_t seed, const void* x, const void* dy,
-                        const float* gamma, const float* save_mean, const float* save_invstd, void* dx,
-                        float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes, void* stream) {
-    Dims d;
+namespace {
+// Host-side checks of bns_backward's tensor arguments (everything but the workspace); fills `d`.
+bns_status backward_check(const bns_shape* shape, const bns_spec* spec, const void* x, const void* dy,
+                          const float* gamma, const float* save_mean, const float* save_invstd, const void* dx,
+                          const float* dgamma, const float* dbeta, Dims* dims) {
+    Dims& d = *dims;
     bns_status s = check_shape(shape, &d);
     if (s != BNS_OK) return s;
     if ((s = check_spec(shape, spec)) != BNS_OK) return s;
-    if (!x || !dy || !gamma || !save_mean || !save_invstd || !dx || !dgamma || !dbeta || !workspace)
-        return BNS_EINVAL;
-    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || !aligned16(workspace)) return BNS_EINVAL;
+    if (!x || !dy || !gamma || !save_mean || !save_invstd || !dx || !dgamma || !dbeta) return BNS_EINVAL;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx)) return BNS_EINVAL;
     const size_t tb = tensor_bytes(d);
     if (overlap(dx, tb, x, tb) || overlap(dx, tb, dy, tb)) return BNS_EINVAL;
-    if ((s = check_layout(d, spec)) != BNS_OK) return s;
+    return check_layout(d, spec);
+}
+
+bns_status backward_impl(const bns_shape* shape, const bns_spec* spec, uint64_t seed, const void* x, const void* dy,
+                         const float* gamma, const float* save_mean, const float* save_invstd, void* dx,
+                         float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes, void* stream) {
+    Dims d;
+    bns_status s = backward_check(shape, spec, x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta, &d);
+    if (s != BNS_OK) return s;
+    if (!workspace || !aligned16(workspace)) return BNS_EINVAL;
     if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
     const IndexParams ip = make_index_params(*shape, *spec, seed);
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -400,6 +414,49 @@ bns_status bns_backward(const bns_shape* shape, const bns_spec* spec, uint64_t s
         if (s != BNS_OK) return s;
     }
     return BNS_OK;
+}
+
+// Scratch memory of bns_backward_builtin_workspace: one copy per device, held from the moment the library's code
+// is loaded on that device until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; kernels and copies take the address that call returns.
+constexpr int kMaxDevices = 16;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Address of this device's copy of `scratch` (looked up once per device, with that device current).
+bns_status builtin_workspace(void** out) {
+    int devid = -1;
+    if (hipGetDevice(&devid) != hipSuccess) return BNS_EDEVICE;
+    if (devid < 0 || devid >= kMaxDevices) return BNS_EUNSUPPORTED;
+    void* p = g_scratch_ptr[devid].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return BNS_EDEVICE;
+        g_scratch_ptr[devid].store(p, std::memory_order_release);     // every thread finds the same address
+    }
+    *out = p;
+    return BNS_OK;
+}
+}  // namespace
+
+bns_status bns_backward(const bns_shape* shape, const bns_spec* spec, uint64_t seed, const void* x, const void* dy,
+                        const float* gamma, const float* save_mean, const float* save_invstd, void* dx,
+                        float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes, void* stream) {
+    return backward_impl(shape, spec, seed, x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta, workspace,
+                         workspace_bytes, stream);
+}
+
+bns_status bns_backward_builtin_workspace(const bns_shape* shape, const bns_spec* spec, uint64_t seed, const void* x,
+                                          const void* dy, const float* gamma, const float* save_mean,
+                                          const float* save_invstd, void* dx, float* dgamma, float* dbeta,
+                                          void* stream) {
+    Dims d;
+    const bns_status s = backward_check(shape, spec, x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta, &d);
+    if (s != BNS_OK) return s;
+    if (workspace_need(d) > kBuiltinWorkspaceBytes) return BNS_EWORKSPACE;     // too many channels for the built-in scratch
+    void* ws = nullptr;
+    const bns_status ws_status = builtin_workspace(&ws);
+    if (ws_status != BNS_OK) return ws_status;
+    return backward_impl(shape, spec, seed, x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta, ws,
+                         kBuiltinWorkspaceBytes, stream);
 }
 
 // ---- "VDN + sampling", Eq. 4 ---------------------------------------------------------------

@@ -129,6 +129,26 @@ def test_null_misaligned_overlapping_and_small_workspace_are_rejected_without_a_
     assert lib.bns_copy_reference(P(x), P(x + 32), 64, None) == bns.BNS_EINVAL
 
 
+def test_builtin_workspace_call_validates_before_it_touches_a_device():
+    """bns_backward_builtin_workspace: bns_backward's argument checks, then the 4 MiB limit, all on the host."""
+    lib = bns.load()
+    shape, spec = bns.make_shape(8, 4, 6, 6), bns.make_spec(bns.BNS_BS, 2)
+    P = lambda a: C.c_void_p(a)
+    x, dy, dx, v = 0x10000, 0x30000, 0x40000, 0x60000
+
+    def call(shape=shape, spec=spec, x=x, dy=dy, dx=dx, gamma=v):
+        return lib.bns_backward_builtin_workspace(C.byref(shape), C.byref(spec), 1, P(x), P(dy), P(gamma), P(v + 128),
+                                                  P(v + 256), P(dx), P(v + 384), P(v + 512), None)
+
+    assert call(x=0) == bns.BNS_EINVAL and call(dx=0) == bns.BNS_EINVAL and call(gamma=0) == bns.BNS_EINVAL
+    assert call(dy=dy + 4) == bns.BNS_EINVAL and call(dx=dy) == bns.BNS_EINVAL
+    assert call(spec=bns.make_spec(bns.BNS_BS, 9)) == bns.BNS_EINVAL
+    big = bns.make_shape(2, 3841, 2, 2)
+    assert bns.bns_workspace_bytes(big, spec) > 4 << 20
+    assert call(shape=big, x=0x1000000, dy=0x2000000, dx=0x3000000) == bns.BNS_EWORKSPACE
+    assert bns.bns_workspace_bytes(bns.make_shape(2, 3840, 2, 2), spec) <= 4 << 20
+
+
 def test_mixed_index_and_argument_checks():
     rng = np.random.default_rng(4)
     for _ in range(400):
