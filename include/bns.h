@@ -21,20 +21,26 @@
  *            frees nothing and keeps no state between calls except the tuning
  *            overrides of bns_set_option.  `workspace` is caller-provided
  *            device scratch of at least bns_workspace_bytes() bytes; its
- *            contents need not be initialised and are undefined afterwards.
+ *            contents need not be initialised.  Its first 256 bytes hold a launch
+ *            counter that the single-launch kernels keep from call to call: a
+ *            workspace may be overwritten between calls (the counter is set up
+ *            again), but not while a call that uses it is running.
  * Streams    `stream` is a hipStream_t passed as void* (NULL = the default
  *            stream).  Work is enqueued on it and the call returns without
  *            synchronising.  Calls that share a workspace must be ordered on
  *            one stream.
  * Concurrency The single-launch ("fused") kernels size their grid to what the
  *            device holds at once and let the blocks that share a channel wait
- *            for each other.  If other kernels occupy the device at the same
- *            time (another stream, another process), such a wait can last until
- *            those finish; it is bounded (2^21 polls), after which the sums of
- *            that channel are NaN and the kernel still ends: never a hang, and
- *            never a silently wrong finite value.  Callers that overlap libbns
- *            with other GPU work set the "path" option to 1: the streaming
- *            kernels have no waits between blocks.
+ *            for each other.  Calls from several host threads and streams of one
+ *            process are safe: the library chains such kernels with an event, so
+ *            that two of them never share the device.  If work the library does not
+ *            know of occupies the device at the same time (another process, a HIP
+ *            graph that holds captured libbns calls and is replayed beside other
+ *            libbns calls), a wait can last until that work ends; it is bounded
+ *            (2^21 polls, then 2^15 for the rest of the launch), after which the
+ *            results of that channel are NaN -- never a wrong finite value -- the
+ *            moving averages keep their old values, the kernel ends normally, and
+ *            bns_expired_waits() reports it, so nobody has to scan tensors.
  * Aliasing   Outputs must not overlap inputs or each other (x is needed again
  *            by the backward pass; dx is written while dy is read).
  * Errors     Every call returns a bns_status.  Arguments are validated on the
@@ -174,6 +180,14 @@ bns_status bns_backward_builtin_workspace(const bns_shape* shape, const bns_spec
                                           const float* save_mean, const float* save_invstd,
                                           void* dx, float* dgamma, float* dbeta, void* stream);
 
+/* How many waits between blocks of the single-launch kernels ran out (see Concurrency) in the calls that used
+ * `workspace` since the last such query; 0 = every result is what the equations say.  Calls whose waits ran
+ * out have written NaN to the outputs of the channels concerned.  Synchronises `stream` (the stream those calls
+ * were issued to), reads the count from the workspace and clears it; not to be called while `stream` is being
+ * captured.  workspace = NULL asks about the built-in scratch of bns_backward_builtin_workspace.
+ * expired: HOST, written. */
+bns_status bns_expired_waits(void* workspace, size_t workspace_bytes, void* stream, int32_t* expired /* HOST */);
+
 /* The stages that the two calls above are made of, for callers that want to place
  * other work between them (and for per-kernel timing).  Same conventions.
  *
@@ -262,6 +276,10 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  *                    (BNS_EUNSUPPORTED if a channel does not fit or the layout is N x H x W x C, which has
  *                    none); 0: whichever is faster for the shape
  *   "fused_variant"  1..7: block size / registers-per-thread variant of the fused kernels
+ *   "fused_pipe"     the backward kernel that holds two channels per block, loading the next one while the
+ *                    sums of the current one are exchanged: 1..6 that (block size, vectors) variant whatever
+ *                    the shape, 16 never; 0: when the launch has three or more rounds (tensors below 4 GiB)
+ *   "fused_team"     blocks that share a channel in that kernel, if they can hold it    (1..128)
  *   "fused_coop"     1: launch the fused kernels with hipLaunchCooperativeKernel
  *   "fused_spin_limit"  polls a block of a fused kernel waits for a team-mate's sums before it gives up
  *                    (1..2^21, the default); "fused_mute" 1: no block publishes its sums, so every such wait
@@ -284,8 +302,8 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  *   "norm_nt", "dx_nt", "reduce_nt"   non-temporal access mask + 1: bit 0 loads, bit 1 stores
  * Notes on the fused kernels: blocks of a team exchange partial sums through the workspace and wait
  * for each other with a bounded spin (the grid never exceeds what the device holds at once); they
- * are bit-reproducible like the streaming kernels; teams of more than one block are not used while
- * the stream is being captured into a graph (the streaming kernels are captured instead). */
+ * are bit-reproducible like the streaming kernels, and they can be captured into a HIP graph like any other
+ * launch (the stamps that tell one exchange from the next are counted in the workspace, on the device). */
 bns_status bns_set_option(const char* name, int32_t value);
 /* Current value of an option (as set, 0 = automatic); also "last_path_forward" / "last_path_backward":
  * 1 if the last bns_forward / bns_backward took the streaming kernels, 2 if the fused one, 3 if the

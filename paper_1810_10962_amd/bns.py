@@ -57,6 +57,7 @@ _PROTOS = {
                               _P, _P, _P, _P, _P, _P, C.c_size_t, _P]),
     "bns_backward": (C.c_int, [_SHP, _SPC, C.c_uint64, _P, _P, _P, _P, _P, _P, _P, _P, _P, C.c_size_t, _P]),
     "bns_backward_builtin_workspace": (C.c_int, [_SHP, _SPC, C.c_uint64, _P, _P, _P, _P, _P, _P, _P, _P, _P]),
+    "bns_expired_waits": (C.c_int, [_P, C.c_size_t, _P, C.POINTER(C.c_int32)]),
     "bns_forward_stats": (C.c_int, [_SHP, _SPC, C.c_uint64, _P, C.c_float, C.c_float, _P, _P, _P, _P,
                                     _P, C.c_size_t, _P]),
     "bns_forward_normalize": (C.c_int, [_SHP, _P, _P, _P, _P, _P, _P, _P]),
@@ -195,6 +196,17 @@ def bns_backward_builtin_workspace(shape, spec, seed, x, dy, gamma, save_mean, s
                                                  _ptr(gamma), _ptr(save_mean), _ptr(save_invstd), _ptr(dx),
                                                  _ptr(dgamma), _ptr(dbeta), _stream(x)),
            "bns_backward_builtin_workspace")
+
+
+def bns_expired_waits(workspace=None, stream_of=None) -> int:
+    """Waits between blocks that ran out in the calls on `workspace` (None: the built-in scratch) since the last query."""
+    import torch
+    out = C.c_int32(-1)
+    t = workspace if workspace is not None else stream_of
+    stream = _stream(t) if t is not None else C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    nbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load().bns_expired_waits(_ptr(workspace), C.c_size_t(nbytes), stream, C.byref(out)), "bns_expired_waits")
+    return int(out.value)
 
 
 def bns_forward_stats(shape, spec, seed, x, eps, momentum, save_mean, save_invstd, running_mean, running_var,

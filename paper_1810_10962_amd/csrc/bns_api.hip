@@ -12,7 +12,7 @@
 using namespace bns;
 
 // Built-in scratch memory of bns_backward_builtin_workspace (see there).
-constexpr size_t kBuiltinWorkspaceBytes = size_t(4) << 20;
+constexpr size_t kBuiltinWorkspaceBytes = (size_t(4) << 20) + bns::kHeaderBytes;    // 3840 channels
 static __device__ __align__(256) unsigned char scratch[kBuiltinWorkspaceBytes];
 
 namespace {
@@ -79,9 +79,17 @@ inline size_t elem_bytes(const Dims& d) { return d.dtype == BNS_F32 ? 4 : 2; }
 inline size_t tensor_bytes(const Dims& d) { return size_t(d.N) * d.C * d.HW * elem_bytes(d); }
 inline size_t partial_bytes(const Dims& d) { return (size_t(d.C) * kMaxSplits * sizeof(Partial) + 255) & ~size_t(255); }
 inline bool nhwc(const Dims& d) { return d.layout == BNS_NHWC; }
+// Workspace layout: [header][sums S][sums V][slots] (N x H x W x C: no slots).  The header comes first so that
+// bns_expired_waits finds it without knowing the shape.
 inline size_t workspace_need(const Dims& d) {
-    if (nhwc(d)) return 2 * nhwc_partial_bytes(d);   // [sums S][sums V]
-    return 2 * partial_bytes(d) + kSlotBytes;   // [sums S][sums V][slots]
+    if (nhwc(d)) return kHeaderBytes + 2 * nhwc_partial_bytes(d);
+    return kHeaderBytes + 2 * partial_bytes(d) + kSlotBytes;
+}
+inline Partial* partials_of(void* workspace) {
+    return reinterpret_cast<Partial*>(static_cast<char*>(workspace) + kHeaderBytes);
+}
+inline void* slots_of(void* workspace, const Dims& d) {
+    return static_cast<char*>(workspace) + kHeaderBytes + 2 * partial_bytes(d);
 }
 // N x H x W x C: one location set for all channels
 inline bns_status check_layout(const Dims& d, const bns_spec* sp) {
@@ -104,6 +112,8 @@ const TuningEntry kTuningTable[] = {
     {"reduce_unroll", &Tuning::reduce_unroll, 4, 0, true}, {"reduce_nt", &Tuning::reduce_nt, 2, 1, false},
     {"path", &Tuning::path, 2, 0, false},
     {"fused_variant", &Tuning::fused_variant, 7, 0, false},
+    {"fused_pipe", &Tuning::fused_pipe, 16, 0, false},
+    {"fused_team", &Tuning::fused_team, 128, 0, false},
     {"fused_coop", &Tuning::fused_coop, 1, 0, false},
     {"fused_spin_limit", &Tuning::fused_spin_limit, 1 << 21, 0, false},
     {"fused_mute", &Tuning::fused_mute, 1, 0, false},
@@ -214,10 +224,10 @@ bns_status bns_forward_stats(const bns_shape* shape, const bns_spec* spec, uint6
     if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
     const IndexParams ip = make_index_params(*shape, *spec, seed);
     if (nhwc(d))
-        return dev(launch_nhwc_stats(d, ip.shared, x, static_cast<Partial*>(workspace), eps, momentum, save_mean,
+        return dev(launch_nhwc_stats(d, ip.shared, x, partials_of(workspace), eps, momentum, save_mean,
                                      save_invstd, running_mean, running_var, static_cast<hipStream_t>(stream)));
     return stats_range(d, ip, x, eps, momentum, save_mean, save_invstd, running_mean, running_var,
-                       static_cast<Partial*>(workspace), 0, d.C, static_cast<hipStream_t>(stream));
+                       partials_of(workspace), 0, d.C, static_cast<hipStream_t>(stream));
 }
 
 bns_status bns_forward_normalize(const bns_shape* shape, const void* x, const float* gamma, const float* beta,
@@ -265,7 +275,7 @@ bns_status bns_forward(const bns_shape* shape, const bns_spec* spec, uint64_t se
     if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
     const IndexParams ip = make_index_params(*shape, *spec, seed);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    Partial* ws = static_cast<Partial*>(workspace);
+    Partial* ws = partials_of(workspace);
     if (nhwc(d)) {
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
         hipError_t se = hipSuccess;
@@ -291,7 +301,7 @@ bns_status bns_forward(const bns_shape* shape, const bns_spec* spec, uint64_t se
         io.running_mean = running_mean;
         io.running_var = running_var;
         const hipError_t fe = launch_fused(d, ip, false, io, eps, momentum,
-                                           static_cast<char*>(workspace) + 2 * partial_bytes(d), kSlotBytes, 0, d.C, st);
+                                           workspace, slots_of(workspace, d), kSlotBytes, 0, d.C, st);
         if (fe == hipSuccess) {
             g_last_path_forward.store(2);
             return BNS_OK;
@@ -321,9 +331,9 @@ bns_status bns_backward_reduce(const bns_shape* shape, const void* x, const void
     if (!aligned16(x) || !aligned16(dy) || !aligned16(workspace)) return BNS_EINVAL;
     if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
     if (nhwc(d))
-        return dev(launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, static_cast<Partial*>(workspace), dgamma, dbeta,
+        return dev(launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, partials_of(workspace), dgamma, dbeta,
                                       static_cast<hipStream_t>(stream)));
-    return reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, static_cast<Partial*>(workspace), 0, d.C,
+    return reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, partials_of(workspace), 0, d.C,
                         static_cast<hipStream_t>(stream));
 }
 
@@ -365,7 +375,8 @@ bns_status backward_check(const bns_shape* shape, const bns_spec* spec, const vo
 
 bns_status backward_impl(const bns_shape* shape, const bns_spec* spec, uint64_t seed, const void* x, const void* dy,
                          const float* gamma, const float* save_mean, const float* save_invstd, void* dx,
-                         float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes, void* stream) {
+                         float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes, void* stream,
+                         bool order_streams) {
     Dims d;
     bns_status s = backward_check(shape, spec, x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta, &d);
     if (s != BNS_OK) return s;
@@ -373,7 +384,7 @@ bns_status backward_impl(const bns_shape* shape, const bns_spec* spec, uint64_t 
     if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
     const IndexParams ip = make_index_params(*shape, *spec, seed);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    Partial* ws = static_cast<Partial*>(workspace);
+    Partial* ws = partials_of(workspace);
     if (nhwc(d)) {
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
         hipError_t se = hipSuccess;
@@ -395,8 +406,8 @@ bns_status backward_impl(const bns_shape* shape, const bns_spec* spec, uint64_t 
         io.save_invstd = const_cast<float*>(save_invstd);
         io.dgamma = dgamma;
         io.dbeta = dbeta;
-        const hipError_t fe = launch_fused(d, ip, true, io, 0.f, 0.f, static_cast<char*>(workspace) + 2 * partial_bytes(d),
-                                           kSlotBytes, 0, d.C, st);
+        const hipError_t fe = launch_fused(d, ip, true, io, 0.f, 0.f, workspace, slots_of(workspace, d),
+                                           kSlotBytes, 0, d.C, st, nullptr, order_streams);
         if (fe == hipSuccess) {
             g_last_path_backward.store(2);
             return BNS_OK;
@@ -441,7 +452,7 @@ bns_status bns_backward(const bns_shape* shape, const bns_spec* spec, uint64_t s
                         const float* gamma, const float* save_mean, const float* save_invstd, void* dx,
                         float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes, void* stream) {
     return backward_impl(shape, spec, seed, x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta, workspace,
-                         workspace_bytes, stream);
+                         workspace_bytes, stream, true);
 }
 
 bns_status bns_backward_builtin_workspace(const bns_shape* shape, const bns_spec* spec, uint64_t seed, const void* x,
@@ -455,8 +466,9 @@ bns_status bns_backward_builtin_workspace(const bns_shape* shape, const bns_spec
     void* ws = nullptr;
     const bns_status ws_status = builtin_workspace(&ws);
     if (ws_status != BNS_OK) return ws_status;
+    // (no event between streams here: creating one allocates, and these calls are ordered by the caller anyway)
     return backward_impl(shape, spec, seed, x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta, ws,
-                         kBuiltinWorkspaceBytes, stream);
+                         kBuiltinWorkspaceBytes, stream, false);
 }
 
 // ---- "VDN + sampling", Eq. 4 ---------------------------------------------------------------
@@ -503,7 +515,7 @@ bns_status bns_forward_mixed(const bns_shape* shape, const bns_spec* spec, uint6
     if (nhwc(d)) {
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
         g_last_path_forward.store(1);
-        if (launch_nhwc_stats_mixed(d, ip_s.shared, n_v, x, static_cast<Partial*>(workspace), mix_beta, eps, momentum,
+        if (launch_nhwc_stats_mixed(d, ip_s.shared, n_v, x, partials_of(workspace), mix_beta, eps, momentum,
                                     save_mean, save_invstd, save_mean_parts, running_mean, running_var, st) != hipSuccess)
             return BNS_EDEVICE;
         return dev(launch_nhwc_normalize(d, x, gamma, beta, save_mean, save_invstd, y, st));
@@ -523,7 +535,7 @@ bns_status bns_forward_mixed(const bns_shape* shape, const bns_spec* spec, uint6
         mix.mix_beta = mix_beta;
         mix.mean_parts = save_mean_parts;
         const hipError_t fe = launch_fused(d, ip_s, false, io, eps, momentum,
-                                           static_cast<char*>(workspace) + 2 * partial_bytes(d), kSlotBytes, 0, d.C, st,
+                                           workspace, slots_of(workspace, d), kSlotBytes, 0, d.C, st,
                                            &mix);
         if (fe == hipSuccess) {
             g_last_path_forward.store(2);
@@ -534,8 +546,8 @@ bns_status bns_forward_mixed(const bns_shape* shape, const bns_spec* spec, uint6
     }
     g_last_path_forward.store(1);
     const IndexParams ip_v = make_index_params_virtual(*shape, n_v);
-    Partial* ws_s = static_cast<Partial*>(workspace);
-    Partial* ws_v = reinterpret_cast<Partial*>(static_cast<char*>(workspace) + partial_bytes(d));
+    Partial* ws_s = partials_of(workspace);
+    Partial* ws_v = reinterpret_cast<Partial*>(reinterpret_cast<char*>(partials_of(workspace)) + partial_bytes(d));
     const int splits_s = stats_splits(d, ip_s, d.C);
     const int splits_v = stats_splits(d, ip_v, d.C);
     if (launch_stats_partial(d, ip_s, x, ws_s, splits_s, 0, d.C, st) != hipSuccess) return BNS_EDEVICE;
@@ -565,7 +577,7 @@ bns_status bns_backward_mixed(const bns_shape* shape, const bns_spec* spec, uint
     if (nhwc(d)) {
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
         g_last_path_backward.store(1);
-        if (launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, static_cast<Partial*>(workspace), dgamma, dbeta, st) !=
+        if (launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, partials_of(workspace), dgamma, dbeta, st) !=
             hipSuccess)
             return BNS_EDEVICE;
         return dev(launch_nhwc_dx_mixed(d, ip_s.shared, n_v, mix_beta, x, dy, gamma, save_invstd, dgamma, dbeta,
@@ -585,7 +597,7 @@ bns_status bns_backward_mixed(const bns_shape* shape, const bns_spec* spec, uint
         mix.n_v = n_v;
         mix.mix_beta = mix_beta;
         mix.mean_parts = const_cast<float*>(save_mean_parts);
-        const hipError_t fe = launch_fused(d, ip_s, true, io, 0.f, 0.f, static_cast<char*>(workspace) + 2 * partial_bytes(d),
+        const hipError_t fe = launch_fused(d, ip_s, true, io, 0.f, 0.f, workspace, slots_of(workspace, d),
                                            kSlotBytes, 0, d.C, st, &mix);
         if (fe == hipSuccess) {
             g_last_path_backward.store(2);
@@ -595,7 +607,7 @@ bns_status bns_backward_mixed(const bns_shape* shape, const bns_spec* spec, uint
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
     }
     g_last_path_backward.store(1);
-    s = reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, static_cast<Partial*>(workspace), 0, d.C, st);
+    s = reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, partials_of(workspace), 0, d.C, st);
     if (s != BNS_OK) return s;
     const bns_box& b = ip_s.shared;
     DxSets sets;
@@ -605,6 +617,20 @@ bns_status bns_backward_mixed(const bns_shape* shape, const bns_spec* spec, uint
     sets.centre_v = save_mean_parts;
     sets.centre_s = save_mean_parts + d.C;
     return dev(launch_dx(d, ip_s, x, dy, gamma, save_mean, save_invstd, dgamma, dbeta, dx, 0, d.C, st, &sets));
+}
+
+bns_status bns_expired_waits(void* workspace, size_t workspace_bytes, void* stream, int32_t* expired) {
+    if (!expired) return BNS_EINVAL;
+    void* ws = workspace;
+    if (!ws) {                                              // the built-in scratch of bns_backward_builtin_workspace
+        const bns_status s = builtin_workspace(&ws);
+        if (s != BNS_OK) return s;
+    } else if (!aligned16(ws)) {
+        return BNS_EINVAL;
+    } else if (workspace_bytes < kHeaderBytes) {
+        return BNS_EWORKSPACE;
+    }
+    return dev(read_expired_waits(ws, static_cast<hipStream_t>(stream), expired));
 }
 
 float bns_moving_average_weight(uint64_t iteration, float alpha) { return iteration <= 1 ? 1.0f : alpha; }   // Eq. 8

@@ -32,6 +32,7 @@
 #include <mutex>
 
 #include "bns_device.hpp"
+#include "bns_fused_device.hpp"
 #include "bns_internal.hpp"
 
 namespace bns {
@@ -39,244 +40,6 @@ namespace bns {
 namespace {
 
 // ---------------------------------------------------------------------------------------
-// RawVec<T, V>: V storage elements as they sit in memory (kept packed in registers).
-// ---------------------------------------------------------------------------------------
-template <typename T, int V>
-struct RawVec;
-
-template <>
-struct RawVec<float, 1> {
-    typedef float raw_t;
-    static __device__ __forceinline__ raw_t ld(const float* p) { return __builtin_nontemporal_load(p); }
-    static __device__ __forceinline__ void st(float* p, raw_t r) { __builtin_nontemporal_store(r, p); }
-    static __device__ __forceinline__ void unpack(raw_t r, float* f) { f[0] = r; }
-    static __device__ __forceinline__ raw_t pack(const float* f) { return f[0]; }
-};
-template <>
-struct RawVec<float, 4> {
-    typedef float raw_t __attribute__((ext_vector_type(4)));
-    static __device__ __forceinline__ raw_t ld(const float* p) {
-        return __builtin_nontemporal_load(reinterpret_cast<const raw_t*>(p));
-    }
-    static __device__ __forceinline__ void st(float* p, raw_t r) {
-        __builtin_nontemporal_store(r, reinterpret_cast<raw_t*>(p));
-    }
-    static __device__ __forceinline__ void unpack(raw_t r, float* f) {
-        f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w;
-    }
-    static __device__ __forceinline__ raw_t pack(const float* f) { return raw_t{f[0], f[1], f[2], f[3]}; }
-};
-template <>
-struct RawVec<bf16_t, 1> {
-    typedef uint16_t raw_t;
-    static __device__ __forceinline__ raw_t ld(const bf16_t* p) { return p->bits; }
-    static __device__ __forceinline__ void st(bf16_t* p, raw_t r) { p->bits = r; }
-    static __device__ __forceinline__ void unpack(raw_t r, float* f) { f[0] = bf16_to_f32(r); }
-    static __device__ __forceinline__ raw_t pack(const float* f) { return uint16_t(f32_to_bf16(f[0])); }
-};
-template <>
-struct RawVec<bf16_t, 4> {
-    typedef uint32_t raw_t __attribute__((ext_vector_type(2)));
-    static __device__ __forceinline__ raw_t ld(const bf16_t* p) {
-        return __builtin_nontemporal_load(reinterpret_cast<const raw_t*>(p));
-    }
-    static __device__ __forceinline__ void st(bf16_t* p, raw_t r) {
-        __builtin_nontemporal_store(r, reinterpret_cast<raw_t*>(p));
-    }
-    static __device__ __forceinline__ void unpack(raw_t r, float* f) {
-        f[0] = bf16_to_f32(r.x & 0xFFFFu); f[1] = __uint_as_float(r.x & 0xFFFF0000u);
-        f[2] = bf16_to_f32(r.y & 0xFFFFu); f[3] = __uint_as_float(r.y & 0xFFFF0000u);
-    }
-    static __device__ __forceinline__ raw_t pack(const float* f) {
-        return raw_t{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3])};
-    }
-};
-template <>
-struct RawVec<bf16_t, 8> {
-    typedef uint32_t raw_t __attribute__((ext_vector_type(4)));
-    static __device__ __forceinline__ raw_t ld(const bf16_t* p) {
-        return __builtin_nontemporal_load(reinterpret_cast<const raw_t*>(p));
-    }
-    static __device__ __forceinline__ void st(bf16_t* p, raw_t r) {
-        __builtin_nontemporal_store(r, reinterpret_cast<raw_t*>(p));
-    }
-    static __device__ __forceinline__ void unpack(raw_t r, float* f) {
-        f[0] = bf16_to_f32(r.x & 0xFFFFu); f[1] = __uint_as_float(r.x & 0xFFFF0000u);
-        f[2] = bf16_to_f32(r.y & 0xFFFFu); f[3] = __uint_as_float(r.y & 0xFFFF0000u);
-        f[4] = bf16_to_f32(r.z & 0xFFFFu); f[5] = __uint_as_float(r.z & 0xFFFF0000u);
-        f[6] = bf16_to_f32(r.w & 0xFFFFu); f[7] = __uint_as_float(r.w & 0xFFFF0000u);
-    }
-    static __device__ __forceinline__ raw_t pack(const float* f) {
-        return raw_t{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
-                     pack_bf16x2(f[6], f[7])};
-    }
-};
-
-constexpr int kMaxTeam = 1024;            // members of a team (T)
-constexpr uint32_t kSpinLimit = 1u << 21; // polls before a missing team-mate is given up on (default)
-
-struct FusedArgs {
-    const void* x;
-    const void* dy;   // backward only
-    void* out;        // forward: y; backward: dx
-    const float* gamma;
-    const float* beta;
-    float* save_mean;     // forward: written; backward: read
-    float* save_invstd;
-    float* running_mean;
-    float* running_var;
-    float* dgamma;
-    float* dbeta;
-    unsigned long long* slots;  // [2][gridDim.x][2] words of {payload, stamp}
-    IndexParams ip;
-    FastDiv hwv_div, w_div;
-    int32_t C, W, HW;
-    int32_t c0, cg;
-    int32_t T, num_teams;
-    uint32_t tot;   // vectors per channel: N * HW / V
-    uint32_t s_cnt; // |S| per channel
-    // "VDN + sampling" (Eq. 4), the MIXED flavours: samples [0, n_v) are the virtual set, `ip` describes the
-    // sampled real set; mean_parts = [E_v per channel][E_s per channel] (forward: written; backward: read)
-    int32_t n_v;
-    float mix_beta, w_v, w_s;       // backward weights: mix_beta / s_v and (1 - mix_beta) / s_s
-    double s_v;                     // n_v * HW
-    float* mean_parts;
-    FastDiv patch_div, pw_div;   // h_cnt * w_cnt and w_cnt of S: sampled element q -> (n, ph, pw)
-    uint32_t stamp0;
-    uint32_t spin_limit;    // polls before a missing team-mate is given up on
-    int32_t mute;           // 1: members do not publish (host-forced give-up, for tests of that path)
-    float eps, momentum, inv_s;
-    double s;       // |S| per channel
-};
-
-// Block-wide sum of (a, b) over NT threads; result returned to every thread.
-template <int NT>
-__device__ __forceinline__ void block_allsum2(float& a, float& b, float* red) {
-    a = wave_sum(a);
-    b = wave_sum(b);
-    constexpr int nw = NT / kWave;
-    if (nw > 1) {
-        const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-        __syncthreads();                       // red[] may still be read from the previous use
-        if (lane == 0) {
-            red[wave] = a;
-            red[nw + wave] = b;
-        }
-        __syncthreads();
-        float sa = red[0], sb = red[nw];
-#pragma unroll
-        for (int w = 1; w < nw; ++w) {
-            sa += red[w];
-            sb += red[nw + w];
-        }
-        a = sa;
-        b = sb;
-    }
-}
-
-// All-gather of one (a, b) pair per team member, summed in member order in fp64, in two steps so
-// that a kernel can put independent work (prefetching the next channel) between them.
-// team_publish: thread 0 writes this member's stamped pair.
-__device__ __forceinline__ void team_publish(const FusedArgs& A, int team_first_block, int j, uint32_t it, float a,
-                                             float b) {
-    if (A.T == 1 || threadIdx.x != 0 || A.mute) return;
-    const uint32_t stamp = A.stamp0 + it;
-    unsigned long long* mine = A.slots + (size_t(it & 1u) * gridDim.x + size_t(team_first_block + j)) * 2;
-    __hip_atomic_store(mine, (static_cast<unsigned long long>(stamp) << 32) | __float_as_uint(a), __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(mine + 1, (static_cast<unsigned long long>(stamp) << 32) | __float_as_uint(b), __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// team_collect: waits for every member's pair and returns the team totals to every thread.
-template <int NT>
-__device__ __forceinline__ void team_collect(const FusedArgs& A, int team_first_block, uint32_t it, float a, float b,
-                                             double& ta, double& tb, float* team_lds, double* bc) {
-    if (A.T == 1) {
-        ta = double(a);
-        tb = double(b);
-        return;
-    }
-    const uint32_t stamp = A.stamp0 + it;
-    unsigned long long* base = A.slots + size_t(it & 1u) * gridDim.x * 2;
-    for (int t = threadIdx.x; t < A.T; t += NT) {
-        unsigned long long* theirs = base + size_t(team_first_block + t) * 2;
-        float pa = __builtin_nanf(""), pb = __builtin_nanf("");
-        for (uint32_t spin = 0; spin < A.spin_limit; ++spin) {
-            const unsigned long long wa = __hip_atomic_load(theirs, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const unsigned long long wb = __hip_atomic_load(theirs + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (uint32_t(wa >> 32) == stamp && uint32_t(wb >> 32) == stamp) {
-                pa = __uint_as_float(uint32_t(wa));
-                pb = __uint_as_float(uint32_t(wb));
-                break;
-            }
-            __builtin_amdgcn_s_sleep(2);
-        }
-        team_lds[t] = pa;
-        team_lds[kMaxTeam + t] = pb;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        double sa = 0.0, sb = 0.0;
-        for (int t = 0; t < A.T; ++t) {
-            sa += double(team_lds[t]);
-            sb += double(team_lds[kMaxTeam + t]);
-        }
-        bc[0] = sa;
-        bc[1] = sb;
-    }
-    __syncthreads();
-    ta = bc[0];
-    tb = bc[1];
-}
-
-template <int NT>
-__device__ __forceinline__ void team_allsum2(const FusedArgs& A, int team_first_block, int j, uint32_t it,
-                                             float a, float b, double& ta, double& tb, float* team_lds,
-                                             double* bc) {
-    team_publish(A, team_first_block, j, it, a, b);
-    team_collect<NT>(A, team_first_block, it, a, b, ta, tb, team_lds, bc);
-}
-
-// Returns v unchanged but opaque to the optimiser.  Each phase of a fused kernel derives its
-// addresses from its own opaque copy of the thread's first vector index, so that the compiler
-// recomputes them (a few integer operations) instead of keeping KMAX 64-bit addresses alive
-// across phases next to the KMAX data vectors.
-__device__ __forceinline__ uint32_t opaque(uint32_t v) {
-    asm volatile("" : "+v"(v));
-    return v;
-}
-
-// Same for a data vector: stops the compiler from keeping the unpacked (wider) form of a packed
-// bf16 vector alive from the reduction phase to the element-wise phase.
-template <typename R>
-__device__ __forceinline__ void opaque_raw(R& r) {
-    asm volatile("" : "+v"(r));
-}
-template <>
-__device__ __forceinline__ void opaque_raw<uint16_t>(uint16_t& r) {
-    uint32_t t = r;
-    asm volatile("" : "+v"(t));
-    r = uint16_t(t);
-}
-
-// Is element (h, w) of sample n inside the box?  Whole-vector shortcuts are taken by the callers.
-__device__ __forceinline__ bool in_hw(const bns_box& b, uint32_t h, uint32_t w) {
-    return h >= uint32_t(b.h0) && h < uint32_t(b.h0 + b.h_cnt) && w >= uint32_t(b.w0) && w < uint32_t(b.w0 + b.w_cnt);
-}
-
-// ---------------------------------------------------------------------------------------
-// sampled elements a thread reads ahead of its vectors (more: in a loop after them); registers decide how many
-constexpr int patch_loads(int kmax, bool mixed) { return (kmax >= 50 || (mixed && kmax >= 16)) ? 2 : 4; }
-
-// Offset of sampled element q of a channel from its first sampled element.
-__device__ __forceinline__ size_t patch_offset(const FusedArgs& A, uint32_t q, size_t nstride) {
-    const uint32_t n = fdiv(q, A.patch_div);
-    const uint32_t r = q - n * A.patch_div.d;
-    const uint32_t ph = fdiv(r, A.pw_div);
-    return n * nstride + size_t(ph) * A.W + (r - ph * A.pw_div.d);
-}
-
 // Forward: Eq. 3 + Eq. 8 + Eq. 1 with x read once
 // ---------------------------------------------------------------------------------------
 // PATCH: S is a patch of each plane (host guarantee: h_cnt * w_cnt < H * W); else S is whole planes.
@@ -288,6 +51,8 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
     __shared__ float red[2 * (NT / kWave)];
     __shared__ float team_lds[2 * kMaxTeam];
     __shared__ double bc[2];
+    __shared__ uint32_t words[3];                           // launch stamp, flags of the exchanges
+    const unsigned long long header_word = stamp_request(A);       // every block of the grid
     const int team = blockIdx.x / A.T;
     if (team >= A.num_teams) return;                       // blocks beyond the last whole team
     const int j = blockIdx.x - team * A.T;
@@ -387,9 +152,11 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
                 }
             }
         }
+        if (it == 0) stamp_accept(A, header_word, words);       // (the channel's loads have been issued)
         block_allsum2<NT>(s1, s2, red);
+        if (NT == kWave) __syncthreads();                       // (one wave: block_allsum2 has no barrier of its own)
         double t1, t2;
-        team_allsum2<NT>(A, team * A.T, j, MIXED ? 2u * it : it, s1, s2, t1, t2, team_lds, bc);
+        bool arrived = team_allsum2<NT>(A, words, team * A.T, j, MIXED ? 2u * it : it, s1, s2, t1, t2, team_lds, bc);
 
         // Eq. 3 (every thread computes the same values from the same totals)
         const double m1 = t1 / A.s;
@@ -400,7 +167,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
             __syncthreads();                                    // red[] is read by every thread of the first sum
             block_allsum2<NT>(v1, v2, red);
             double u1, u2;
-            team_allsum2<NT>(A, team * A.T, j, 2u * it + 1u, v1, v2, u1, u2, team_lds, bc);
+            arrived &= team_allsum2<NT>(A, words, team * A.T, j, 2u * it + 1u, v1, v2, u1, u2, team_lds, bc);
             const double mv = u1 / A.s_v;
             const double e_v = double(pivot_v) + mv;
             double var_v = u2 / A.s_v - mv * mv;
@@ -419,8 +186,9 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
             A.save_mean[c] = mu;
             A.save_invstd[c] = r;
             const double al = double(A.momentum);
-            if (A.running_mean) A.running_mean[c] = float((1.0 - al) * double(A.running_mean[c]) + al * mean);
-            if (A.running_var) A.running_var[c] = float((1.0 - al) * double(A.running_var[c]) + al * var);
+            // (a wait for a team-mate that ran out leaves NaN statistics; the moving averages then stay as they are)
+            if (A.running_mean && arrived) A.running_mean[c] = float((1.0 - al) * double(A.running_mean[c]) + al * mean);
+            if (A.running_var && arrived) A.running_var[c] = float((1.0 - al) * double(A.running_var[c]) + al * var);
         }
         const float sc = A.gamma[c] * r;
         const float sh = A.beta[c];
@@ -439,6 +207,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
             }
         }
     }
+    team_done(A, j, read_stamp(A, words));
 }
 
 // ---------------------------------------------------------------------------------------
@@ -454,6 +223,8 @@ __global__ __launch_bounds__(NT, (KEEPX && NT == 512 && KMAX <= 8) ? 4 : 1) void
     __shared__ float red[2 * (NT / kWave)];
     __shared__ float team_lds[2 * kMaxTeam];
     __shared__ double bc[2];
+    __shared__ uint32_t words[3];                           // launch stamp, flags of the exchanges
+    const unsigned long long header_word = stamp_request(A);
     const int team = blockIdx.x / A.T;
     if (team >= A.num_teams) return;
     const int j = blockIdx.x - team * A.T;
@@ -542,9 +313,11 @@ __global__ __launch_bounds__(NT, (KEEPX && NT == 512 && KMAX <= 8) ? 4 : 1) void
             }
         }
         }
+        if (it == 0) stamp_accept(A, header_word, words);
         block_allsum2<NT>(s1, s2, red);
+        if (NT == kWave) __syncthreads();
         double t1, t2;
-        team_allsum2<NT>(A, team * A.T, j, it, s1, s2, t1, t2, team_lds, bc);
+        team_allsum2<NT>(A, words, team * A.T, j, it, s1, s2, t1, t2, team_lds, bc);
 
         const float dbeta = float(t1);
         const float dgamma = float(t2 * double(r));
@@ -603,6 +376,7 @@ __global__ __launch_bounds__(NT, (KEEPX && NT == 512 && KMAX <= 8) ? 4 : 1) void
             }
         }
     }
+    team_done(A, j, read_stamp(A, words));
 }
 
 // ---------------------------------------------------------------------------------------
@@ -670,10 +444,15 @@ const void* kernel_for(const Dims& d, int kind, int variant) {
     return kernel_ptr<bf16_t, 1>(kind, variant);
 }
 
+constexpr int kMaxPipeVariants = 16;
 struct DeviceInfo {
     int cus = 0;
     int coop = 0;
     int blocks_per_cu[8][5][kNumVariants];  // [kernel kind][type/vec combo][variant], 0 = not queried yet
+    int pipe_blocks_per_cu[5][kMaxPipeVariants];
+    hipEvent_t chain_event = nullptr;       // orders launches whose blocks wait for each other across streams
+    hipStream_t chain_stream = nullptr;     // the stream the last such launch went to
+    bool chain_active = false;
 };
 DeviceInfo g_dev[16];
 std::mutex g_dev_mutex;   // guards g_dev: launches may come from several host threads
@@ -697,11 +476,32 @@ std::atomic<uint32_t> g_stamp{first_stamp()};
 
 }  // namespace
 
+// bns_fused_pipe.hip
+int pipe_variant_count();
+int pipe_default_variant(const Dims& d);
+int pipe_alternative_variant(const Dims& d);
+int pipe_max_team();
+const void* pipe_backward_kernel(const Dims& d, int variant, int* nt, int* k);
+
+hipError_t read_expired_waits(void* header, hipStream_t st, int32_t* expired) {
+    static_assert(sizeof(TeamHeader) <= kHeaderBytes, "the workspace header outgrew its place");
+    TeamHeader h;
+    hipError_t e = hipMemcpyAsync(&h, header, sizeof(TeamHeader), hipMemcpyDeviceToHost, st);
+    if (e != hipSuccess) return e;
+    if ((e = hipStreamSynchronize(st)) != hipSuccess) return e;
+    *expired = 0;
+    if ((h.state & kHeaderMask) != kHeaderMagic || h.expired == 0u) return hipSuccess;
+    *expired = h.expired > 0x7fffffffu ? 0x7fffffff : int32_t(h.expired);
+    e = hipMemsetAsync(&static_cast<TeamHeader*>(header)->expired, 0, sizeof(unsigned int), st);
+    if (e != hipSuccess) return e;
+    return hipStreamSynchronize(st);
+}
+
 // Plans and launches one fused pass over channels [c0, c0 + cg).  Returns hipErrorNotSupported
 // when the channel does not fit on chip (the caller then takes the streaming kernels).
 hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, const FusedIo& io, float eps,
-                        float momentum, void* slots, size_t slot_bytes, int c0, int cg, hipStream_t st,
-                        const FusedMix* mix) {
+                        float momentum, void* header, void* slots, size_t slot_bytes, int c0, int cg, hipStream_t st,
+                        const FusedMix* mix, bool order_streams) {
     int devid = 0;
     hipError_t e = hipGetDevice(&devid);
     if (e != hipSuccess) return e;
@@ -836,16 +636,97 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
                 kind &= ~2;
         }
     }
+    // Backward over several rounds: the pipelined kernel (bns_fused_pipe.hip), which holds the dy vectors of two
+    // channels per member so that loads stay in flight across the exchange, and parks x in LDS so that no mode
+    // reads anything twice.  "fused_pipe": 0 = whenever it applies, 1..n = that variant, 16 = never.
+    const void* pipe_kernel = nullptr;
+    int pipe_nt = 0, pipe_k = 0;
+    const bool pipe_forced = g_tuning.fused_pipe > 0 && g_tuning.fused_pipe <= pipe_variant_count();
+    const bool pipe_auto = g_tuning.fused_pipe == 0 && g_tuning.fused_variant == 0 && g_tuning.fused_keep_x == 0;
+    // (its per-vector byte offsets are 32-bit: tensors below 4 GiB)
+    const bool pipe_fits = uint64_t(d.N) * uint64_t(d.C) * uint64_t(d.HW) * (d.dtype == BNS_F32 ? 4u : 2u) < (uint64_t(1) << 32);
+    if (backward && !mix && pipe_fits && (pipe_forced || pipe_auto)) {
+        struct PipePlan {
+            const void* kernel = nullptr;
+            int nt = 0, k = 0;
+            long T = 0, rounds = 0, blocks = 0;
+            double cost = 0.0;
+        };
+        auto pipe_plan = [&](int pv, PipePlan* out) -> hipError_t {
+            out->kernel = nullptr;
+            int nt = 0, k = 0;
+            const void* kp = pipe_backward_kernel(d, pv, &nt, &k);
+            if (!kp) return hipSuccess;
+            int& bpc = di.pipe_blocks_per_cu[combo][pv];
+            if (bpc == 0) {
+                int nb = 0;
+                const hipError_t oe = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kp, nt, 0);
+                if (oe != hipSuccess) return oe;
+                bpc = nb > 0 ? nb : -1;
+            }
+            if (bpc < 0) return hipSuccess;
+            const long blocks = long(di.cus) * bpc;
+            const long chunks = long((tot + nt - 1) / nt);
+            const long Tmin = (chunks + k - 1) / k;
+            const long Tmax = blocks < pipe_max_team() ? blocks : pipe_max_team();
+            long bestT = 0, best_rounds = 0;
+            double best_cost = 0.0;
+            for (long T = Tmin; T <= 2 * Tmin && T <= Tmax; ++T) {
+                const long teams = blocks / T < cg ? blocks / T : cg;
+                const long rounds = (cg + teams - 1) / teams;
+                // a round lasts as long as its busiest member's share (whole chunks) plus the exchange
+                const double cost = double(rounds) * (double((chunks + T - 1) / T) + 2.0) * double(nt);
+                if (bestT == 0 || cost < best_cost) {
+                    bestT = T;
+                    best_cost = cost;
+                    best_rounds = rounds;
+                }
+            }
+            if (g_tuning.fused_team > 0 && g_tuning.fused_team >= Tmin && g_tuning.fused_team <= Tmax)
+                bestT = g_tuning.fused_team;
+            if (bestT == 0) return hipSuccess;
+            out->kernel = kp;
+            out->nt = nt;
+            out->k = k;
+            out->T = bestT;
+            out->rounds = best_rounds;
+            out->blocks = blocks;
+            out->cost = best_cost;
+            return hipSuccess;
+        };
+        PipePlan pp;
+        if (pipe_forced) {
+            if ((e = pipe_plan(g_tuning.fused_pipe - 1, &pp)) != hipSuccess) return e;
+        } else {
+            // 512 or 448 threads, whichever cuts the channel into shares with less padding.  Measured at
+            // 64x256x56x56 (fp32, 8 rounds): 115-117 us for every mode against 127-130 for the plain kernels; bf16
+            // (6 rounds) 63-64 against 66 (Batch Sampling) and 71 (full BN).  With two rounds (128x64x32x32,
+            // 130x128x28x28) the plain kernels are faster, and so they are for a patch of every plane in bf16, where
+            // most vectors of 8 elements need the element-by-element test (70 against 68 us).
+            const bns_box& sb = ip.shared;
+            const bool patch_bf16 = d.vec == 8 && (ip.per_channel || sb.w_cnt != d.W || sb.w0 != 0);
+            PipePlan alt;
+            if ((e = pipe_plan(pipe_default_variant(d), &pp)) != hipSuccess) return e;
+            if (pipe_alternative_variant(d) >= 0) {
+                if ((e = pipe_plan(pipe_alternative_variant(d), &alt)) != hipSuccess) return e;
+                if (alt.kernel && (!pp.kernel || alt.cost < pp.cost)) pp = alt;
+            }
+            if (pp.kernel && (pp.rounds < 3 || patch_bf16)) pp.kernel = nullptr;
+        }
+        if (pp.kernel) {
+            pipe_kernel = pp.kernel;
+            pipe_nt = pp.nt;
+            pipe_k = pp.k;
+            kind = 1;
+            chosen.v = 0;
+            chosen.T = int(pp.T);
+            chosen.blocks = int(pp.blocks);
+        }
+    }
     if (chosen.v < 0) return hipErrorNotSupported;
     const int best = chosen.v, bestT = chosen.T, best_blocks = chosen.blocks;
-
-    // The exchange stamps are drawn on the host, so a captured launch would replay the same stamps
-    // and a team could pick up its previous replay's sums.  Single-member teams exchange nothing.
-    if (bestT > 1) {
-        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-        if (hipStreamIsCapturing(st, &cap) != hipSuccess) return hipErrorNotSupported;
-        if (cap != hipStreamCaptureStatusNone) return hipErrorNotSupported;
-    }
+    const int launch_nt = pipe_kernel ? pipe_nt : kVariants[best].nt;
+    const int launch_k = pipe_kernel ? pipe_k : kVariants[best].kmax;
 
     FusedArgs A;
     A.x = io.x;
@@ -859,10 +740,12 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     A.running_var = io.running_var;
     A.dgamma = io.dgamma;
     A.dbeta = io.dbeta;
+    A.hdr = static_cast<TeamHeader*>(header);
     A.slots = static_cast<unsigned long long*>(slots);
     A.ip = ip;
     A.hwv_div = make_fastdiv(hwv);
     A.w_div = make_fastdiv(uint32_t(d.W));
+    A.chw_div = make_fastdiv(uint32_t(d.C) * uint32_t(d.HW));       // C * HW < 2^31 (limits of bns_shape)
     A.C = d.C;
     A.W = d.W;
     A.HW = d.HW;
@@ -873,7 +756,8 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     if (A.num_teams > cg) A.num_teams = cg;
     A.tot = tot;
     const uint32_t rounds = uint32_t((cg + A.num_teams - 1) / A.num_teams);
-    A.stamp0 = g_stamp.fetch_add((mix ? 2u : 1u) * rounds + 1u);   // Eq. 4 forward exchanges twice per round
+    A.stamp_advance = (mix ? 2u : 1u) * rounds + 1u;               // Eq. 4 forward exchanges twice per round
+    A.stamp_seed = g_stamp.fetch_add(1u);
     A.spin_limit = g_tuning.fused_spin_limit > 0 ? uint32_t(g_tuning.fused_spin_limit) : kSpinLimit;
     A.mute = g_tuning.fused_mute;
     A.eps = eps;
@@ -900,14 +784,40 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     const int grid = A.num_teams * bestT;
     if (size_t(grid) * 2 * 2 * sizeof(unsigned long long) > slot_bytes) return hipErrorNotSupported;
     {
-        const uint64_t chunks = (uint64_t(tot) + kVariants[best].nt - 1) / kVariants[best].nt;
-        if ((chunks + bestT - 1) / bestT > uint64_t(kVariants[best].kmax)) return hipErrorNotSupported;
+        const uint64_t chunks = (uint64_t(tot) + launch_nt - 1) / launch_nt;
+        if ((chunks + bestT - 1) / bestT > uint64_t(launch_k)) return hipErrorNotSupported;
     }
+    const void* kernel = pipe_kernel ? pipe_kernel : kernel_for(d, kind, best);
     void* params[] = {&A};
-    if (g_tuning.fused_coop)
-        return hipLaunchCooperativeKernel(kernel_for(d, kind, best), dim3(grid), dim3(kVariants[best].nt), params,
-                                          0, st);
-    return hipLaunchKernel(kernel_for(d, kind, best), dim3(grid), dim3(kVariants[best].nt), params, 0, st);
+
+    // Kernels whose blocks wait for each other must not share the device with one another: two of them, each with
+    // part of its grid resident, would wait for blocks that the other keeps out.  Within a process they are therefore
+    // chained across streams: when such a launch goes to another stream than the one before it, an event is
+    // recorded on that earlier stream (behind the earlier launch) and the new stream waits for it.  A caller that
+    // stays on one stream pays nothing.  Not while a stream is being captured (the event would belong to the
+    // graph); a graph that holds such launches must not run beside other calls.
+    bool chain = false;
+    if (bestT > 1 && order_streams) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        chain = hipStreamIsCapturing(st, &cap) == hipSuccess && cap == hipStreamCaptureStatusNone;
+        (void)hipGetLastError();
+    }
+    if (chain && di.chain_active && di.chain_stream != st) {
+        if (!di.chain_event && hipEventCreateWithFlags(&di.chain_event, hipEventDisableTiming) != hipSuccess)
+            di.chain_event = nullptr;
+        // (an earlier stream that has been destroyed meanwhile refuses the record: nothing is left to wait for)
+        if (di.chain_event && hipEventRecord(di.chain_event, di.chain_stream) == hipSuccess &&
+            (e = hipStreamWaitEvent(st, di.chain_event, 0)) != hipSuccess)
+            return e;
+        (void)hipGetLastError();
+    }
+    e = g_tuning.fused_coop ? hipLaunchCooperativeKernel(kernel, dim3(grid), dim3(launch_nt), params, 0, st)
+                            : hipLaunchKernel(kernel, dim3(grid), dim3(launch_nt), params, 0, st);
+    if (e == hipSuccess && chain) {
+        di.chain_active = true;
+        di.chain_stream = st;
+    }
+    return e;
 }
 
 }  // namespace bns

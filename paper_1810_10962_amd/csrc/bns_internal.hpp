@@ -42,6 +42,8 @@ struct Tuning {
                                             // 1: streaming kernels only; 2: fused only (error if it cannot)
     int fused_variant = 0;                  // 1..7 forces a (block size, registers) variant of the fused kernels
     int fused_keep_x = 0;                   // backward keeps x in registers next to dy: 1 always, 2 never, 0 when it pays
+    int fused_pipe = 0;                     // backward: 1..n forces variant n of the pipelined kernel, 16: never
+    int fused_team = 0;                     // blocks per team of the pipelined kernel, if the channel fits (0: planner)
     int fused_coop = 0;                     // 1: launch the fused kernels with hipLaunchCooperativeKernel
     int fused_spin_limit = 0;               // polls a team member waits for a team-mate before giving up (default 2^21)
     int fused_mute = 0;                     // 1 (tests of the give-up path): no member publishes its sums
@@ -117,6 +119,7 @@ struct FusedIo {
     float* dbeta = nullptr;
 };
 constexpr size_t kSlotBytes = 256 * 1024;   // stamped exchange slots of the fused kernels
+constexpr size_t kHeaderBytes = 256;        // in front of everything else in a workspace
 // hipErrorNotSupported: the channel does not fit on chip (take the streaming kernels instead).
 // mix != nullptr: "VDN + sampling" (Eq. 4); `ip` then describes the sampled real set.
 struct FusedMix {
@@ -124,9 +127,13 @@ struct FusedMix {
     float mix_beta = 0.f;
     float* mean_parts = nullptr;     // [E_v per channel][E_s per channel]: forward writes, backward reads
 };
+// header: the first kHeaderBytes of the workspace (launch counter, count of waits that ran out).
+// order_streams: chain launches whose blocks wait for each other across streams with an event (see there).
 hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, const FusedIo& io, float eps,
-                        float momentum, void* slots, size_t slot_bytes, int c0, int cg, hipStream_t st,
-                        const FusedMix* mix = nullptr);
+                        float momentum, void* header, void* slots, size_t slot_bytes, int c0, int cg, hipStream_t st,
+                        const FusedMix* mix = nullptr, bool order_streams = true);
+// Reads the count of waits that ran out from a workspace header (0 if the header was never set up) and clears it.
+hipError_t read_expired_waits(void* header, hipStream_t st, int32_t* expired);
 
 hipError_t launch_index_boxes(const IndexParams& ip, int C, bns_box* boxes, hipStream_t st);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);

@@ -144,9 +144,20 @@ def test_builtin_workspace_call_validates_before_it_touches_a_device():
     assert call(dy=dy + 4) == bns.BNS_EINVAL and call(dx=dy) == bns.BNS_EINVAL
     assert call(spec=bns.make_spec(bns.BNS_BS, 9)) == bns.BNS_EINVAL
     big = bns.make_shape(2, 3841, 2, 2)
-    assert bns.bns_workspace_bytes(big, spec) > 4 << 20
+    limit = (4 << 20) + 256                                        # 4 MiB and the workspace header
+    assert bns.bns_workspace_bytes(big, spec) > limit
     assert call(shape=big, x=0x1000000, dy=0x2000000, dx=0x3000000) == bns.BNS_EWORKSPACE
-    assert bns.bns_workspace_bytes(bns.make_shape(2, 3840, 2, 2), spec) <= 4 << 20
+    assert bns.bns_workspace_bytes(bns.make_shape(2, 3840, 2, 2), spec) <= limit
+
+
+def test_expired_waits_query_validates_on_the_host():
+    lib = bns.load()
+    out = C.c_int32(7)
+    P = lambda a: C.c_void_p(a)
+    assert lib.bns_expired_waits(P(0x10000), 4096, None, None) == bns.BNS_EINVAL          # nowhere to write the count
+    assert lib.bns_expired_waits(P(0x10004), 4096, None, C.byref(out)) == bns.BNS_EINVAL  # misaligned
+    assert lib.bns_expired_waits(P(0x10000), 255, None, C.byref(out)) == bns.BNS_EWORKSPACE
+    assert out.value == 7
 
 
 def test_mixed_index_and_argument_checks():

@@ -39,6 +39,7 @@ def _one_call(wl):
     for name in ("dx", "dgamma", "dbeta"):
         assert np.array_equal(got[name], want[name]), f"{wl.name} {name}: differs from bns_backward"
     assert_parity(got, oracle_reference(wl, inp), wl, what=wl.name, inp=inp)
+    assert bns.bns_expired_waits(None, stream_of=b.x) == 0        # the count kept in the built-in scratch
 
 
 @pytest.mark.parametrize("path", [0, 1], ids=["auto", "streaming"])
@@ -54,10 +55,10 @@ def test_builtin_workspace_matches_bns_backward_twice_in_a_row(case, path):
 
 
 def test_builtin_workspace_rejects_what_does_not_fit():
-    # 4 MiB hold the partial sums of at most 3840 channels (N x C x H x W); nothing is launched
+    # the built-in scratch holds the workspace of at most 3840 channels (N x C x H x W); nothing is launched
     shape = bns.make_shape(2, 5000, 2, 2)
     spec = bns.make_spec(BS, 1)
-    assert bns.bns_workspace_bytes(shape, spec) > 4 << 20
+    assert bns.bns_workspace_bytes(shape, spec) > (4 << 20) + 256
     t = torch.zeros(2 * 5000 * 2 * 2, device="cuda")
     v = torch.zeros(5000, device="cuda")
     with pytest.raises(bns.BnsError) as e:
