@@ -29,31 +29,30 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published peak
 METRIC = "BN fwd+bwd effective HBM GB/s (% peak) and speedup vs full BN, 64x256x56x56"
 
-# HBM traffic of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-# scaled by what the same counters read for bns_copy_reference of known size; bytes per launch.
-# Filled from profiles/ (see there for the commands); None where no counter run exists.
-MEASURED_TRAFFIC = {
-    # profiles/imagenet_bs_f32_hbm_traffic.md
-    ("imagenet_bs", "bwd"): 642812082,          # fused_backward_kernel
-    ("imagenet_bs", "normalize"): 411248852,
-    ("imagenet_bs", "dx"): 436968405,
-    ("imagenet_bs", "reduce"): 411114431,
-    # profiles/imagenet_bs_nhwc_f32_hbm_traffic.md
-    ("imagenet_bs_nhwc", "normalize"): 411111929,
-    ("imagenet_bs_nhwc", "dx"): 436805623,
-    ("imagenet_bs_nhwc", "reduce"): 412120265,
-    # profiles/imagenet_bs_bf16_hbm_traffic.md
-    ("imagenet_bs_bf16", "bwd"): 321698909,     # fused_backward_kernel
-    ("imagenet_bs_bf16", "fwd"): 206160664,     # fused_forward_kernel
-    ("imagenet_bs_bf16", "normalize"): 205590313,
-    ("imagenet_bs_bf16", "dx"): 218472118,
-    ("imagenet_bs_bf16", "reduce"): 205601072,
-    # profiles/feature_sampling_f32_hbm_traffic.md
-    ("imagenet_fs", "bwd"): 618586743,          # fused_backward_kernel, x kept on chip
-    ("imagenet_fs", "normalize"): 411222742,
-    ("imagenet_fs", "dx"): 463525848,
-    ("imagenet_fs", "reduce"): 411114419,
-}
+# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by what the same counters
+# read for bns_copy_reference of known size: profiles/hbm_traffic.json (the summaries beside it give the commands).
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def load_traffic():
+    try:
+        with open(TRAFFIC_FILE) as f:
+            return json.load(f)
+    except (OSError, ValueError):
+        return {"bytes_per_launch": {}, "measured_at_commit": None}
+
+
+def default_path_kernels(wl, dirs, bns):
+    """Names of the kernels one default forward + backward launches for this workload (as in the counter table)."""
+    pre = "nhwc_" if wl.layout == "nhwc" else ""
+    fwd = {"fused": ["fused_forward_kernel"], "one-launch": [pre + "small_forward_kernel"],
+           "streaming": ([pre + "stats_partial_kernel", pre + "stats_finalize_kernel"] if wl.layout == "nhwc" else
+                         ["stats_one_block_kernel"]) + [pre + "normalize_kernel"]}[dirs["forward_path"]]
+    fused_bwd = {1: "fused_backward_kernel", 2: "fused_backward_kernel", 3: "fused_backward_pipe_kernel"}
+    bwd = {"fused": [fused_bwd.get(bns.bns_get_option("last_fused_backward"), "fused_backward_kernel")],
+           "one-launch": [pre + "small_backward_kernel"],
+           "streaming": [pre + "reduce_partial_kernel", pre + "reduce_finalize_kernel", pre + "dx_kernel"]}[dirs["backward_path"]]
+    return fwd, bwd
 
 
 def sampling_ratio(wl, boxes) -> float:
@@ -155,12 +154,19 @@ def time_directions(ds, steps, torch, bns):
         e[2].record()
     torch.cuda.synchronize()
     paths = {1: "streaming", 2: "fused", 3: "one-launch"}
+    c0 = bns.bns_get_option("launch_count")
+    ds.bufs[0].forward()
+    c1 = bns.bns_get_option("launch_count")
+    ds.bufs[0].backward()
+    c2 = bns.bns_get_option("launch_count")
+    torch.cuda.synchronize()
+    launches = ((c1 - c0) % (1 << 31), (c2 - c1) % (1 << 31))
     fwd = np.array([e[0].elapsed_time(e[1]) for e in evs]) * 1e-3
     bwd = np.array([e[1].elapsed_time(e[2]) for e in evs]) * 1e-3
     both = fwd + bwd
     stat = lambda a: {"mean": round(float(a.mean()) * 1e6, 2), "median": round(float(np.median(a)) * 1e6, 2),
                       "min": round(float(a.min()) * 1e6, 2)}
-    return dict(forward=float(fwd.mean()), backward=float(bwd.mean()),
+    return dict(forward=float(fwd.mean()), backward=float(bwd.mean()), launches=launches,
                 spread_us={"forward": stat(fwd), "backward": stat(bwd), "forward+backward": stat(both)},
                 forward_path=paths.get(bns.bns_get_option("last_path_forward"), "?"),
                 backward_path=paths.get(bns.bns_get_option("last_path_backward"), "?"))
@@ -280,24 +286,36 @@ def main():
     # byte model (reduction + element-wise pass); a streaming direction is several kernels, of which
     # the longest single-kernel stage is taken (the statistics and reduce stages also contain a
     # one-block finalize kernel, so their event pair covers two launches).
+    traffic_table = load_traffic()
+    table = traffic_table.get("bytes_per_launch", {}).get(wl.name, {})
+    fwd_kernels, bwd_kernels = default_path_kernels(wl, dirs, bns)
     cands = []
     if dirs["backward_path"] == "fused":
-        cands.append(("fused_backward_kernel", dirs["backward"], alg["reduce"] + alg["dx"], "bwd"))
+        cands.append((bwd_kernels[0], dirs["backward"], alg["reduce"] + alg["dx"]))
     else:
-        cands += [("reduce_partial_kernel", stages["reduce"], alg["reduce"], "reduce"),
-                  ("dx_kernel", stages["dx"], alg["dx"], "dx")]
+        cands += [(bwd_kernels[0], stages["reduce"], alg["reduce"]), (bwd_kernels[-1], stages["dx"], alg["dx"])]
     if dirs["forward_path"] == "fused":
-        cands.append(("fused_forward_kernel", dirs["forward"], alg["stats"] + alg["normalize"], "fwd"))
+        cands.append((fwd_kernels[0], dirs["forward"], alg["stats"] + alg["normalize"]))
     else:
-        cands.append(("normalize_kernel", stages["normalize"], alg["normalize"], "normalize"))
-    kernel_name, dom_s, dom_bytes, dom_key = max(cands, key=lambda c: c[1])
-    if wl.layout == "nhwc":
-        kernel_name = "nhwc_" + kernel_name
+        cands.append((fwd_kernels[-1], stages["normalize"], alg["normalize"]))
+    kernel_name, dom_s, dom_bytes = max(cands, key=lambda c: c[1])
     achieved = dom_bytes / dom_s / 1e9
+    traffic = table.get(kernel_name)
+    e_bytes = 4 if wl.dtype == "f32" else 2
     roofline = dict(bound="hbm", kernel=kernel_name, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=MEASURED_TRAFFIC.get((wl.name, dom_key)),
-                    algorithmic_bytes_per_launch=int(dom_bytes), avg_launch_us=round(dom_s * 1e6, 2),
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic,
+                    achieved_by_counters=round(traffic / dom_s / 1e9, 1) if traffic else None,
+                    frac_by_counters=round(traffic / dom_s / 1e9 / HBM_PEAK_GBS, 4) if traffic else None,
+                    stale=traffic is None, counters_measured_at_commit=traffic_table.get("measured_at_commit"),
+                    algorithmic_bytes_per_launch=int(dom_bytes),
+                    algorithmic_bytes_note="two-pass byte model (reductions 2e + dx (2+r)e per element); the single-launch "
+                                           "kernel keeps the channel on chip and has to move 3e = %d bytes" % (3 * e_bytes * wl.elements)
+                    if kernel_name.startswith("fused_backward") else "byte model of this stage",
+                    avg_launch_us=round(dom_s * 1e6, 2),
                     timing="HIP events on the launch stream around the call, mean over the timed steps")
+    # the whole default step by the counters: what forward + backward really moved through HBM
+    step_kernels = fwd_kernels + bwd_kernels
+    measured_step = sum(table[k] for k in step_kernels) if all(k in table for k in step_kernels) else None
 
     out = {
         "metric": METRIC, "value": round(alg["fwd+bwd"] / sec / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": K,
@@ -310,9 +328,16 @@ def main():
         "pct_of_hbm_peak": round(100 * alg["fwd+bwd"] / sec / 1e9 / HBM_PEAK_GBS, 2),
         "elements_per_s": round(wl.elements / sec, 1),
         "algorithmic_bytes_per_step": int(alg["fwd+bwd"]),
+        "hbm_bytes_measured_per_step": measured_step,
+        "measured_hbm_GBs": round(measured_step / sec / 1e9, 1) if measured_step else None,
+        "measured_pct_of_peak": round(100 * measured_step / sec / 1e9 / HBM_PEAK_GBS, 2) if measured_step else None,
+        "measured_note": "FETCH_SIZE + WRITE_SIZE of the default path's kernels (profiles/hbm_traffic.json) over the time "
+                         "per step; `value` counts the bytes of the two-pass byte model instead, which the single-launch "
+                         "backward kernel undercuts by keeping a channel on chip",
         "warm": {"us_per_step": round(warm_sec * 1e6, 2), "GBs": round(alg["fwd+bwd"] / warm_sec / 1e9, 1),
                  "note": "one buffer set reused every step (value and ms_per_step rotate over buffer_sets_rotated sets)"},
         "default_path": {"forward": dirs["forward_path"], "backward": dirs["backward_path"],
+                         "kernels": step_kernels, "launches": {"forward": dirs["launches"][0], "backward": dirs["launches"][1]},
                          "forward_us": round(dirs["forward"] * 1e6, 2), "backward_us": round(dirs["backward"] * 1e6, 2),
                          "event_pairs_us": dirs["spread_us"]},
         "streaming_stages_us": {k: round(v * 1e6, 2) for k, v in stages.items()},
@@ -388,6 +413,35 @@ def main():
             out["speedup_vs_full_bn_streaming_kernels"] = variants[wl.name].get("speedup_vs_full_bn_streaming_kernels")
             out["forward_speedup_vs_full_bn_streaming_kernels"] = variants[wl.name][
                 "forward_speedup_vs_full_bn_streaming_kernels"]
+        # planes four times as large (the first-stage maps of the ImageNet models, Table 1): same element count
+        big = {}
+        big_inputs = None
+        for name in ("stage1_bs", "stage1_fs", "stage1_full"):
+            v = workloads.WORKLOADS[name]
+            big_inputs = workloads.make_inputs(v) if big_inputs is None else big_inputs
+            vds = DeviceSet(v, big_inputs, 2, torch, bns)
+            vr = sampling_ratio(v, bns.bns_sample_index(vds.bufs[0].shape, vds.bufs[0].spec, v.sampling_seed))
+            vsec = time_steps(vds, max(K // 2, 10), max(W // 2, 5), torch)
+            vd = time_directions(vds, max(K // 2, 10), torch, bns)
+            bns.bns_set_option("path", 1)
+            try:
+                ssec = time_steps(vds, max(K // 2, 10), max(W // 2, 5), torch)
+            finally:
+                bns.bns_set_option("path", 0)
+            va = algorithmic_bytes(v, vr)["fwd+bwd"]
+            big[name] = dict(shape="x".join(map(str, v.shape)), label=v.label(), ratio=round(vr, 4),
+                             us_per_step=round(vsec * 1e6, 2), streaming_us=round(ssec * 1e6, 2),
+                             forward_us=round(vd["forward"] * 1e6, 2), backward_us=round(vd["backward"] * 1e6, 2),
+                             paths=f'{vd["forward_path"]}/{vd["backward_path"]}', effective_GBs=round(va / vsec / 1e9, 1),
+                             ideal_speedup_two_pass_model=round(32.0 / (24.0 + 8.0 * vr), 4))
+            del vds
+            torch.cuda.empty_cache()
+        for name, v in big.items():
+            v["speedup_vs_full_bn"] = round(big["stage1_full"]["us_per_step"] / v["us_per_step"], 4)
+            v["speedup_vs_full_bn_streaming_kernels"] = round(big["stage1_full"]["streaming_us"] / v["streaming_us"], 4)
+            v["forward_speedup_vs_full_bn"] = round(big["stage1_full"]["forward_us"] / v["forward_us"], 4)
+        out["large_plane_variants"] = big
+        del big_inputs
         others = {}
         for name in ("tiny_bs", "cifar_fs", "vdn", "vdn_fs_mix", "vdn_bs_mix", "micro_a_fs", "micro_a_full", "micro_b_fs",
                      "micro_b_full"):
@@ -402,8 +456,14 @@ def main():
                 vr = sampling_ratio(v, bns.bns_sample_index(vds.bufs[0].shape, vds.bufs[0].spec, v.sampling_seed))
             vsec = time_steps(vds, K, W, torch)
             va = algorithmic_bytes(v, vr)["fwd+bwd"]
+            vd = time_directions(vds, K, torch, bns)
             others[name] = dict(shape="x".join(map(str, v.shape)), label=v.label(), us_per_step=round(vsec * 1e6, 2),
-                                effective_GBs=round(va / vsec / 1e9, 1), elements_per_s=round(v.elements / vsec, 1))
+                                effective_GBs=round(va / vsec / 1e9, 1), elements_per_s=round(v.elements / vsec, 1),
+                                # device side: event pairs around the two calls (kernels and the gap between them), and
+                                # how many kernels they launch; us_per_step above also holds the host's call overhead
+                                device_us=round((vd["forward"] + vd["backward"]) * 1e6, 2),
+                                launches_per_step=vd["launches"][0] + vd["launches"][1],
+                                paths=f'{vd["forward_path"]}/{vd["backward_path"]}')
             del vds
             torch.cuda.empty_cache()
         out["other_configs"] = others

@@ -307,7 +307,9 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
 bns_status bns_set_option(const char* name, int32_t value);
 /* Current value of an option (as set, 0 = automatic); also "last_path_forward" / "last_path_backward":
  * 1 if the last bns_forward / bns_backward took the streaming kernels, 2 if the fused one, 3 if the
- * one-launch kernel for small N x H x W x C tensors.
+ * one-launch kernel for small N x H x W x C tensors; "last_fused_backward": which fused backward kernel that was
+ * (1 plain, 2 x kept in registers, 3 pipelined); "launch_count": kernels launched by the library since it was
+ * loaded, modulo 2^31 (benchmarks report launches per call from its differences).
  * -1 for an unknown name. */
 int32_t bns_get_option(const char* name);
 

@@ -11,6 +11,9 @@
 
 using namespace bns;
 
+std::atomic<uint32_t> bns::g_launch_count{0};
+std::atomic<int32_t> bns::g_last_fused_backward{0};
+
 // Built-in scratch memory of bns_backward_builtin_workspace (see there).
 constexpr size_t kBuiltinWorkspaceBytes = (size_t(4) << 20) + bns::kHeaderBytes;    // 3840 channels
 static __device__ __align__(256) unsigned char scratch[kBuiltinWorkspaceBytes];
@@ -669,6 +672,8 @@ int32_t bns_get_option(const char* name) {
     if (!strcmp(name, "channel_group")) return g_channel_group.load();
     if (!strcmp(name, "last_path_forward")) return g_last_path_forward.load();
     if (!strcmp(name, "last_path_backward")) return g_last_path_backward.load();
+    if (!strcmp(name, "last_fused_backward")) return g_last_fused_backward.load();
+    if (!strcmp(name, "launch_count")) return int32_t(g_launch_count.load() & 0x7fffffffu);
     for (const TuningEntry& t : kTuningTable)
         if (!strcmp(name, t.name)) {
             const int v = g_tuning.*(t.field) + t.bias;         // as it was set; 0 = automatic

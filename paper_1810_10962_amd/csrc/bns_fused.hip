@@ -52,7 +52,6 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
     __shared__ float team_lds[2 * kMaxTeam];
     __shared__ double bc[2];
     __shared__ uint32_t words[3];                           // launch stamp, flags of the exchanges
-    const unsigned long long header_word = stamp_request(A);       // every block of the grid
     const int team = blockIdx.x / A.T;
     if (team >= A.num_teams) return;                       // blocks beyond the last whole team
     const int j = blockIdx.x - team * A.T;
@@ -65,6 +64,13 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
     const size_t nstride = size_t(A.C) * A.HW;
     const T* x = static_cast<const T*>(A.x);
     T* y = static_cast<T*>(A.out);
+
+    // The launch stamp (every block of the grid reads the workspace header once): behind the first channel's loads,
+    // where the round trip costs nothing -- except in the variants that fill the register file with that channel,
+    // which take it first (they run with one or few blocks per channel, where a microsecond at the start is cheap
+    // and spilled registers are not).
+    constexpr bool kStampFirst = KMAX >= 32;
+    if (kStampFirst) stamp_accept(A, stamp_request(A), words);
 
     uint32_t it = 0;
     for (int cl = team; cl < A.cg; cl += A.num_teams, ++it) {
@@ -127,10 +133,21 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
                 s1 += d;
                 s2 = fmaf(d, d, s2);
             }
-            for (uint32_t q = q0 + uint32_t(kPatchLoads) * step; q < A.s_cnt; q += step) {
-                const float d = load_scalar<T>(first + patch_offset(A, q, nstride)) - pivot;
-                s1 += d;
-                s2 = fmaf(d, d, s2);
+            // what is left of the patch (most of it when one block holds the channel), a few loads in flight at a time
+            constexpr int kBatch = KMAX >= 50 ? 2 : KMAX >= 32 ? 4 : 8;      // (registers)
+            for (uint32_t q = q0 + uint32_t(kPatchLoads) * step; q < A.s_cnt; q += uint32_t(kBatch) * step) {
+                float t[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const uint32_t qu = q + uint32_t(u) * step;
+                    t[u] = qu < A.s_cnt ? load_scalar<T>(first + patch_offset(A, qu, nstride)) : pivot;
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const float d = t[u] - pivot;
+                    s1 += d;
+                    s2 = fmaf(d, d, s2);
+                }
             }
         }
         float v1 = 0.f, v2 = 0.f, pivot_v = 0.f;
@@ -152,7 +169,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
                 }
             }
         }
-        if (it == 0) stamp_accept(A, header_word, words);       // (the channel's loads have been issued)
+        if (!kStampFirst && it == 0) stamp_accept(A, stamp_request(A), words);
         block_allsum2<NT>(s1, s2, red);
         if (NT == kWave) __syncthreads();                       // (one wave: block_allsum2 has no barrier of its own)
         double t1, t2;
@@ -224,7 +241,6 @@ __global__ __launch_bounds__(NT, (KEEPX && NT == 512 && KMAX <= 8) ? 4 : 1) void
     __shared__ float team_lds[2 * kMaxTeam];
     __shared__ double bc[2];
     __shared__ uint32_t words[3];                           // launch stamp, flags of the exchanges
-    const unsigned long long header_word = stamp_request(A);
     const int team = blockIdx.x / A.T;
     if (team >= A.num_teams) return;
     const int j = blockIdx.x - team * A.T;
@@ -236,6 +252,9 @@ __global__ __launch_bounds__(NT, (KEEPX && NT == 512 && KMAX <= 8) ? 4 : 1) void
     const T* x = static_cast<const T*>(A.x);
     const T* dy = static_cast<const T*>(A.dy);
     T* dx = static_cast<T*>(A.out);
+
+    constexpr bool kStampFirst = KMAX >= 32;               // as in the forward kernel
+    if (kStampFirst) stamp_accept(A, stamp_request(A), words);
 
     uint32_t it = 0;
     for (int cl = team; cl < A.cg; cl += A.num_teams, ++it) {
@@ -313,7 +332,7 @@ __global__ __launch_bounds__(NT, (KEEPX && NT == 512 && KMAX <= 8) ? 4 : 1) void
             }
         }
         }
-        if (it == 0) stamp_accept(A, header_word, words);
+        if (!kStampFirst && it == 0) stamp_accept(A, stamp_request(A), words);
         block_allsum2<NT>(s1, s2, red);
         if (NT == kWave) __syncthreads();
         double t1, t2;
@@ -610,7 +629,9 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
         const bool everything = !ip.per_channel && sb.n_cnt == d.N && sb.h_cnt == d.H && sb.w_cnt == d.W;
         const bool patch = sb.h_cnt * sb.w_cnt != d.HW;
         constexpr int kTwoPerUnit = 4;                                       // {512, 16}
-        if (chosen.v > kTwoPerUnit && (backward || everything)) {
+        // (not when the big variant holds a channel per block: without any exchange it is the faster one, full BN
+        // forward at 64x256x56x56 bf16 41 against 47 us)
+        if (chosen.v > kTwoPerUnit && (backward || (everything && chosen.T > 1))) {
             Plan p;
             if ((e = plan_for(kTwoPerUnit, &p)) != hipSuccess) return e;
             if (p.v >= 0) chosen = p;
@@ -638,7 +659,11 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     }
     // Backward over several rounds: the pipelined kernel (bns_fused_pipe.hip), which holds the dy vectors of two
     // channels per member so that loads stay in flight across the exchange, and parks x in LDS so that no mode
-    // reads anything twice.  "fused_pipe": 0 = whenever it applies, 1..n = that variant, 16 = never.
+    // reads anything twice.  "fused_pipe": 0 = whenever it applies, 1..n = that variant, 16 = never.  (A forward
+    // kernel built the same way was 10 us slower than the plain one at 64x256x56x56 and was dropped: with one
+    // tensor to read there is no second stream of loads to put between the prefetch and the stores.  So was a
+    // forward flavour that takes the statistics of a patch from the registers under per-element masks: it has
+    // to wait for the vectors that the patch elements, read on their own, run ahead of.)
     const void* pipe_kernel = nullptr;
     int pipe_nt = 0, pipe_k = 0;
     const bool pipe_forced = g_tuning.fused_pipe > 0 && g_tuning.fused_pipe <= pipe_variant_count();
@@ -811,6 +836,8 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
             return e;
         (void)hipGetLastError();
     }
+    g_launch_count.fetch_add(1, std::memory_order_relaxed);
+    if (backward) g_last_fused_backward.store(pipe_kernel ? 3 : (kind & 2) ? 2 : 1);
     e = g_tuning.fused_coop ? hipLaunchCooperativeKernel(kernel, dim3(grid), dim3(launch_nt), params, 0, st)
                             : hipLaunchKernel(kernel, dim3(grid), dim3(launch_nt), params, 0, st);
     if (e == hipSuccess && chain) {

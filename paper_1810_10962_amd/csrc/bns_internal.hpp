@@ -5,18 +5,26 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "bns_index.hpp"
 
 // Kernel launch whose status the following hipGetLastError() reports: the thread's last-error state may
 // still hold a failure of some earlier, unrelated runtime call (the caller's, the framework's), which must
 // not be taken for this launch's, so it is cleared first.
-#define BNS_LAUNCH(...)                  \
-    do {                                 \
-        (void)hipGetLastError();         \
-        hipLaunchKernelGGL(__VA_ARGS__); \
+#define BNS_LAUNCH(...)                                              \
+    do {                                                             \
+        (void)hipGetLastError();                                     \
+        ::bns::g_launch_count.fetch_add(1, std::memory_order_relaxed); \
+        hipLaunchKernelGGL(__VA_ARGS__);                             \
     } while (0)
 
 namespace bns {
+
+// Kernels launched by the library since it was loaded ("launch_count" option: benchmarks report launches per call).
+extern std::atomic<uint32_t> g_launch_count;
+// Which single-launch backward kernel the last fused backward call took: 1 plain, 2 x kept in registers, 3 pipelined.
+extern std::atomic<int32_t> g_last_fused_backward;
 
 constexpr int kMaxSplits = 64;  // upper bound on blocks that share one channel's reduction
 

@@ -99,6 +99,11 @@ WORKLOADS = {
         _wl(3, "imagenet_full_nhwc", 64, 256, 56, 56, FULL, layout="nhwc"),
         _wl(3, "imagenet_bs_nhwc_bf16", 64, 256, 56, 56, BS, n_s=8, dtype="bf16", layout="nhwc"),
         _wl(3, "imagenet_full_nhwc_bf16", 64, 256, 56, 56, FULL, dtype="bf16", layout="nhwc"),
+        # the 112 x 112 maps of the first stage of the ImageNet models (Table 1): same element count as above, planes
+        # four times as large, a quarter of the channels
+        _wl(7, "stage1_bs", 64, 64, 112, 112, BS, n_s=8),
+        _wl(7, "stage1_fs", 64, 64, 112, 112, FS, patch_h=28, patch_w=28),
+        _wl(7, "stage1_full", 64, 64, 112, 112, FULL),
         _wl(4, "vdn", 130, 128, 28, 28, VDN, n_s=2),
         # "FS + VDN", the paper's best-accuracy combination (Table 2): 2 virtual + 128 real samples,
         # one 7x7 patch (1/16 of a 28x28 map) of every real sample, beta = 0.5

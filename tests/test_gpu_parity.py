@@ -230,6 +230,29 @@ def test_imagenet_shape_all_channels(name, imagenet_inputs):
     _announce(f"{name} worst scaled errors {worst}")
 
 
+@pytest.fixture(scope="module")
+def stage1_inputs():
+    wl = workloads.WORKLOADS["stage1_bs"]
+    _announce("generating 64x64x112x112 inputs")
+    return workloads.make_inputs(wl)
+
+
+@pytest.mark.parametrize("name", ["stage1_bs", "stage1_fs", "stage1_full"])
+def test_first_stage_shape_all_channels(name, stage1_inputs):
+    """64x64x112x112, the first-stage maps of the ImageNet models (Table 1): a channel is 3.2 MB, which a team of
+    several dozen blocks still holds on chip; every channel against the oracle."""
+    wl = workloads.WORKLOADS[name]
+    _, res = _run(wl, stage1_inputs)
+    assert (res["boxes"] == oracle_boxes(wl)).all()
+    worst = {}
+    for c0 in range(0, wl.C, 16):
+        ch = list(range(c0, min(c0 + 16, wl.C)))
+        errs = assert_parity(res, oracle_reference(wl, stage1_inputs, channels=ch), wl, channels=ch, what=f"{name} ch {c0}")
+        for k, v in errs.items():
+            worst[k] = max(worst.get(k, 0.0), v)
+    _announce(f"{name} worst scaled errors {worst}")
+
+
 # ---------------------------------------------------------------------------------------
 # determinism, stages, channel groups
 # ---------------------------------------------------------------------------------------
