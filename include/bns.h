@@ -42,12 +42,17 @@
  *            moving averages keep their old values, the kernel ends normally, and
  *            bns_expired_waits() reports it, so nobody has to scan tensors.
  * Aliasing   Outputs must not overlap inputs or each other (x is needed again
- *            by the backward pass; dx is written while dy is read).
+ *            by the backward pass; dx is written while dy is read).  The host
+ *            checks the tensors (y against x; dx against x and dy) and returns
+ *            BNS_EINVAL when they overlap.  The per-channel vectors and the
+ *            workspace are not checked against anything: keeping them apart
+ *            from each other and from the tensors is the caller's duty.
  * Errors     Every call returns a bns_status.  Arguments are validated on the
  *            host before anything is enqueued: BNS_EINVAL for NULL pointers,
  *            non-positive extents, n_s outside [1, N] (Alg. 1), patch sizes
  *            outside [1, H] x [1, W] (Alg. 2), VDN with n_s >= N, unknown
- *            enums, misaligned pointers, overlapping buffers;
+ *            enums, misaligned pointers, an output tensor that overlaps an
+ *            input tensor (see Aliasing);
  *            BNS_EUNSUPPORTED for extents beyond the limits listed at
  *            bns_shape; BNS_EWORKSPACE when the workspace is too small;
  *            BNS_EDEVICE when the HIP runtime reports a launch failure.
@@ -168,9 +173,9 @@ bns_status bns_backward(const bns_shape* shape, const bns_spec* spec, uint64_t s
 /* bns_backward for callers that cannot hand over a workspace they allocated: code recorded into a HIP graph
  * whose buffers are fixed before the scratch size is known, tight serving or training loops, harnesses that
  * forbid hipMalloc.  Same arguments, results (bit for bit) and errors as bns_backward, without `workspace`:
- * the partial sums and exchange slots live in a 4 MiB array built into the library's device code, one copy
+ * the partial sums and exchange slots live in an array of 4 MiB + 256 bytes built into the library's device code, one copy
  * per GPU, held from the first use of the library on that GPU until the process ends.  The call allocates
- * and frees nothing.  BNS_EWORKSPACE if bns_workspace_bytes(shape, spec) exceeds 4 MiB (N x C x H x W: more than
+ * and frees nothing.  BNS_EWORKSPACE if bns_workspace_bytes(shape, spec) exceeds that size (N x C x H x W: more than
  * 3840 channels).  All such calls on one GPU share the one array, which keeps what the last call left in it
  * (nothing in it has to start at zero): they must be ordered on one stream, like calls that share a
  * workspace; calls that overlap on a GPU race.  The first call on each GPU looks the array's address up and
@@ -281,10 +286,11 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  *                    the shape, 16 never; 0: when the launch has three or more rounds (tensors below 4 GiB)
  *   "fused_team"     blocks that share a channel in that kernel, if they can hold it    (1..128)
  *   "fused_coop"     1: launch the fused kernels with hipLaunchCooperativeKernel
- *   "fused_spin_limit"  polls a block of a fused kernel waits for a team-mate's sums before it gives up
- *                    (1..2^21, the default); "fused_mute" 1: no block publishes its sums, so every such wait
- *                    expires -- the two together let a test reach the give-up path (NaN sums, the kernel
- *                    ends normally) from the host
+ *   "fused_patch_mask"  Feature Sampling forward: by default, when one block holds a channel, the statistics of
+ *                    the patch come from the vectors already in registers, under a column mask (built for the
+ *                    two largest variants and rows that are a whole number of vectors); 1: also when several
+ *                    blocks share a channel; 2: the patch elements are always read on their own, ahead of
+ *                    the vectors
  *   "fused_keep_x"   the fused backward kernel keeps x in registers beside dy instead of reading it again
  *                    on S: 1 always, 2 never; 0: when S is the whole tensor or a patch of every plane
  *   "split_statistics"  1: the streaming forward statistics always run as partial sums + finalize
@@ -300,15 +306,24 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  *                    per direction does everything when a thread would walk at most 16 rows)
  *   "norm_unroll", "dx_unroll", "reduce_unroll"   128-bit accesses per thread    (1, 2, 4)
  *   "norm_nt", "dx_nt", "reduce_nt"   non-temporal access mask + 1: bit 0 loads, bit 1 stores
+ * Two more exist for the library's own tests only; they make results wrong on purpose and a caller has no
+ * use for them:
+ *   "test_spin_limit"    polls a block of a fused kernel waits for a team-mate's sums before it gives up
+ *                    (1..2^21, the default)
+ *   "test_mute_exchange" 1: no block publishes its sums, so every such wait runs out -- the two together let
+ *                    a test reach the give-up path (NaN sums, the kernel ends normally) from the host
+ * The options are atomics: setting one while another thread launches work is defined (that call sees the old
+ * or the new value), but the launch choices of calls in flight are then anyone's guess -- set them first.
  * Notes on the fused kernels: blocks of a team exchange partial sums through the workspace and wait
  * for each other with a bounded spin (the grid never exceeds what the device holds at once); they
  * are bit-reproducible like the streaming kernels, and they can be captured into a HIP graph like any other
  * launch (the stamps that tell one exchange from the next are counted in the workspace, on the device). */
 bns_status bns_set_option(const char* name, int32_t value);
-/* Current value of an option (as set, 0 = automatic); also "last_path_forward" / "last_path_backward":
- * 1 if the last bns_forward / bns_backward took the streaming kernels, 2 if the fused one, 3 if the
+/* Current value of an option (as set, 0 = automatic); also, kept per calling thread,
+ * "last_path_forward" / "last_path_backward": 1 if this thread's last bns_forward / bns_backward took the streaming kernels, 2 if the fused one, 3 if the
  * one-launch kernel for small N x H x W x C tensors; "last_fused_backward": which fused backward kernel that was
- * (1 plain, 2 x kept in registers, 3 pipelined); "launch_count": kernels launched by the library since it was
+ * (1 plain, 2 x kept in registers, 3 pipelined); "last_fused_forward": 2 if the fused forward kernel took the
+ * statistics of a patch from the registers (see "fused_patch_mask"), else 1; "launch_count": kernels launched by the library since it was
  * loaded, modulo 2^31 (benchmarks report launches per call from its differences).
  * -1 for an unknown name. */
 int32_t bns_get_option(const char* name);

@@ -342,8 +342,7 @@ class Buffers:
                                   _ptr(self.save_invstd), _ptr(self.running_mean), _ptr(self.running_var), _ptr(ws),
                                   C.c_size_t(ws.numel() * ws.element_size()))
             _check(_lib.bns_forward(*self._fwd_args, self._stream_ptr()), "bns_forward")
-            return
-        if self.n_v:
+        else:
             # same call as bns_forward_mixed(...), marshalled once
             if self._fwd_args is None:
                 ws = self.workspace
@@ -354,9 +353,6 @@ class Buffers:
                                   _ptr(self.running_mean), _ptr(self.running_var), _ptr(ws),
                                   C.c_size_t(ws.numel() * ws.element_size()))
             _check(_lib.bns_forward_mixed(*self._fwd_args, self._stream_ptr()), "bns_forward_mixed")
-            return
-        bns_forward(self.shape, self.spec, self.seed, self.x, self.gamma, self.beta, self.wl.eps, self.wl.momentum,
-                    self.y, self.save_mean, self.save_invstd, self.running_mean, self.running_var, self.workspace)
 
     def backward(self):
         if self.n_v == 0:
@@ -367,8 +363,7 @@ class Buffers:
                                   _ptr(self.dx), _ptr(self.dgamma), _ptr(self.dbeta), _ptr(ws),
                                   C.c_size_t(ws.numel() * ws.element_size()))
             _check(_lib.bns_backward(*self._bwd_args, self._stream_ptr()), "bns_backward")
-            return
-        if self.n_v:
+        else:
             if self._bwd_args is None:
                 ws = self.workspace
                 self._bwd_args = (C.byref(self.shape), C.byref(self.spec), C.c_uint64(self.seed), C.c_int32(self.n_v),
@@ -377,9 +372,6 @@ class Buffers:
                                   _ptr(self.dx), _ptr(self.dgamma), _ptr(self.dbeta), _ptr(ws),
                                   C.c_size_t(ws.numel() * ws.element_size()))
             _check(_lib.bns_backward_mixed(*self._bwd_args, self._stream_ptr()), "bns_backward_mixed")
-            return
-        bns_backward(self.shape, self.spec, self.seed, self.x, self.dy, self.gamma, self.save_mean,
-                     self.save_invstd, self.dx, self.dgamma, self.dbeta, self.workspace)
 
     def results(self):
         import torch

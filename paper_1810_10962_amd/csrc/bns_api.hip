@@ -12,7 +12,8 @@
 using namespace bns;
 
 std::atomic<uint32_t> bns::g_launch_count{0};
-std::atomic<int32_t> bns::g_last_fused_backward{0};
+thread_local int32_t bns::t_last_fused_backward = 0;
+thread_local int32_t bns::t_last_fused_forward = 0;
 
 // Built-in scratch memory of bns_backward_builtin_workspace (see there).
 constexpr size_t kBuiltinWorkspaceBytes = (size_t(4) << 20) + bns::kHeaderBytes;    // 3840 channels
@@ -23,60 +24,10 @@ namespace {
 std::atomic<int32_t> g_splits_stats{0};
 std::atomic<int32_t> g_splits_reduce{0};
 std::atomic<int32_t> g_channel_group{0};
-std::atomic<int32_t> g_last_path_forward{0};    // what the last forward / backward call launched: 1 = streaming kernels,
-std::atomic<int32_t> g_last_path_backward{0};   // 2 = fused single-launch kernel, 3 = one-launch kernel for small N x H x W x C tensors
-
-inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
-inline bool overlap(const void* a, size_t na, const void* b, size_t nb) {
-    const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
-    return pa < pb + nb && pb < pa + na;
-}
-
-bns_status check_shape(const bns_shape* sh, Dims* d) {
-    if (!sh) return BNS_EINVAL;
-    if (sh->N <= 0 || sh->C <= 0 || sh->H <= 0 || sh->W <= 0) return BNS_EINVAL;
-    if (sh->dtype != BNS_F32 && sh->dtype != BNS_BF16) return BNS_EINVAL;
-    if (sh->layout != BNS_NCHW && sh->layout != BNS_NHWC) return BNS_EINVAL;
-    const int64_t hw = int64_t(sh->H) * sh->W;
-    const int64_t lim = int64_t(1) << 31;
-    if (sh->N > 65535 || sh->C > (1 << 24) || hw >= lim || hw * sh->N >= lim || hw * sh->C >= lim)
-        return BNS_EUNSUPPORTED;
-    d->N = sh->N;
-    d->C = sh->C;
-    d->H = sh->H;
-    d->W = sh->W;
-    d->HW = int32_t(hw);
-    d->dtype = sh->dtype;
-    d->layout = sh->layout;
-    if (sh->dtype == BNS_BF16 && hw % 8 == 0)
-        d->vec = 8;
-    else if (hw % 4 == 0)
-        d->vec = 4;
-    else
-        d->vec = 1;
-    return BNS_OK;
-}
-
-bns_status check_spec(const bns_shape* sh, const bns_spec* sp) {
-    if (!sp) return BNS_EINVAL;
-    switch (sp->mode) {
-        case BNS_FULL:
-            return BNS_OK;
-        case BNS_NS:
-        case BNS_BS:
-            return (sp->n_s >= 1 && sp->n_s <= sh->N) ? BNS_OK : BNS_EINVAL;   // n_s in (0, N], Alg. 1
-        case BNS_VDN:
-            return (sp->n_s >= 1 && sp->n_s < sh->N) ? BNS_OK : BNS_EINVAL;    // at least one real sample
-        case BNS_FS:
-            if (sp->fs_per_channel != 0 && sp->fs_per_channel != 1) return BNS_EINVAL;
-            return (sp->patch_h >= 1 && sp->patch_h <= sh->H && sp->patch_w >= 1 && sp->patch_w <= sh->W)
-                       ? BNS_OK
-                       : BNS_EINVAL;                                           // h_s in (0, H], w_s in (0, W], Alg. 2
-        default:
-            return BNS_EINVAL;
-    }
-}
+// What the calling thread's last forward / backward call launched: 1 = streaming kernels,
+// 2 = fused single-launch kernel, 3 = one-launch kernel for small N x H x W x C tensors.
+thread_local int32_t t_last_path_forward = 0;
+thread_local int32_t t_last_path_backward = 0;
 
 inline size_t elem_bytes(const Dims& d) { return d.dtype == BNS_F32 ? 4 : 2; }
 inline size_t tensor_bytes(const Dims& d) { return size_t(d.N) * d.C * d.HW * elem_bytes(d); }
@@ -105,7 +56,7 @@ inline bns_status dev(hipError_t e) { return e == hipSuccess ? BNS_OK : BNS_EDEV
 // non-temporal masks are given as mask + 1 so that 0 keeps that meaning.
 struct TuningEntry {
     const char* name;
-    int Tuning::*field;
+    TuneInt Tuning::*field;
     int hi, bias;
     bool pow2;      // unroll factors: 1, 2 or 4
 };
@@ -118,9 +69,10 @@ const TuningEntry kTuningTable[] = {
     {"fused_pipe", &Tuning::fused_pipe, 16, 0, false},
     {"fused_team", &Tuning::fused_team, 128, 0, false},
     {"fused_coop", &Tuning::fused_coop, 1, 0, false},
-    {"fused_spin_limit", &Tuning::fused_spin_limit, 1 << 21, 0, false},
-    {"fused_mute", &Tuning::fused_mute, 1, 0, false},
+    {"test_spin_limit", &Tuning::test_spin_limit, 1 << 21, 0, false},
+    {"test_mute_exchange", &Tuning::test_mute_exchange, 1, 0, false},
     {"fused_keep_x", &Tuning::fused_keep_x, 2, 0, false},
+    {"fused_patch_mask", &Tuning::fused_patch_mask, 2, 0, false},
     {"split_statistics", &Tuning::split_statistics, 1, 0, false},
     {"nhwc_blocks", &Tuning::nhwc_blocks, kNhwcBlocksMax, 0, false},
     {"nhwc_ew_rows", &Tuning::nhwc_ew_rows, 1 << 20, 0, false},
@@ -284,10 +236,10 @@ bns_status bns_forward(const bns_shape* shape, const bns_spec* spec, uint64_t se
         hipError_t se = hipSuccess;
         if (launch_nhwc_small_forward(d, ip.shared, x, gamma, beta, eps, momentum, y, save_mean, save_invstd, running_mean,
                                       running_var, st, &se)) {
-            g_last_path_forward.store(3);
+            t_last_path_forward = 3;
             return dev(se);
         }
-        g_last_path_forward.store(1);
+        t_last_path_forward = 1;
         if (launch_nhwc_stats(d, ip.shared, x, ws, eps, momentum, save_mean, save_invstd, running_mean, running_var,
                               st) != hipSuccess)
             return BNS_EDEVICE;
@@ -306,13 +258,13 @@ bns_status bns_forward(const bns_shape* shape, const bns_spec* spec, uint64_t se
         const hipError_t fe = launch_fused(d, ip, false, io, eps, momentum,
                                            workspace, slots_of(workspace, d), kSlotBytes, 0, d.C, st);
         if (fe == hipSuccess) {
-            g_last_path_forward.store(2);
+            t_last_path_forward = 2;
             return BNS_OK;
         }
         if (fe != hipErrorNotSupported) return BNS_EDEVICE;
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
     }
-    g_last_path_forward.store(1);
+    t_last_path_forward = 1;
     const int G = channel_group(d);
     for (int c0 = 0; c0 < d.C; c0 += G) {
         const int cg = (d.C - c0 < G) ? d.C - c0 : G;
@@ -392,10 +344,10 @@ bns_status backward_impl(const bns_shape* shape, const bns_spec* spec, uint64_t 
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
         hipError_t se = hipSuccess;
         if (launch_nhwc_small_backward(d, ip.shared, x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta, st, &se)) {
-            g_last_path_backward.store(3);
+            t_last_path_backward = 3;
             return dev(se);
         }
-        g_last_path_backward.store(1);
+        t_last_path_backward = 1;
         if (launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, ws, dgamma, dbeta, st) != hipSuccess) return BNS_EDEVICE;
         return dev(launch_nhwc_dx(d, ip.shared, x, dy, gamma, save_mean, save_invstd, dgamma, dbeta, dx, st));
     }
@@ -412,13 +364,13 @@ bns_status backward_impl(const bns_shape* shape, const bns_spec* spec, uint64_t 
         const hipError_t fe = launch_fused(d, ip, true, io, 0.f, 0.f, workspace, slots_of(workspace, d),
                                            kSlotBytes, 0, d.C, st, nullptr, order_streams);
         if (fe == hipSuccess) {
-            g_last_path_backward.store(2);
+            t_last_path_backward = 2;
             return BNS_OK;
         }
         if (fe != hipErrorNotSupported) return BNS_EDEVICE;
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
     }
-    g_last_path_backward.store(1);
+    t_last_path_backward = 1;
     const int G = channel_group(d);
     for (int c0 = 0; c0 < d.C; c0 += G) {
         const int cg = (d.C - c0 < G) ? d.C - c0 : G;
@@ -517,7 +469,7 @@ bns_status bns_forward_mixed(const bns_shape* shape, const bns_spec* spec, uint6
     const IndexParams ip_s = make_index_params_mixed(*shape, *spec, seed, n_v);
     if (nhwc(d)) {
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
-        g_last_path_forward.store(1);
+        t_last_path_forward = 1;
         if (launch_nhwc_stats_mixed(d, ip_s.shared, n_v, x, partials_of(workspace), mix_beta, eps, momentum,
                                     save_mean, save_invstd, save_mean_parts, running_mean, running_var, st) != hipSuccess)
             return BNS_EDEVICE;
@@ -541,13 +493,13 @@ bns_status bns_forward_mixed(const bns_shape* shape, const bns_spec* spec, uint6
                                            workspace, slots_of(workspace, d), kSlotBytes, 0, d.C, st,
                                            &mix);
         if (fe == hipSuccess) {
-            g_last_path_forward.store(2);
+            t_last_path_forward = 2;
             return BNS_OK;
         }
         if (fe != hipErrorNotSupported) return BNS_EDEVICE;
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
     }
-    g_last_path_forward.store(1);
+    t_last_path_forward = 1;
     const IndexParams ip_v = make_index_params_virtual(*shape, n_v);
     Partial* ws_s = partials_of(workspace);
     Partial* ws_v = reinterpret_cast<Partial*>(reinterpret_cast<char*>(partials_of(workspace)) + partial_bytes(d));
@@ -579,7 +531,7 @@ bns_status bns_backward_mixed(const bns_shape* shape, const bns_spec* spec, uint
     const IndexParams ip_s = make_index_params_mixed(*shape, *spec, seed, n_v);
     if (nhwc(d)) {
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
-        g_last_path_backward.store(1);
+        t_last_path_backward = 1;
         if (launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, partials_of(workspace), dgamma, dbeta, st) !=
             hipSuccess)
             return BNS_EDEVICE;
@@ -603,13 +555,13 @@ bns_status bns_backward_mixed(const bns_shape* shape, const bns_spec* spec, uint
         const hipError_t fe = launch_fused(d, ip_s, true, io, 0.f, 0.f, workspace, slots_of(workspace, d),
                                            kSlotBytes, 0, d.C, st, &mix);
         if (fe == hipSuccess) {
-            g_last_path_backward.store(2);
+            t_last_path_backward = 2;
             return BNS_OK;
         }
         if (fe != hipErrorNotSupported) return BNS_EDEVICE;
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
     }
-    g_last_path_backward.store(1);
+    t_last_path_backward = 1;
     s = reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, partials_of(workspace), 0, d.C, st);
     if (s != BNS_OK) return s;
     const bns_box& b = ip_s.shared;
@@ -670,9 +622,10 @@ int32_t bns_get_option(const char* name) {
     if (!strcmp(name, "splits_stats")) return g_splits_stats.load();
     if (!strcmp(name, "splits_reduce")) return g_splits_reduce.load();
     if (!strcmp(name, "channel_group")) return g_channel_group.load();
-    if (!strcmp(name, "last_path_forward")) return g_last_path_forward.load();
-    if (!strcmp(name, "last_path_backward")) return g_last_path_backward.load();
-    if (!strcmp(name, "last_fused_backward")) return g_last_fused_backward.load();
+    if (!strcmp(name, "last_path_forward")) return t_last_path_forward;
+    if (!strcmp(name, "last_path_backward")) return t_last_path_backward;
+    if (!strcmp(name, "last_fused_backward")) return t_last_fused_backward;
+    if (!strcmp(name, "last_fused_forward")) return t_last_fused_forward;
     if (!strcmp(name, "launch_count")) return int32_t(g_launch_count.load() & 0x7fffffffu);
     for (const TuningEntry& t : kTuningTable)
         if (!strcmp(name, t.name)) {

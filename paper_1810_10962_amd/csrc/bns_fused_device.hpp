@@ -95,6 +95,18 @@ constexpr uint32_t kSpinLimit = 1u << 21; // polls before a missing team-mate is
 // are ordered on one stream.)  A workspace need not be initialised by the caller: the first block that finds no
 // magic sets the words up, the others wait for it; chance bytes that look like the magic are as good a start as any.
 // `expired` counts waits for a team-mate that ran out.
+// A per-channel constant that came straight from a load and is used inside the (divergent) blocks of the unrolled
+// store loops: the compiler's wait-count bookkeeping loses track of such a register at the joins and waits for
+// "everything outstanding" before each use -- which includes the stores of the previous block, so the stores of a
+// thread would go out one at a time.  Passing the value through an empty asm ends its life as a load result.
+// (The stores of a thread now leave back to back; at 64x256x56x56 the launch times did not change measurably.)
+__device__ __forceinline__ float settled(float v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
+constexpr int kStageSlots = 3072;    // 16-byte vectors of a channel that touch the patch (forward, one block per channel)
+
 struct TeamHeader {
     unsigned long long state;
     unsigned int done;
@@ -121,6 +133,8 @@ struct FusedArgs {
     unsigned long long* slots;  // [2][gridDim.x][2] words of {payload, stamp}
     IndexParams ip;
     FastDiv hwv_div, w_div;
+    FastDiv wv_div;             // vectors per row (rows that are a whole number of vectors)
+    int32_t patch_stage;        // forward, patch statistics from the registers: 1 = through the LDS staging array
     FastDiv chw_div;            // C * HW: element offset inside the tensor -> sample (pipelined kernel)
     int32_t C, W, HW;
     int32_t c0, cg;

@@ -148,7 +148,10 @@ struct BackwardPipe {
 
     template <typename P>
     static __device__ __forceinline__ P* at(P* base, uint32_t byte_off) {
-        return reinterpret_cast<P*>(reinterpret_cast<uintptr_t>(base) + byte_off);
+        // pointer arithmetic, not integer arithmetic: the access stays a global one (an address rebuilt from an integer
+        // is a flat address, whose loads also count as LDS traffic and stall every wait for the LDS)
+        typedef std::conditional_t<std::is_const<P>::value, const char, char> byte_t;
+        return reinterpret_cast<P*>(reinterpret_cast<byte_t*>(base) + byte_off);
     }
 
     // Issues the loads of channel c that can run ahead: all K dy vectors and the first XB x vectors.
@@ -263,9 +266,9 @@ __global__ __launch_bounds__(NT, 4) void fused_backward_pipe_kernel(FusedArgs A)
     auto one_channel = [&](raw_t(&cur)[K], raw_t(&nxt)[K], int cl, uint32_t it) {
         const int c = A.c0 + cl;
         const bns_box b = box_of_channel(A.ip, c);
-        const float mu = A.save_mean[c];
-        const float r = A.save_invstd[c];
-        const float ga_c = A.gamma[c];
+        const float mu = settled(A.save_mean[c]);
+        const float r = settled(A.save_invstd[c]);
+        const float ga_c = settled(A.gamma[c]);
         float s1 = 0.f, s2 = 0.f;
         p.sums(cur, x0, c, mu, park, s1, s2);
         block_total2<NT>(s1, s2, red);

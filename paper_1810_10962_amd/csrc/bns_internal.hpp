@@ -8,6 +8,7 @@
 #include <atomic>
 
 #include "bns_index.hpp"
+#include "bns_validate.hpp"
 
 // Kernel launch whose status the following hipGetLastError() reports: the thread's last-error state may
 // still hold a failure of some earlier, unrelated runtime call (the caller's, the framework's), which must
@@ -23,42 +24,42 @@ namespace bns {
 
 // Kernels launched by the library since it was loaded ("launch_count" option: benchmarks report launches per call).
 extern std::atomic<uint32_t> g_launch_count;
-// Which single-launch backward kernel the last fused backward call took: 1 plain, 2 x kept in registers, 3 pipelined.
-extern std::atomic<int32_t> g_last_fused_backward;
+// Which single-launch backward kernel the calling thread's last fused backward call took: 1 plain, 2 x kept in registers, 3 pipelined.
+extern thread_local int32_t t_last_fused_backward;
+// Which flavour the calling thread's last fused forward call took: 1 plain or patch elements read on their own,
+// 2 patch statistics from the registers.
+extern thread_local int32_t t_last_fused_forward;
 
 constexpr int kMaxSplits = 64;  // upper bound on blocks that share one channel's reduction
 
-struct Dims {
-    int32_t N, C, H, W;
-    int32_t HW;     // H * W
-    int32_t dtype;  // bns_dtype
-    int32_t vec;    // elements per memory access: largest of {8 (bf16 only), 4, 1} dividing HW
-    int32_t layout; // bns_layout
-};
 
 // Launch-shape choices; 0 = the default for the storage type (see tuned()).  The benchmark
 // can override them through bns_set_option.  Defaults come from sweeps on MI355X at
 // 64x256x56x56: one 128-bit access per thread and non-temporal loads and stores stream
 // fastest (streamed data is not re-read, so keeping it out of L2 avoids write-backs of
 // lines nobody will hit).
-// Plain ints set by bns_set_option: meant to be set before work is launched, not concurrently with it.
+// Every field is an atomic: bns_set_option may run while another thread launches work (that call then
+// sees the old or the new value of each field it reads, never a torn one).
+using TuneInt = std::atomic<int>;
 struct Tuning {
-    int norm_unroll = 0, norm_nt = -1;      // accesses per thread; bit 0: non-temporal loads, bit 1: stores
-    int dx_unroll = 0, dx_nt = -1;
-    int reduce_unroll = 0, reduce_nt = -1;
-    int path = 0;                           // 0: fused kernels when a channel fits on chip, else streaming;
+    TuneInt norm_unroll{0}, norm_nt{-1};    // accesses per thread; bit 0: non-temporal loads, bit 1: stores
+    TuneInt dx_unroll{0}, dx_nt{-1};
+    TuneInt reduce_unroll{0}, reduce_nt{-1};
+    TuneInt path{0};                        // 0: fused kernels when a channel fits on chip, else streaming;
                                             // 1: streaming kernels only; 2: fused only (error if it cannot)
-    int fused_variant = 0;                  // 1..7 forces a (block size, registers) variant of the fused kernels
-    int fused_keep_x = 0;                   // backward keeps x in registers next to dy: 1 always, 2 never, 0 when it pays
-    int fused_pipe = 0;                     // backward: 1..n forces variant n of the pipelined kernel, 16: never
-    int fused_team = 0;                     // blocks per team of the pipelined kernel, if the channel fits (0: planner)
-    int fused_coop = 0;                     // 1: launch the fused kernels with hipLaunchCooperativeKernel
-    int fused_spin_limit = 0;               // polls a team member waits for a team-mate before giving up (default 2^21)
-    int fused_mute = 0;                     // 1 (tests of the give-up path): no member publishes its sums
-    int split_statistics = 0;               // 1: forward statistics always as partial sums + finalize
-    int nhwc_blocks = 0;                    // blocks an N x H x W x C reduction aims for (default kNhwcBlocks)
-    int nhwc_small = 0;                     // 2: never take the one-launch kernels for small N x H x W x C tensors
-    int nhwc_ew_rows = 0;                   // rows per row lane in its element-wise kernels (default kNhwcEwRows)
+    TuneInt fused_variant{0};               // 1..7 forces a (block size, registers) variant of the fused kernels
+    TuneInt fused_keep_x{0};                // backward keeps x in registers next to dy: 1 always, 2 never, 0 when it pays
+    TuneInt fused_pipe{0};                  // backward: 1..n forces variant n of the pipelined kernel, 16: never
+    TuneInt fused_team{0};                  // blocks per team of the pipelined kernel, if the channel fits (0: planner)
+    TuneInt fused_patch_mask{0};            // forward, patch: statistics from the registers 1 = whenever built, 2 = never, 0 = when a block holds its channel alone
+    TuneInt fused_coop{0};                  // 1: launch the fused kernels with hipLaunchCooperativeKernel
+    TuneInt split_statistics{0};            // 1: forward statistics always as partial sums + finalize
+    TuneInt nhwc_blocks{0};                 // blocks an N x H x W x C reduction aims for (default kNhwcBlocks)
+    TuneInt nhwc_small{0};                  // 2: never take the one-launch kernels for small N x H x W x C tensors
+    TuneInt nhwc_ew_rows{0};                // rows per row lane in its element-wise kernels (default kNhwcEwRows)
+    // For the library's own tests of the give-up path only; a caller has no use for them.
+    TuneInt test_spin_limit{0};             // polls a team member waits for a team-mate before giving up (default 2^21)
+    TuneInt test_mute_exchange{0};          // 1: no member publishes its sums, so every wait runs out
 };
 extern Tuning g_tuning;
 inline int tuned(int v, int dflt) { return v > 0 ? v : dflt; }

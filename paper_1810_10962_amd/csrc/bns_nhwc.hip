@@ -39,6 +39,7 @@ struct RowSet {                 // the rows of S: sampled row i -> (n, ph, pw) -
     uint32_t rows;              // n_cnt * h_cnt * w_cnt
     uint32_t pivot_rows;        // min(kPivotRows, rows)
     float inv_pivot_rows;
+    bool contiguous;            // sampled row i = sampled row 0 + i
 };
 
 // The one-pass variance is taken about a pivot p_c close to the mean: sum (x - p)^2 / s - (sum (x - p) / s)^2
@@ -107,14 +108,25 @@ __device__ __forceinline__ void write_partials(float (&a)[V], float (&q)[V], flo
 
 // Forward statistics (Eq. 3): partial[k][c] = (sum (x - p_c), sum (x - p_c)^2) over the k-th share of
 // S, p_c = mean of x over the first few sampled rows.
-template <typename T, int V>
+//
+// A row lane takes its rows kStatRows at a time.  The loads of the next batch are issued before the
+// current one is added up, and the pivot rows travel together with the first batch, so a block with few
+// rows (a small S spread over the whole device) waits for memory once and a block with many rows keeps
+// two batches in flight.  Row indices past the end of the share are clamped to its last row and their
+// terms dropped, so every load is unconditional.  CONTIG: the rows of S are one contiguous run (Batch
+// Sampling, full BN, NS, the virtual set), so the sampled row needs no division.
+constexpr int kStatRows = 8;
+
+template <typename T, int V, bool CONTIG>
 __global__ __launch_bounds__(kBlock) void nhwc_stats_partial_kernel(const T* __restrict__ x,
                                                                     Partial* __restrict__ partial, RowSet S, Tiling t) {
     __shared__ float lds[2 * kBlock * V];
     const Lane l = lane_of(t);
     const uint32_t i0 = uint32_t(l.k) * t.rows_per_block;
-    const uint32_t i1 = min(i0 + t.rows_per_block, S.rows);
+    const uint32_t i1 = min(i0 + t.rows_per_block, S.rows);      // i1 > i0: no block is empty
     const uint32_t TY = uint32_t(l.TY);
+    const uint32_t step = uint32_t(kStatRows) * TY;
+    const uint32_t batches = (i1 - i0 + step - 1u) / step;      // the same for every thread of the block
     float a[V], q[V], p[V];
     double A[V], Q[V];
 #pragma unroll
@@ -124,37 +136,61 @@ __global__ __launch_bounds__(kBlock) void nhwc_stats_partial_kernel(const T* __r
     }
     if (l.live) {
         const T* xc = x + size_t(l.cv) * V;
-        Vec<T, V> pv[kPivotRows];
+        const uint32_t first = sampled_row(S, 0u);
+        auto row_of = [&](uint32_t i) { return CONTIG ? first + i : sampled_row(S, i); };
+        auto fetch = [&](Vec<T, V>(&v)[kStatRows], uint32_t i) {
+#pragma unroll
+            for (int u = 0; u < kStatRows; ++u)
+                v[u].load_nt(xc + size_t(row_of(min(i + uint32_t(u) * TY, i1 - 1u))) * t.C);
+        };
+        auto add = [&](const Vec<T, V>(&v)[kStatRows], uint32_t i) {
+            if (i + uint32_t(kStatRows - 1) * TY < i1) {         // every row of the batch belongs to the share
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    float d[kStatRows];
+#pragma unroll
+                    for (int u = 0; u < kStatRows; ++u) d[u] = v[u].f[e] - p[e];
+                    A[e] += double(((d[0] + d[1]) + (d[2] + d[3])) + ((d[4] + d[5]) + (d[6] + d[7])));
+                    float sq = d[0] * d[0];
+#pragma unroll
+                    for (int u = 1; u < kStatRows; ++u) sq = fmaf(d[u], d[u], sq);
+                    Q[e] += double(sq);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    float d[kStatRows];
+#pragma unroll
+                    for (int u = 0; u < kStatRows; ++u) d[u] = i + uint32_t(u) * TY < i1 ? v[u].f[e] - p[e] : 0.f;
+                    A[e] += double(((d[0] + d[1]) + (d[2] + d[3])) + ((d[4] + d[5]) + (d[6] + d[7])));
+                    float sq = d[0] * d[0];
+#pragma unroll
+                    for (int u = 1; u < kStatRows; ++u) sq = fmaf(d[u], d[u], sq);
+                    Q[e] += double(sq);
+                }
+            }
+        };
+        static_assert(kStatRows == 8, "the sums above are written out for eight rows");
+        Vec<T, V> pv[kPivotRows], v0[kStatRows], v1[kStatRows];
+        uint32_t i = i0 + uint32_t(l.ty);
 #pragma unroll
         for (int j = 0; j < kPivotRows; ++j)     // no branches: all loads in flight together
-            pv[j].load(xc + size_t(sampled_row(S, min(uint32_t(j), S.pivot_rows - 1u))) * t.C);
+            pv[j].load(xc + size_t(row_of(min(uint32_t(j), S.pivot_rows - 1u))) * t.C);
+        fetch(v0, i);
 #pragma unroll
         for (int j = 0; j < kPivotRows; ++j)
 #pragma unroll
             for (int e = 0; e < V; ++e) p[e] += uint32_t(j) < S.pivot_rows ? pv[j].f[e] : 0.f;
 #pragma unroll
         for (int e = 0; e < V; ++e) p[e] = coarse(p[e] * S.inv_pivot_rows);
-        uint32_t i = i0 + uint32_t(l.ty);
-        for (; i + 3u * TY < i1; i += 4u * TY) {
-            Vec<T, V> v[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) v[u].load_nt(xc + size_t(sampled_row(S, i + uint32_t(u) * TY)) * t.C);
-#pragma unroll
-            for (int e = 0; e < V; ++e) {
-                const float d0 = v[0].f[e] - p[e], d1 = v[1].f[e] - p[e], d2 = v[2].f[e] - p[e], d3 = v[3].f[e] - p[e];
-                A[e] += double((d0 + d1) + (d2 + d3));
-                Q[e] += double(fmaf(d3, d3, fmaf(d2, d2, fmaf(d1, d1, d0 * d0))));
+        for (uint32_t b = 0; b < batches; b += 2u) {
+            if (b + 1u < batches) fetch(v1, i + step);
+            add(v0, i);
+            if (b + 1u < batches) {
+                if (b + 2u < batches) fetch(v0, i + 2u * step);
+                add(v1, i + step);
             }
-        }
-        for (; i < i1; i += TY) {
-            Vec<T, V> v;
-            v.load_nt(xc + size_t(sampled_row(S, i)) * t.C);
-#pragma unroll
-            for (int e = 0; e < V; ++e) {
-                const float dlt = v.f[e] - p[e];
-                A[e] += double(dlt);
-                Q[e] += double(dlt * dlt);
-            }
+            i += 2u * step;
         }
 #pragma unroll
         for (int e = 0; e < V; ++e) {
@@ -228,6 +264,10 @@ __global__ __launch_bounds__(kBlock) void nhwc_reduce_partial_kernel(const T* __
 constexpr int kFinCh = 8;
 constexpr int kFinK = kBlock / kFinCh;
 
+// The thread that sum_splits returns true for, and its channel.
+__device__ __forceinline__ int led_channel() { return blockIdx.x * kFinCh + int(threadIdx.x % kFinCh); }
+__device__ __forceinline__ bool leads_channel(int C) { return threadIdx.x / kFinCh == 0 && led_channel() < C; }
+
 __device__ __forceinline__ bool sum_splits(const Partial* __restrict__ partial, int C, int splits, double* lds, int& c,
                                            double& s1, double& s2) {
     const int ch = threadIdx.x % kFinCh, kl = threadIdx.x / kFinCh;
@@ -235,12 +275,12 @@ __device__ __forceinline__ bool sum_splits(const Partial* __restrict__ partial, 
     double a = 0.0, b = 0.0;
     if (c < C) {
         int k = kl;
-        for (; k + 7 * kFinK < splits; k += 8 * kFinK) {     // eight loads in flight, added in index order
-            Partial p[8];
+        for (; k + 15 * kFinK < splits; k += 16 * kFinK) {     // sixteen loads in flight, added in index order
+            Partial p[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) p[u] = partial[size_t(k + u * kFinK) * C + c];
+            for (int u = 0; u < 16; ++u) p[u] = partial[size_t(k + u * kFinK) * C + c];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < 16; ++u) {
                 a += double(p[u].a);
                 b += double(p[u].b);
             }
@@ -284,8 +324,9 @@ __global__ __launch_bounds__(kBlock) void nhwc_stats_finalize_kernel(
     __shared__ double lds[2 * kBlock];
     int c;
     double s1, s2;
+    const float pivot_f = leads_channel(C) ? column_pivot(x, S, C, led_channel()) : 0.f;   // loads overlap the sums'
     if (!sum_splits(partial, C, splits, lds, c, s1, s2)) return;
-    const double pivot = double(column_pivot(x, S, C, c));
+    const double pivot = double(pivot_f);
     const double s = double(S.rows);
     const double m1 = s1 / s;
     const double mean = pivot + m1;
@@ -310,14 +351,17 @@ __global__ __launch_bounds__(kBlock) void nhwc_stats_finalize_mixed_kernel(
     __shared__ double lds[2 * kBlock];
     int c;
     double a1 = 0.0, a2 = 0.0, v1 = 0.0, v2 = 0.0;
+    const bool lead = leads_channel(C);
+    const float pivot_s = lead ? column_pivot(x, S, C, led_channel()) : 0.f;
+    const float pivot_v = lead ? column_pivot(x, Vs, C, led_channel()) : 0.f;
     const bool lead_s = sum_splits(partial_s, C, splits_s, lds, c, a1, a2);
     __syncthreads();                                            // the leaders have read their sums
     const bool lead_v = sum_splits(partial_v, C, splits_v, lds, c, v1, v2);
     if (!lead_s || !lead_v) return;
     const double ss = double(S.rows), sv = double(Vs.rows);
     const double ms = a1 / ss, mv = v1 / sv;
-    const double e_s = double(column_pivot(x, S, C, c)) + ms;
-    const double e_v = double(column_pivot(x, Vs, C, c)) + mv;
+    const double e_s = double(pivot_s) + ms;
+    const double e_v = double(pivot_v) + mv;
     double var_s = a2 / ss - ms * ms, var_v = v2 / sv - mv * mv;
     if (var_s < 0.0) var_s = 0.0;
     if (var_v < 0.0) var_v = 0.0;
@@ -340,9 +384,10 @@ __global__ __launch_bounds__(kBlock) void nhwc_reduce_finalize_kernel(const Part
     __shared__ double lds[2 * kBlock];
     int c;
     double s1, s2;
+    const float r = leads_channel(C) ? invstd[led_channel()] : 0.f;
     if (!sum_splits(partial, C, splits, lds, c, s1, s2)) return;
     dbeta[c] = float(s1);
-    dgamma[c] = float(s2 * double(invstd[c]));
+    dgamma[c] = float(s2 * double(r));
 }
 
 // Eq. 1 on every element.  var_eps >= 0: `invstd` holds variances (inference, Appendix D).
@@ -808,6 +853,7 @@ RowSet make_rowset(const Dims& d, const bns_box& b) {
     s.rows = uint32_t(b.n_cnt) * uint32_t(b.h_cnt) * uint32_t(b.w_cnt);
     s.pivot_rows = s.rows < uint32_t(kPivotRows) ? s.rows : uint32_t(kPivotRows);
     s.inv_pivot_rows = 1.0f / float(s.pivot_rows);
+    s.contiguous = (b.w_cnt == d.W && (b.h_cnt == d.H || b.n_cnt == 1)) || (b.n_cnt == 1 && b.h_cnt == 1);
     return s;
 }
 
@@ -853,6 +899,15 @@ hipError_t dispatch_nhwc(const Dims& d, F&& f) {
     return V == 4 ? f(bf16_t(), VecTag<4>()) : f(bf16_t(), VecTag<1>());
 }
 
+template <typename T, int V>
+hipError_t launch_stats_partial(const T* x, Partial* partial, const RowSet& S, const Tiling& t, hipStream_t st) {
+    if (S.contiguous)
+        BNS_LAUNCH((nhwc_stats_partial_kernel<T, V, true>), dim3(grid_of(t)), dim3(kBlock), 0, st, x, partial, S, t);
+    else
+        BNS_LAUNCH((nhwc_stats_partial_kernel<T, V, false>), dim3(grid_of(t)), dim3(kBlock), 0, st, x, partial, S, t);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 size_t nhwc_partial_bytes(const Dims& d) {
@@ -878,9 +933,7 @@ hipError_t launch_nhwc_stats(const Dims& d, const bns_box& b, const void* x, Par
     return dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
         constexpr int V = decltype(vt)::value;
-        BNS_LAUNCH((nhwc_stats_partial_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st,
-                   static_cast<const T*>(x), partial, S, t);
-        hipError_t e = hipGetLastError();
+        hipError_t e = launch_stats_partial<T, V>(static_cast<const T*>(x), partial, S, t, st);
         if (e != hipSuccess) return e;
         BNS_LAUNCH((nhwc_stats_finalize_kernel<T>), dim3(ceil_div_u(uint32_t(d.C), kFinCh)), dim3(kBlock), 0, st,
                    static_cast<const T*>(x), partial, S, d.C, t.splits, eps, momentum, save_mean, save_invstd,
@@ -987,13 +1040,9 @@ hipError_t launch_nhwc_stats_mixed(const Dims& d, const bns_box& b, int n_v, con
     return dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
         constexpr int V = decltype(vt)::value;
-        BNS_LAUNCH((nhwc_stats_partial_kernel<T, V>), dim3(grid_of(ts)), dim3(kBlock), 0, st,
-                   static_cast<const T*>(x), partial, S, ts);
-        hipError_t e = hipGetLastError();
+        hipError_t e = launch_stats_partial<T, V>(static_cast<const T*>(x), partial, S, ts, st);
         if (e != hipSuccess) return e;
-        BNS_LAUNCH((nhwc_stats_partial_kernel<T, V>), dim3(grid_of(tv)), dim3(kBlock), 0, st,
-                   static_cast<const T*>(x), partial_v, Vs, tv);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if ((e = launch_stats_partial<T, V>(static_cast<const T*>(x), partial_v, Vs, tv, st)) != hipSuccess) return e;
         BNS_LAUNCH((nhwc_stats_finalize_mixed_kernel<T>), dim3(ceil_div_u(uint32_t(d.C), kFinCh)), dim3(kBlock), 0,
                    st, static_cast<const T*>(x), partial, ts.splits, partial_v, tv.splits, S, Vs, d.C, mix_beta, eps,
                    momentum, save_mean, save_invstd, mean_parts, running_mean, running_var);

@@ -132,15 +132,12 @@ def summand_scale(inp, ref, channels=None):
                 dgamma=np.sqrt(m * np.mean((dy * xh) ** 2, axis=(0, 2, 3))))
 
 
-def assert_parity(res, ref, wl, channels=None, what="", inp=None):
+def parity_floors(wl, inp, ref, channels=None):
+    """The floor of every output of ``ref`` (scalar or per channel), as assert_parity applies it when it is given
+    the inputs.  0.0 = none: the output is measured against its own RMS alone."""
     tol_t = TOL_F32 if wl.dtype == "f32" else TOL_BF16
-    errs = {}
-    for k, r in ref.items():
-        g = res[k]
-        if channels is not None:
-            g = g[:, channels] if g.ndim == 4 else g[channels]
-        assert g.shape == r.shape, (k, g.shape, r.shape)
-        assert np.isfinite(g).all(), f"{what} {k}: non-finite output"
+    floors = {}
+    for k in ref:
         tol = tol_t if k in ("y", "dx") else TOL_F32          # per-channel vectors are fp32 in every mode
         floor = 0.0
         if inp is not None and k == "dx":
@@ -159,6 +156,33 @@ def assert_parity(res, ref, wl, channels=None, what="", inp=None):
             # a variance enters the method only as Var + eps (Eq. 1, and App. D for the moving average); where every
             # channel's variance is exactly zero (one sampled point) the RMS over channels is zero as well
             floor = wl.eps
-        errs[k] = scaled_err(g, r, floor)
-        assert errs[k] <= tol, f"{what} {k}: scaled error {errs[k]:.3e} > {tol:g}"
+        floors[k] = floor
+    return floors
+
+
+def plain_scale(ref_k):
+    """The RMS that scaled_err adds to |ref| when there is no floor: per channel for the N x C x H x W outputs,
+    over the channels for the per-channel vectors."""
+    r = np.asarray(ref_k, dtype=np.float64)
+    if r.ndim == 4:
+        return np.sqrt(np.mean(r ** 2, axis=(0, 2, 3)))
+    return np.sqrt(np.mean(r ** 2))
+
+
+def assert_parity(res, ref, wl, channels=None, what="", inp=None, floors=True):
+    """Every output of ``ref`` within the build's tolerance of the oracle.  floors=False: no floor on any output,
+    i.e. |got - ref| / (|ref| + RMS(ref)) alone (the check for the benchmark configurations, whose outputs do
+    not cancel)."""
+    tol_t = TOL_F32 if wl.dtype == "f32" else TOL_BF16
+    floor_of = parity_floors(wl, inp, ref, channels) if floors else {}
+    errs = {}
+    for k, r in ref.items():
+        g = res[k]
+        if channels is not None:
+            g = g[:, channels] if g.ndim == 4 else g[channels]
+        assert g.shape == r.shape, (k, g.shape, r.shape)
+        assert np.isfinite(g).all(), f"{what} {k}: non-finite output"
+        tol = tol_t if k in ("y", "dx") else TOL_F32          # per-channel vectors are fp32 in every mode
+        errs[k] = scaled_err(g, r, floor_of.get(k, 0.0))
+        assert errs[k] <= tol, f"{what} {k}: scaled error {errs[k]:.3e} > {tol:g}" + ("" if floors else " (no floors)")
     return errs

@@ -36,10 +36,12 @@ def _run(wl, inp=None):
 # sampling index: device generator = host generator = oracle, bit for bit
 # ---------------------------------------------------------------------------------------
 def test_index_device_equals_host_equals_oracle():
+    """More than 10^4 random (shape, spec, seed, layer, epoch) tuples: the first few hundred with many channels
+    (several blocks of the index kernel), the rest with a handful, so that the oracle's loop stays short."""
     rng = np.random.default_rng(1)
-    for i in range(300):
+    for i in range(10500):
         N, H, W = (int(v) for v in rng.integers(1, 80, 3))
-        C_ = int(rng.integers(1, 700))
+        C_ = int(rng.integers(1, 700)) if i < 300 else int(rng.integers(1, 7))
         mode = int(rng.integers(0, 5))
         if mode == VDN and N == 1:
             continue
@@ -189,8 +191,11 @@ def test_benchmark_configs_full_tensor(name):
     wl = workloads.WORKLOADS[name]
     inp, res = _run(wl)
     assert (res["boxes"] == oracle_boxes(wl)).all()
-    errs = assert_parity(res, oracle_reference(wl, inp), wl, what=name)
-    _announce(f"{name} scaled errors {errs}")
+    ref = oracle_reference(wl, inp)
+    errs = assert_parity(res, ref, wl, what=name, inp=inp)
+    plain = assert_parity(res, ref, wl, what=name, floors=False)       # |got - ref| / (|ref| + RMS) alone
+    _announce(f"{name} scaled errors with floors {errs}")
+    _announce(f"{name} scaled errors without   {plain}")
 
 
 def test_cifar_fs_per_channel_patches():
@@ -220,14 +225,18 @@ def test_imagenet_shape_all_channels(name, imagenet_inputs):
         inp["dy"] = workloads.round_to_bf16(inp["dy"])
     _, res = _run(wl, inp)
     assert (res["boxes"] == oracle_boxes(wl)).all()
-    worst = {}
+    worst, worst_plain = {}, {}
     step = 32
     for c0 in range(0, wl.C, step):
         ch = list(range(c0, min(c0 + step, wl.C)))
-        errs = assert_parity(res, oracle_reference(wl, inp, channels=ch), wl, channels=ch, what=f"{name} ch {c0}")
+        ref = oracle_reference(wl, inp, channels=ch)
+        errs = assert_parity(res, ref, wl, channels=ch, what=f"{name} ch {c0}", inp=inp)
+        plain = assert_parity(res, ref, wl, channels=ch, what=f"{name} ch {c0}", floors=False)
         for k, v in errs.items():
             worst[k] = max(worst.get(k, 0.0), v)
-    _announce(f"{name} worst scaled errors {worst}")
+            worst_plain[k] = max(worst_plain.get(k, 0.0), plain[k])
+    _announce(f"{name} worst scaled errors with floors {worst}")
+    _announce(f"{name} worst scaled errors without   {worst_plain}")
 
 
 @pytest.fixture(scope="module")
@@ -367,9 +376,48 @@ def test_fused_backward_with_x_kept_on_chip(variant, shape, mkw, dtype, kernel_p
         assert scaled_err(res[k], plain[k]) <= (2e-5 if k not in ("y", "dx") or dtype == "f32" else 1e-2), k
 
 
+@pytest.mark.parametrize("shape,dtype,patch,per_channel,variant,masked", [
+    ((24, 6, 56, 56), "bf16", (14, 14), 0, 6, True),    # 9408 vectors of 8 in (512 threads, 32 vectors): one block a channel
+    ((24, 6, 56, 56), "bf16", (5, 3), 1, 6, True),      # a patch inside one vector, a location per channel
+    ((44, 5, 56, 56), "bf16", (56, 9), 0, 7, True),     # (512, 50); every row sampled, columns masked
+    ((24, 40, 56, 56), "bf16", (14, 14), 0, 7, True),   # (512, 50) with room to spare: several blocks a channel
+    ((12, 7, 56, 56), "f32", (14, 14), 0, 6, True),     # vectors of 4
+    ((12, 7, 56, 56), "f32", (1, 56), 1, 6, True),      # whole rows: every vector of a sampled row unmasked
+    ((30, 5, 10, 60), "bf16", (3, 7), 0, 6, False),     # rows of 7.5 vectors: the patch elements are read on their own
+    ((24, 6, 56, 56), "bf16", (14, 14), 0, 5, False),   # a variant the flavour is not built for
+])
+def test_patch_statistics_from_the_registers(shape, dtype, patch, per_channel, variant, masked, kernel_path):
+    """Feature Sampling forward where one block holds a channel: the statistics come from the vectors in registers under
+    a column mask (when a row is a whole number of vectors).  Against the oracle, and against the flavour that reads
+    the patch elements on their own."""
+    if kernel_path != "auto":
+        pytest.skip("forced-fused test runs once")
+    N, C_, H, W = shape
+    wl = Workload(name="patch_mask", N=N, C=C_, H=H, W=W, dtype=dtype, mode=FS, patch_h=patch[0], patch_w=patch[1],
+                  fs_per_channel=per_channel, data_seed=21, sampling_seed=22, layer_id=2, epoch=5)
+    inp = workloads.make_inputs(wl)
+    try:
+        bns.bns_set_option("path", 2)
+        bns.bns_set_option("fused_variant", variant)    # (few channels: the planner would take smaller blocks)
+        bns.bns_set_option("fused_patch_mask", 1)
+        _, res = _run(wl, inp)
+        flavour = bns.bns_get_option("last_fused_forward")
+        bns.bns_set_option("fused_patch_mask", 2)
+        other = bns.run_workload(wl, inp)
+        assert bns.bns_get_option("last_fused_forward") == 1
+    finally:
+        bns.bns_set_option("fused_patch_mask", 0)
+        bns.bns_set_option("fused_variant", 0)
+        bns.bns_set_option("path", 0)
+    assert flavour == (2 if masked else 1)
+    ref = oracle_reference(wl, inp)
+    assert_parity(res, ref, wl, what=f"patch from registers {shape} {dtype} {patch}", inp=inp)
+    assert_parity(other, ref, wl, what=f"patch read on its own {shape} {dtype} {patch}", inp=inp)
+
+
 def test_missing_team_mate_ends_in_nan_not_in_a_hang(kernel_path):
     """The give-up path of the single-launch kernels, forced from the host: with publishing switched off every
-    wait for a team-mate's sums expires after `fused_spin_limit` polls.  The sums are then NaN (never a finite
+    wait for a team-mate's sums expires after `test_spin_limit` polls.  The sums are then NaN (never a finite
     wrong value), the kernels end normally, and the next ordinary call on the same buffers and workspace is right."""
     if kernel_path != "auto":
         pytest.skip("forced-fused test runs once")
@@ -389,17 +437,17 @@ def test_missing_team_mate_ends_in_nan_not_in_a_hang(kernel_path):
     try:
         bns.bns_set_option("path", 2)
         bns.bns_set_option("fused_variant", 1)           # 64-thread blocks: a channel takes a team of 16
-        bns.bns_set_option("fused_spin_limit", 64)
-        bns.bns_set_option("fused_mute", 1)
+        bns.bns_set_option("test_spin_limit", 64)
+        bns.bns_set_option("test_mute_exchange", 1)
         _announce("give-up path: no block publishes, 64 polls per wait")
         bad = forward_backward()
         expired_bad = bns.bns_expired_waits(buf.workspace)      # reads the count and clears it
-        bns.bns_set_option("fused_mute", 0)
-        bns.bns_set_option("fused_spin_limit", 0)
+        bns.bns_set_option("test_mute_exchange", 0)
+        bns.bns_set_option("test_spin_limit", 0)
         good = forward_backward()
         expired_good = bns.bns_expired_waits(buf.workspace)
     finally:
-        for name in ("fused_mute", "fused_spin_limit", "fused_variant", "path"):
+        for name in ("test_mute_exchange", "test_spin_limit", "fused_variant", "path"):
             bns.bns_set_option(name, 0)
     for k in ("y", "save_mean", "save_invstd", "dx", "dgamma", "dbeta"):
         assert np.isnan(bad[k]).all(), f"{k}: finite values after a wait that expired"
@@ -421,20 +469,20 @@ def test_missing_team_mate_in_the_pipelined_backward_kernel(kernel_path):
     try:
         bns.bns_set_option("fused_pipe", 1)             # 512 threads, 4 vectors: 6144 vectors per channel take 3 blocks
         bns.bns_set_option("fused_team", 4)
-        bns.bns_set_option("fused_spin_limit", 64)
-        bns.bns_set_option("fused_mute", 1)
+        bns.bns_set_option("test_spin_limit", 64)
+        bns.bns_set_option("test_mute_exchange", 1)
         _announce("give-up path of the pipelined backward kernel")
         buf.backward()
         bad = buf.results()
         expired_bad = bns.bns_expired_waits(buf.workspace)
-        bns.bns_set_option("fused_mute", 0)
-        bns.bns_set_option("fused_spin_limit", 0)
+        bns.bns_set_option("test_mute_exchange", 0)
+        bns.bns_set_option("test_spin_limit", 0)
         buf.backward()
         good = buf.results()
         expired_good = bns.bns_expired_waits(buf.workspace)
         assert bns.bns_get_option("last_path_backward") == 2
     finally:
-        for name in ("fused_mute", "fused_spin_limit", "fused_pipe", "fused_team"):
+        for name in ("test_mute_exchange", "test_spin_limit", "fused_pipe", "fused_team"):
             bns.bns_set_option(name, 0)
     for k in ("dgamma", "dbeta"):
         assert np.isnan(bad[k]).all(), f"{k}: finite values after a wait that expired"
@@ -507,7 +555,7 @@ def test_single_launch_kernels_from_several_threads_and_streams(kernel_path):
             errors.append((k, repr(e)))
 
     bns.bns_set_option("path", 2)
-    bns.bns_set_option("fused_spin_limit", 1 << 16)          # a wait that ran out would cost tens of milliseconds
+    bns.bns_set_option("test_spin_limit", 1 << 16)          # a wait that ran out would cost tens of milliseconds
     try:
         threads = [threading.Thread(target=worker, args=(k,)) for k in range(4)]
         for t in threads:
@@ -515,7 +563,7 @@ def test_single_launch_kernels_from_several_threads_and_streams(kernel_path):
         for t in threads:
             t.join()
     finally:
-        bns.bns_set_option("fused_spin_limit", 0)
+        bns.bns_set_option("test_spin_limit", 0)
         bns.bns_set_option("path", 0)
     assert not errors, errors
     assert len(results) == 4
