@@ -121,6 +121,7 @@ template <typename T, int V, bool CONTIG>
 __global__ __launch_bounds__(kBlock) void nhwc_stats_partial_kernel(const T* __restrict__ x,
                                                                     Partial* __restrict__ partial, RowSet S, Tiling t) {
     __shared__ float lds[2 * kBlock * V];
+    __shared__ float piv[kWave * V];                             // at most 64 column lanes
     const Lane l = lane_of(t);
     const uint32_t i0 = uint32_t(l.k) * t.rows_per_block;
     const uint32_t i1 = min(i0 + t.rows_per_block, S.rows);      // i1 > i0: no block is empty
@@ -134,8 +135,9 @@ __global__ __launch_bounds__(kBlock) void nhwc_stats_partial_kernel(const T* __r
         a[e] = q[e] = p[e] = 0.f;
         A[e] = Q[e] = 0.0;
     }
-    if (l.live) {
-        const T* xc = x + size_t(l.cv) * V;
+    {
+        // (lanes past the last channel vector repeat it: they take part in the barrier below and write nothing)
+        const T* xc = x + size_t(l.live ? l.cv : t.CV - 1) * V;
         const uint32_t first = sampled_row(S, 0u);
         auto row_of = [&](uint32_t i) { return CONTIG ? first + i : sampled_row(S, i); };
         auto fetch = [&](Vec<T, V>(&v)[kStatRows], uint32_t i) {
@@ -173,16 +175,26 @@ __global__ __launch_bounds__(kBlock) void nhwc_stats_partial_kernel(const T* __r
         static_assert(kStatRows == 8, "the sums above are written out for eight rows");
         Vec<T, V> pv[kPivotRows], v0[kStatRows], v1[kStatRows];
         uint32_t i = i0 + uint32_t(l.ty);
+        // The pivot rows are the same few rows for every block of the launch: only the first row lane of a block
+        // reads them and hands the pivots to the others through LDS (every thread of every block reading them put
+        // thousands of requests on the few L2 channels that hold those rows).
+        if (l.ty == 0) {
 #pragma unroll
-        for (int j = 0; j < kPivotRows; ++j)     // no branches: all loads in flight together
-            pv[j].load(xc + size_t(row_of(min(uint32_t(j), S.pivot_rows - 1u))) * t.C);
+            for (int j = 0; j < kPivotRows; ++j)     // no branches: all loads in flight together
+                pv[j].load(xc + size_t(row_of(min(uint32_t(j), S.pivot_rows - 1u))) * t.C);
+        }
         fetch(v0, i);
+        if (l.ty == 0) {
 #pragma unroll
-        for (int j = 0; j < kPivotRows; ++j)
+            for (int j = 0; j < kPivotRows; ++j)
 #pragma unroll
-            for (int e = 0; e < V; ++e) p[e] += uint32_t(j) < S.pivot_rows ? pv[j].f[e] : 0.f;
+                for (int e = 0; e < V; ++e) p[e] += uint32_t(j) < S.pivot_rows ? pv[j].f[e] : 0.f;
 #pragma unroll
-        for (int e = 0; e < V; ++e) p[e] = coarse(p[e] * S.inv_pivot_rows);
+            for (int e = 0; e < V; ++e) piv[l.tx * V + e] = coarse(p[e] * S.inv_pivot_rows);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < V; ++e) p[e] = piv[l.tx * V + e];
         for (uint32_t b = 0; b < batches; b += 2u) {
             if (b + 1u < batches) fetch(v1, i + step);
             add(v0, i);
