@@ -830,10 +830,12 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
             // 512 or 448 threads, whichever cuts the channel into shares with less padding.  Measured at
             // 64x256x56x56 (fp32, 8 rounds): 115-117 us for every mode against 127-130 for the plain kernels; bf16
             // (6 rounds) 63-64 against 66 (Batch Sampling) and 71 (full BN).  With two rounds (128x64x32x32,
-            // 130x128x28x28) the plain kernels are faster, and so they are for a patch of every plane in bf16, where
-            // most vectors of 8 elements need the element-by-element test (70 against 68 us).
+            // 130x128x28x28) the plain kernels are faster, and so they are for a patch of every plane in bf16 whose
+            // rows are not a whole number of vectors: most vectors of 8 elements then need the test of row and
+            // column element by element (70 against 68 us).  With whole vectors per row the patch is a run of
+            // columns in each vector: 71 us against 73-74 for the plain kernel that keeps x in registers.
             const bns_box& sb = ip.shared;
-            const bool patch_bf16 = d.vec == 8 && (ip.per_channel || sb.w_cnt != d.W || sb.w0 != 0);
+            const bool patch_bf16 = d.vec == 8 && d.W % d.vec != 0 && (ip.per_channel || sb.w_cnt != d.W || sb.w0 != 0);
             PipePlan alt;
             if ((e = pipe_plan(pipe_default_variant(d), &pp)) != hipSuccess) return e;
             if (pipe_alternative_variant(d) >= 0) {
@@ -876,6 +878,7 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
     A.w_div = make_fastdiv(uint32_t(d.W));
     A.wv_div = make_fastdiv(uint32_t(d.W / d.vec > 0 ? d.W / d.vec : 1));       // used when W is a multiple of vec
     A.patch_stage = 0;
+    A.rows_whole = d.W % d.vec == 0;
     A.chw_div = make_fastdiv(uint32_t(d.C) * uint32_t(d.HW));       // C * HW < 2^31 (limits of bns_shape)
     A.C = d.C;
     A.W = d.W;

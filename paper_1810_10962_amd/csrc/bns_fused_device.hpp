@@ -134,6 +134,7 @@ struct FusedArgs {
     IndexParams ip;
     FastDiv hwv_div, w_div;
     FastDiv wv_div;             // vectors per row (rows that are a whole number of vectors)
+    int32_t rows_whole;         // W is a multiple of the vector width: no vector crosses a row
     int32_t patch_stage;        // forward, patch statistics from the registers: 1 = through the LDS staging array
     FastDiv chw_div;            // C * HW: element offset inside the tensor -> sample (pipelined kernel)
     int32_t C, W, HW;

@@ -230,13 +230,26 @@ struct BackwardPipe {
                         uint32_t h = fdiv(e0, A.w_div);
                         uint32_t w = e0 - h * uint32_t(A.W);
                         const bool n_in = n >= uint32_t(b.n0) && n < uint32_t(b.n0 + b.n_cnt);
+                        if (A.rows_whole) {
+                            // a row is a whole number of vectors: the vector lies in one row, and the elements of S
+                            // in it are a run [lo, hi) of its columns
+                            const bool row_in = n_in && h - uint32_t(b.h0) < uint32_t(b.h_cnt);
+                            const int32_t lo = row_in ? max(b.w0 - int32_t(w), 0) : V;
+                            const int32_t hi = min(b.w0 + b.w_cnt - int32_t(w), V);
 #pragma unroll
-                        for (int e = 0; e < V; ++e) {
-                            const float corr = (n_in && in_hw(b, h, w)) ? fmaf(k2, fx[e] - mu, k1) : 0.f;
-                            f[e] = fmaf(a, f[e], -corr);
-                            if (++w == uint32_t(A.W)) {
-                                w = 0;
-                                ++h;
+                            for (int e = 0; e < V; ++e) {
+                                const float corr = (e >= lo && e < hi) ? fmaf(k2, fx[e] - mu, k1) : 0.f;
+                                f[e] = fmaf(a, f[e], -corr);
+                            }
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < V; ++e) {
+                                const float corr = (n_in && in_hw(b, h, w)) ? fmaf(k2, fx[e] - mu, k1) : 0.f;
+                                f[e] = fmaf(a, f[e], -corr);
+                                if (++w == uint32_t(A.W)) {
+                                    w = 0;
+                                    ++h;
+                                }
                             }
                         }
                     }
