@@ -803,8 +803,10 @@ hipError_t launch_fused(const Dims& d, const IndexParams& ip, bool backward, con
             for (long T = Tmin; T <= 2 * Tmin && T <= Tmax; ++T) {
                 const long teams = blocks / T < cg ? blocks / T : cg;
                 const long rounds = (cg + teams - 1) / teams;
-                // a round lasts as long as its busiest member's share (whole chunks) plus the exchange
-                const double cost = double(rounds) * (double((chunks + T - 1) / T) + 2.0) * double(nt);
+                // a round lasts as long as its busiest member's share (whole chunks) plus the exchange, whose wait and
+                // sum grow with the team (128 per member: between the two shapes it was fitted to -- 64x256x56x56,
+                // teams of 16 x 448 threads, 1 us faster than 14 x 512; 64x64x112x112, 56 x 512 5 us faster than 64 x 448)
+                const double cost = double(rounds) * ((double((chunks + T - 1) / T) + 2.0) * double(nt) + 128.0 * double(T));
                 if (bestT == 0 || cost < best_cost) {
                     bestT = T;
                     best_cost = cost;
