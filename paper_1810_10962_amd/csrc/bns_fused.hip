@@ -49,8 +49,11 @@ namespace {
 //      whole number of vectors; it then costs what full BN costs instead of a second, scattered read.
 // MIXED: Eq. 4 -- a second pair of sums over the virtual set (samples [0, n_v), always whole planes, taken
 // from the registers), a second exchange, and the blend of the two (E, Var) pairs.
+// Eq. 4 at (512 threads, up to 16 vectors) runs two blocks per compute unit, i.e. four waves per SIMD and at most 128
+// registers; the compiler is told so, because left alone it takes 150 and the second block is gone (130x128x28x28,
+// 7x7 patch + 2 virtual samples: forward 34 -> 29.7 us, a few registers spilled included).
 template <typename T, int V, int KMAX, int NT, int PATCH, bool MIXED>
-__global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
+__global__ __launch_bounds__(NT, (MIXED && NT == 512 && KMAX <= 16) ? 4 : 1) void fused_forward_kernel(FusedArgs A) {
     typedef RawVec<T, V> RV;
     __shared__ float red[2 * (NT / kWave)];
     __shared__ float team_lds[2 * kMaxTeam];
@@ -217,7 +220,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs A) {
                 s2 = fmaf(d, d, s2);
             }
             // what is left of the patch (most of it when one block holds the channel), a few loads in flight at a time
-            constexpr int kBatch = KMAX >= 50 ? 2 : KMAX >= 32 ? 4 : 8;      // (registers)
+            constexpr int kBatch = KMAX >= 50 ? 2 : KMAX >= 32 ? 4 : KMAX >= 16 ? 1 : 8;      // (registers)
             for (uint32_t q = q0 + uint32_t(kPatchLoads) * step; q < A.s_cnt; q += uint32_t(kBatch) * step) {
                 float t[kBatch];
 #pragma unroll
