@@ -54,7 +54,10 @@ def default_path_kernels(wl, dirs, bns):
     fused_bwd = {1: "fused_backward_kernel", 2: "fused_backward_kernel", 3: "fused_backward_pipe_kernel"}
     bwd = {"fused": [fused_bwd.get(bns.bns_get_option("last_fused_backward"), "fused_backward_kernel")],
            "one-launch": [pre + "small_backward_kernel"],
-           "streaming": [pre + "reduce_partial_kernel", pre + "reduce_finalize_kernel", pre + "dx_kernel"]}[dirs["backward_path"]]
+           "streaming": [pre + "reduce_partial_kernel", pre + "reduce_finalize_kernel", pre + "dx_kernel"],
+           # N x H x W x C: dx outside S written by the reduction kernel, the rows of S by a kernel of their own
+           "streaming-split": ["nhwc_reduce_outside_kernel", "nhwc_reduce_finalize_kernel", "nhwc_dx_rows_kernel"],
+           }[dirs["backward_path"]]
     return fwd, bwd
 
 
@@ -156,7 +159,7 @@ def time_directions(ds, steps, torch, bns):
         b.backward()
         e[2].record()
     torch.cuda.synchronize()
-    paths = {1: "streaming", 2: "fused", 3: "one-launch"}
+    paths = {1: "streaming", 2: "fused", 3: "one-launch", 4: "streaming-split"}
     c0 = bns.bns_get_option("launch_count")
     ds.bufs[0].forward()
     c1 = bns.bns_get_option("launch_count")
@@ -303,6 +306,11 @@ def main():
         cands.append((bwd_kernels[0], dirs["backward"], (3 + r if plain else 3) * tensor, alg["reduce"] + alg["dx"],
                       "single-launch backward: dy and x read once, dx written once, 3e bytes per element"
                       + (" + x again on S, r e" if plain else "")))
+    elif dirs["backward_path"] == "streaming-split":
+        # three launches timed as one (the event pair is around bns_backward): sums + dx outside S, finalize, dx on S
+        cands.append((bwd_kernels[0], dirs["backward"], (3 + 2 * r) * tensor, alg["reduce"] + alg["dx"],
+                      "backward in three launches, timed together: dy and x read once and dx written outside S by the "
+                      "reduction kernel (3 - r) e, then dy, x, dx on the rows of S, 3 r e: (3 + 2r) e per element"))
     else:
         cands += [(bwd_kernels[0], stages["reduce"], alg["reduce"], alg["reduce"], "dy and x read once: 2e per element"),
                   (bwd_kernels[-1], stages["dx"], alg["dx"], alg["dx"], "dy read, dx written, x read on S: (2+r)e per element")]
@@ -315,6 +323,8 @@ def main():
     kernel_name, dom_s, dom_bytes, two_pass_bytes, dom_note = max(cands, key=lambda c: c[1])
     achieved = dom_bytes / dom_s / 1e9
     traffic = table.get(kernel_name)
+    if dirs["backward_path"] == "streaming-split" and kernel_name == bwd_kernels[0]:
+        traffic = sum(table[k] for k in bwd_kernels) if all(k in table for k in bwd_kernels) else None
     roofline = dict(bound="hbm", kernel=kernel_name, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic,
                     achieved_by_counters=round(traffic / dom_s / 1e9, 1) if traffic else None,

@@ -302,6 +302,9 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  *                    one group before the next                                   (1..C)
  *   "nhwc_blocks"    blocks that an N x H x W x C reduction launch aims for      (1..8192)
  *   "nhwc_ew_rows"   rows per thread in the N x H x W x C element-wise kernels   (1..2^20)
+ *   "nhwc_split_dx"  N x H x W x C backward: the reduction kernel also writes dx on the rows outside S (Eq. 6 needs
+ *                    no sum there), a second kernel the rows of S: 1 always, 2 never; 0: when S is at most half
+ *                    of the rows
  *   "nhwc_small"     2: small N x H x W x C tensors also take the streaming kernels (by default one launch
  *                    per direction does everything when a thread would walk at most 16 rows)
  *   "norm_unroll", "dx_unroll", "reduce_unroll"   128-bit accesses per thread    (1, 2, 4)
@@ -321,7 +324,8 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
 bns_status bns_set_option(const char* name, int32_t value);
 /* Current value of an option (as set, 0 = automatic); also, kept per calling thread,
  * "last_path_forward" / "last_path_backward": 1 if this thread's last bns_forward / bns_backward took the streaming kernels, 2 if the fused one, 3 if the
- * one-launch kernel for small N x H x W x C tensors; "last_fused_backward": which fused backward kernel that was
+ * one-launch kernel for small N x H x W x C tensors, 4 (backward, N x H x W x C) the streaming kernels with dx split
+ * between the reduction kernel and a kernel for the rows of S ("nhwc_split_dx"); "last_fused_backward": which fused backward kernel that was
  * (1 plain, 2 x kept in registers, 3 pipelined); "last_fused_forward": 2 if the fused forward kernel took the
  * statistics of a patch from the registers (see "fused_patch_mask"), else 1; "launch_count": kernels launched by the library since it was
  * loaded, modulo 2^31 (benchmarks report launches per call from its differences).

@@ -25,7 +25,8 @@ std::atomic<int32_t> g_splits_stats{0};
 std::atomic<int32_t> g_splits_reduce{0};
 std::atomic<int32_t> g_channel_group{0};
 // What the calling thread's last forward / backward call launched: 1 = streaming kernels,
-// 2 = fused single-launch kernel, 3 = one-launch kernel for small N x H x W x C tensors.
+// 2 = fused single-launch kernel, 3 = one-launch kernel for small N x H x W x C tensors, 4 = streaming kernels with dx
+// split between the reduction kernel (rows outside S) and a kernel for the rows of S (N x H x W x C).
 thread_local int32_t t_last_path_forward = 0;
 thread_local int32_t t_last_path_backward = 0;
 
@@ -77,6 +78,7 @@ const TuningEntry kTuningTable[] = {
     {"nhwc_blocks", &Tuning::nhwc_blocks, kNhwcBlocksMax, 0, false},
     {"nhwc_ew_rows", &Tuning::nhwc_ew_rows, 1 << 20, 0, false},
     {"nhwc_small", &Tuning::nhwc_small, 2, 0, false},
+    {"nhwc_split_dx", &Tuning::nhwc_split_dx, 2, 0, false},
 };
 
 int stats_splits(const Dims& d, const IndexParams& ip, int cg) {
@@ -348,6 +350,15 @@ bns_status backward_impl(const bns_shape* shape, const bns_spec* spec, uint64_t 
             return dev(se);
         }
         t_last_path_backward = 1;
+        // Eq. 6 outside S needs none of the sums: when S is at most half of the rows, the reduction kernel writes
+        // dx there while it has dy in registers, and only the rows of S are left for after the sums
+        const bns_box& sb = ip.shared;
+        const uint64_t s_rows = uint64_t(sb.n_cnt) * uint64_t(sb.h_cnt) * uint64_t(sb.w_cnt);
+        const int split = g_tuning.nhwc_split_dx;
+        if (split == 1 || (split == 0 && 2u * s_rows <= uint64_t(d.N) * uint64_t(d.HW))) {
+            t_last_path_backward = 4;
+            return dev(launch_nhwc_backward_split(d, sb, x, dy, gamma, save_mean, save_invstd, ws, dgamma, dbeta, dx, st));
+        }
         if (launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, ws, dgamma, dbeta, st) != hipSuccess) return BNS_EDEVICE;
         return dev(launch_nhwc_dx(d, ip.shared, x, dy, gamma, save_mean, save_invstd, dgamma, dbeta, dx, st));
     }

@@ -57,6 +57,7 @@ struct Tuning {
     TuneInt nhwc_blocks{0};                 // blocks an N x H x W x C reduction aims for (default kNhwcBlocks)
     TuneInt nhwc_small{0};                  // 2: never take the one-launch kernels for small N x H x W x C tensors
     TuneInt nhwc_ew_rows{0};                // rows per row lane in its element-wise kernels (default kNhwcEwRows)
+    TuneInt nhwc_split_dx{0};               // backward writes dx outside S from the reduction kernel: 1 always, 2 never, 0 when S is at most half
     // For the library's own tests of the give-up path only; a caller has no use for them.
     TuneInt test_spin_limit{0};             // polls a team member waits for a team-mate before giving up (default 2^21)
     TuneInt test_mute_exchange{0};          // 1: no member publishes its sums, so every wait runs out
@@ -167,6 +168,11 @@ hipError_t launch_nhwc_normalize(const Dims& d, const void* x, const float* gamm
                                  const float* invstd, void* y, hipStream_t st, float var_eps = -1.f);
 hipError_t launch_nhwc_reduce(const Dims& d, const void* x, const void* dy, const float* mean, const float* invstd,
                               Partial* partial, float* dgamma, float* dbeta, hipStream_t st);
+// Backward with dx split by the two branches of Eq. 6: the reduction kernel also writes dx outside S, a second
+// element-wise kernel takes the rows of S after the sums ((3 + 2r) e bytes per element instead of (4 + r) e).
+hipError_t launch_nhwc_backward_split(const Dims& d, const bns_box& b, const void* x, const void* dy, const float* gamma,
+                                      const float* mean, const float* invstd, Partial* partial, float* dgamma,
+                                      float* dbeta, void* dx, hipStream_t st);
 hipError_t launch_nhwc_dx(const Dims& d, const bns_box& b, const void* x, const void* dy, const float* gamma,
                           const float* mean, const float* invstd, const float* dgamma, const float* dbeta, void* dx,
                           hipStream_t st);

@@ -213,27 +213,47 @@ __global__ __launch_bounds__(kBlock) void nhwc_stats_partial_kernel(const T* __r
     write_partials<V>(a, q, lds, t, l, partial);
 }
 
+struct RowBox {                 // membership of a row in S
+    uint32_t n0, n1, h0, h1, w0, w1;
+    FastDiv hw_div, w_div;
+};
+
+__device__ __forceinline__ bool row_in(const RowBox& b, uint32_t row) {
+    const uint32_t n = fdiv(row, b.hw_div);
+    const uint32_t rem = row - n * b.hw_div.d;
+    const uint32_t h = fdiv(rem, b.w_div);
+    const uint32_t w = rem - h * b.w_div.d;
+    return n >= b.n0 && n < b.n1 && h >= b.h0 && h < b.h1 && w >= b.w0 && w < b.w1;
+}
+
 // Backward sums of Eq. 5 over all M rows: partial[k][c] = (sum dy, sum dy * (x - mean_c)).
-template <typename T, int V>
-__global__ __launch_bounds__(kBlock) void nhwc_reduce_partial_kernel(const T* __restrict__ x, const T* __restrict__ dy,
-                                                                     const float* __restrict__ mean,
-                                                                     Partial* __restrict__ partial, Tiling t,
-                                                                     uint32_t M) {
-    __shared__ float lds[2 * kBlock * V];
+// OUTSIDE: the kernel also writes dx on the rows that are NOT in S.  The second branch of Eq. 6, dx = gamma r dy,
+// needs none of the sums, and dy of those rows is in registers here anyway; what is left for after the sums are
+// the rows of S alone (nhwc_dx_rows_kernel).  Backward then has to move (3 + 2r) e bytes per element instead of (4 + r) e.
+template <typename T, int V, bool OUTSIDE>
+__device__ __forceinline__ void reduce_partial_body(const T* __restrict__ x, const T* __restrict__ dy,
+                                                    const float* __restrict__ mean, Partial* __restrict__ partial,
+                                                    const Tiling& t, uint32_t M, T* __restrict__ dx,
+                                                    const float* __restrict__ gamma, const float* __restrict__ invstd,
+                                                    const RowBox& B, float* lds) {
     const Lane l = lane_of(t);
     const uint32_t r0 = uint32_t(l.k) * t.rows_per_block;
     const uint32_t r1 = min(r0 + t.rows_per_block, M);
     const uint32_t TY = uint32_t(l.TY);
-    float a[V], q[V], mu[V];
+    float a[V], q[V], mu[V], sc[V];
     double A[V], Q[V];
 #pragma unroll
     for (int e = 0; e < V; ++e) {
-        a[e] = q[e] = mu[e] = 0.f;
+        a[e] = q[e] = mu[e] = sc[e] = 0.f;
         A[e] = Q[e] = 0.0;
     }
     if (l.live) {
 #pragma unroll
         for (int e = 0; e < V; ++e) mu[e] = mean[l.cv * V + e];
+        if (OUTSIDE) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) sc[e] = gamma[l.cv * V + e] * invstd[l.cv * V + e];      // a = gamma r
+        }
         const size_t col = size_t(l.cv) * V;
         uint32_t r = r0 + uint32_t(l.ty);
         for (; r + TY < r1; r += 2u * TY) {
@@ -249,6 +269,17 @@ __global__ __launch_bounds__(kBlock) void nhwc_reduce_partial_kernel(const T* __
                 A[e] += double(g[0].f[e] + g[1].f[e]);
                 Q[e] += double(fmaf(g[1].f[e], v[1].f[e] - mu[e], g[0].f[e] * (v[0].f[e] - mu[e])));
             }
+            if (OUTSIDE) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const uint32_t row = r + uint32_t(u) * TY;
+                    if (!row_in(B, row)) {
+#pragma unroll
+                        for (int e = 0; e < V; ++e) g[u].f[e] *= sc[e];
+                        g[u].store_nt(dx + size_t(row) * t.C + col);
+                    }
+                }
+            }
         }
         for (; r < r1; r += TY) {
             const size_t off = size_t(r) * t.C + col;
@@ -260,6 +291,11 @@ __global__ __launch_bounds__(kBlock) void nhwc_reduce_partial_kernel(const T* __
                 A[e] += double(g.f[e]);
                 Q[e] += double(g.f[e] * (v.f[e] - mu[e]));
             }
+            if (OUTSIDE && !row_in(B, r)) {
+#pragma unroll
+                for (int e = 0; e < V; ++e) g.f[e] *= sc[e];
+                g.store_nt(dx + off);
+            }
         }
 #pragma unroll
         for (int e = 0; e < V; ++e) {
@@ -268,6 +304,24 @@ __global__ __launch_bounds__(kBlock) void nhwc_reduce_partial_kernel(const T* __
         }
     }
     write_partials<V>(a, q, lds, t, l, partial);
+}
+
+template <typename T, int V>
+__global__ __launch_bounds__(kBlock) void nhwc_reduce_partial_kernel(const T* __restrict__ x, const T* __restrict__ dy,
+                                                                     const float* __restrict__ mean,
+                                                                     Partial* __restrict__ partial, Tiling t, uint32_t M) {
+    __shared__ float lds[2 * kBlock * V];
+    reduce_partial_body<T, V, false>(x, dy, mean, partial, t, M, nullptr, nullptr, nullptr, RowBox{}, lds);
+}
+
+template <typename T, int V>
+__global__ __launch_bounds__(kBlock) void nhwc_reduce_outside_kernel(const T* __restrict__ x, const T* __restrict__ dy,
+                                                                     const float* __restrict__ mean,
+                                                                     Partial* __restrict__ partial, Tiling t, uint32_t M,
+                                                                     T* __restrict__ dx, const float* __restrict__ gamma,
+                                                                     const float* __restrict__ invstd, RowBox B) {
+    __shared__ float lds[2 * kBlock * V];
+    reduce_partial_body<T, V, true>(x, dy, mean, partial, t, M, dx, gamma, invstd, B, lds);
 }
 
 // Finalize kernels: a block takes kFinCh neighbouring channels; thread (ch, kl) adds the partials
@@ -452,19 +506,6 @@ __global__ __launch_bounds__(kBlock) void nhwc_normalize_kernel(const T* __restr
     }
 }
 
-struct RowBox {                 // membership of a row in S
-    uint32_t n0, n1, h0, h1, w0, w1;
-    FastDiv hw_div, w_div;
-};
-
-__device__ __forceinline__ bool row_in(const RowBox& b, uint32_t row) {
-    const uint32_t n = fdiv(row, b.hw_div);
-    const uint32_t rem = row - n * b.hw_div.d;
-    const uint32_t h = fdiv(rem, b.w_div);
-    const uint32_t w = rem - h * b.w_div.d;
-    return n >= b.n0 && n < b.n1 && h >= b.h0 && h < b.h1 && w >= b.w0 && w < b.w1;
-}
-
 // Eq. 6 on every element: rows outside S scale dy, rows in S also read x and take the 1/s terms.
 //   dx = a g                                   a  = gamma r
 //   dx = a g - (k1 (x - mean) + k2)            k1 = a r dgamma / s,  k2 = a dbeta / s
@@ -528,6 +569,62 @@ __global__ __launch_bounds__(kBlock) void nhwc_dx_kernel(const T* __restrict__ x
             for (int e = 0; e < V; ++e) g.f[e] *= a[e];
         }
         g.store_nt(dx + size_t(r) * t.C + col);
+    }
+}
+
+// Eq. 6, first branch, on the rows of S alone (sampled row i of the k-th share, as in the statistics kernel); the
+// other rows were written by nhwc_reduce_outside_kernel.
+template <typename T, int V, bool CONTIG>
+__global__ __launch_bounds__(kBlock) void nhwc_dx_rows_kernel(const T* __restrict__ x, const T* __restrict__ dy,
+                                                              T* __restrict__ dx, const float* __restrict__ gamma,
+                                                              const float* __restrict__ mean,
+                                                              const float* __restrict__ invstd,
+                                                              const float* __restrict__ dgamma,
+                                                              const float* __restrict__ dbeta, RowSet S, Tiling t,
+                                                              float inv_s) {
+    const Lane l = lane_of(t);
+    if (!l.live) return;
+    const uint32_t i0 = uint32_t(l.k) * t.rows_per_block;
+    const uint32_t i1 = min(i0 + t.rows_per_block, S.rows);
+    const uint32_t TY = uint32_t(l.TY);
+    float a[V], mu[V], k1[V], k2[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        const int c = l.cv * V + e;
+        const float r = invstd[c];
+        a[e] = gamma[c] * r;
+        mu[e] = mean[c];
+        k1[e] = a[e] * inv_s * (dgamma[c] * r);
+        k2[e] = a[e] * inv_s * dbeta[c];
+    }
+    const size_t col = size_t(l.cv) * V;
+    const uint32_t first = sampled_row(S, 0u);
+    auto row_of = [&](uint32_t i) { return CONTIG ? first + i : sampled_row(S, i); };
+    uint32_t i = i0 + uint32_t(l.ty);
+    for (; i + 3u * TY < i1; i += 4u * TY) {
+        Vec<T, V> g[4], v[4];
+        size_t off[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            off[u] = size_t(row_of(i + uint32_t(u) * TY)) * t.C + col;
+            g[u].load_nt(dy + off[u]);
+            v[u].load_nt(x + off[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) g[u].f[e] = fmaf(a[e], g[u].f[e], -fmaf(k1[e], v[u].f[e] - mu[e], k2[e]));
+            g[u].store_nt(dx + off[u]);
+        }
+    }
+    for (; i < i1; i += TY) {
+        const size_t off = size_t(row_of(i)) * t.C + col;
+        Vec<T, V> g, v;
+        g.load_nt(dy + off);
+        v.load_nt(x + off);
+#pragma unroll
+        for (int e = 0; e < V; ++e) g.f[e] = fmaf(a[e], g.f[e], -fmaf(k1[e], v.f[e] - mu[e], k2[e]));
+        g.store_nt(dx + off);
     }
 }
 
@@ -981,6 +1078,40 @@ hipError_t launch_nhwc_reduce(const Dims& d, const void* x, const void* dy, cons
         if (e != hipSuccess) return e;
         BNS_LAUNCH(nhwc_reduce_finalize_kernel, dim3(ceil_div_u(uint32_t(d.C), kFinCh)), dim3(kBlock), 0, st,
                    partial, d.C, t.splits, invstd, dgamma, dbeta);
+        return hipGetLastError();
+    });
+}
+
+// The whole backward pass with dx split by Eq. 6's two branches: sums + dx outside S, finalize, dx on S.
+hipError_t launch_nhwc_backward_split(const Dims& d, const bns_box& b, const void* x, const void* dy, const float* gamma,
+                                      const float* mean, const float* invstd, Partial* partial, float* dgamma,
+                                      float* dbeta, void* dx, hipStream_t st) {
+    const uint32_t M = uint32_t(d.N) * uint32_t(d.HW);
+    const Tiling t = make_tiling(d, M);      // the tiling of launch_nhwc_reduce: same partials, same sums, bit for bit
+    if (!fits_region(d, t)) return hipErrorInvalidValue;
+    const RowBox B = make_rowbox(d, b);
+    const RowSet S = make_rowset(d, b);
+    const Tiling ts = make_tiling(d, S.rows, 0, true);
+    const double s = double(b.n_cnt) * double(b.h_cnt) * double(b.w_cnt);
+    return dispatch_nhwc(d, [&](auto ty, auto vt) {
+        using T = decltype(ty);
+        constexpr int V = decltype(vt)::value;
+        BNS_LAUNCH((nhwc_reduce_outside_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st,
+                   static_cast<const T*>(x), static_cast<const T*>(dy), mean, partial, t, M, static_cast<T*>(dx), gamma,
+                   invstd, B);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        BNS_LAUNCH(nhwc_reduce_finalize_kernel, dim3(ceil_div_u(uint32_t(d.C), kFinCh)), dim3(kBlock), 0, st,
+                   partial, d.C, t.splits, invstd, dgamma, dbeta);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if (S.contiguous)
+            BNS_LAUNCH((nhwc_dx_rows_kernel<T, V, true>), dim3(grid_of(ts)), dim3(kBlock), 0, st, static_cast<const T*>(x),
+                       static_cast<const T*>(dy), static_cast<T*>(dx), gamma, mean, invstd, dgamma, dbeta, S, ts,
+                       float(1.0 / s));
+        else
+            BNS_LAUNCH((nhwc_dx_rows_kernel<T, V, false>), dim3(grid_of(ts)), dim3(kBlock), 0, st, static_cast<const T*>(x),
+                       static_cast<const T*>(dy), static_cast<T*>(dx), gamma, mean, invstd, dgamma, dbeta, S, ts,
+                       float(1.0 / s));
         return hipGetLastError();
     });
 }

@@ -306,7 +306,7 @@ void host_functions() {
         bns_set_option("path", INT32_MAX) != BNS_EINVAL || bns_set_option("path", INT32_MIN) != BNS_EINVAL)
         ++g_failures, fprintf(stderr, "options\n");
     const char* names[] = {"path", "fused_variant", "fused_pipe", "fused_team", "fused_coop", "fused_keep_x", "fused_patch_mask", "split_statistics",
-                           "splits_stats", "splits_reduce", "channel_group", "nhwc_blocks", "nhwc_ew_rows", "nhwc_small",
+                           "splits_stats", "splits_reduce", "channel_group", "nhwc_blocks", "nhwc_ew_rows", "nhwc_small", "nhwc_split_dx",
                            "norm_unroll", "dx_unroll", "reduce_unroll", "norm_nt", "dx_nt", "reduce_nt", "test_spin_limit",
                            "test_mute_exchange"};
     for (const char* n : names) {

@@ -193,7 +193,38 @@ def test_bit_identical_reruns_and_stage_calls():
     s = buf.results()
     for k in a:
         assert (a[k] == s[k]).all(), k
-    assert bns.bns_get_option("last_path_forward") == 1 and bns.bns_get_option("last_path_backward") == 1
+    # (the whole-call backward wrote dx outside S from its reduction kernel; the stage calls cannot: same bits)
+    assert bns.bns_get_option("last_path_forward") == 1 and bns.bns_get_option("last_path_backward") == 4
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape,mkw", [
+    ((16, 40, 12, 12), dict(mode=BS, n_s=3)),                       # S a run of rows in the middle
+    ((16, 40, 12, 12), dict(mode=FS, patch_h=5, patch_w=3)),        # S short runs of rows in every sample
+    ((9, 7, 7, 7), dict(mode=NS, n_s=8)),                           # S most of the rows, scalar columns
+    ((6, 300, 20, 20), dict(mode=VDN, n_s=1)),                      # more than one tile of channels
+    ((5, 16, 6, 6), dict(mode=FULL)),                               # nothing outside S
+    ((40, 64, 28, 28), dict(mode=FS, patch_h=1, patch_w=1)),        # one row per sample
+])
+def test_backward_with_dx_split_by_the_branches_of_eq_6(shape, mkw, dtype, kernel_choice):
+    """Backward with dx on the rows outside S written by the reduction kernel and the rows of S by a kernel of their
+    own: the same expressions as the one-kernel dx pass, so the same bits, whichever way the split is forced."""
+    if kernel_choice != "streaming":
+        pytest.skip("the streaming kernels are the subject")
+    N, C_, H, W = shape
+    wl = Workload(name="split_dx", N=N, C=C_, H=H, W=W, dtype=dtype, layout="nhwc", data_seed=31, sampling_seed=32,
+                  layer_id=4, epoch=1, **mkw)
+    inp = workloads.make_inputs(wl)
+    try:
+        bns.bns_set_option("nhwc_split_dx", 1)
+        _, split = _run(wl, inp)
+        bns.bns_set_option("nhwc_split_dx", 2)
+        whole = bns.run_workload(wl, inp)
+    finally:
+        bns.bns_set_option("nhwc_split_dx", 0)
+    assert_parity(split, oracle_reference(wl, inp), wl, what=f"split dx {shape} {mkw} {dtype}", inp=inp)
+    for k in ("dx", "dgamma", "dbeta"):
+        assert (split[k] == whole[k]).all(), f"{k}: split and one-kernel dx differ"
 
 
 def test_same_results_as_the_other_layout():
@@ -274,11 +305,12 @@ def test_small_tensors_take_one_launch_per_direction(kernel_choice):
     inp = workloads.make_inputs(wl)
     res = bns.run_workload(wl, inp)
     want = 3 if kernel_choice == "auto" else 1
-    assert bns.bns_get_option("last_path_forward") == want and bns.bns_get_option("last_path_backward") == want
+    want_b = 3 if kernel_choice == "auto" else 4                  # streaming: S is 16 of 196 rows, dx is split
+    assert bns.bns_get_option("last_path_forward") == want and bns.bns_get_option("last_path_backward") == want_b
     assert_parity(res, oracle_reference(wl, inp), wl, what="micro_a_fs nhwc", inp=inp)
     big = workloads.WORKLOADS["cifar_fs"].replace(layout="nhwc", N=16)
     bns.run_workload(big, workloads.make_inputs(big))
-    assert bns.bns_get_option("last_path_forward") == 1 and bns.bns_get_option("last_path_backward") == 1
+    assert bns.bns_get_option("last_path_forward") == 1 and bns.bns_get_option("last_path_backward") == 4
 
 
 MIXED_MODES = [
