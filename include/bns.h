@@ -304,11 +304,17 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  *   "nhwc_ew_rows"   rows per thread in the N x H x W x C element-wise kernels   (1..2^20)
  *   "nhwc_split_dx"  N x H x W x C backward: the reduction kernel also writes dx on the rows outside S (Eq. 6 needs
  *                    no sum there), a second kernel the rows of S: 1 always, 2 never; 0: when S is at most half
- *                    of the rows
+ *                    of the rows and the tensor too large for "cache_reuse"
+ *   "cache_reuse"    streaming kernels: a first pass (statistics; the sums of Eq. 5) loads what the pass after it
+ *                    (Eq. 1; Eq. 6) reads again without the non-temporal hint, so that it stays in the device's
+ *                    memory-side cache: 1 always, 2 never; 0: when it fits there (224 MB).  Results do not
+ *                    depend on it.
  *   "nhwc_small"     2: small N x H x W x C tensors also take the streaming kernels (by default one launch
  *                    per direction does everything when a thread would walk at most 16 rows)
  *   "norm_unroll", "dx_unroll", "reduce_unroll"   128-bit accesses per thread    (1, 2, 4)
- *   "norm_nt", "dx_nt", "reduce_nt"   non-temporal access mask + 1: bit 0 loads, bit 1 stores
+ *   "norm_nt", "dx_nt"   non-temporal access mask + 1: bit 0 loads, bit 1 stores
+ *   "reduce_nt"      the same for the backward reduction: bit 0 loads of x, bit 1 loads of dy (overrides "cache_reuse"
+ *                    there)
  * Two more exist for the library's own tests only; they make results wrong on purpose and a caller has no
  * use for them:
  *   "test_spin_limit"    polls a block of a fused kernel waits for a team-mate's sums before it gives up

@@ -64,7 +64,7 @@ struct TuningEntry {
 const TuningEntry kTuningTable[] = {
     {"norm_unroll", &Tuning::norm_unroll, 4, 0, true},     {"norm_nt", &Tuning::norm_nt, 4, 1, false},
     {"dx_unroll", &Tuning::dx_unroll, 4, 0, true},         {"dx_nt", &Tuning::dx_nt, 4, 1, false},
-    {"reduce_unroll", &Tuning::reduce_unroll, 4, 0, true}, {"reduce_nt", &Tuning::reduce_nt, 2, 1, false},
+    {"reduce_unroll", &Tuning::reduce_unroll, 4, 0, true}, {"reduce_nt", &Tuning::reduce_nt, 4, 1, false},
     {"path", &Tuning::path, 2, 0, false},
     {"fused_variant", &Tuning::fused_variant, 7, 0, false},
     {"fused_pipe", &Tuning::fused_pipe, 16, 0, false},
@@ -79,6 +79,7 @@ const TuningEntry kTuningTable[] = {
     {"nhwc_ew_rows", &Tuning::nhwc_ew_rows, 1 << 20, 0, false},
     {"nhwc_small", &Tuning::nhwc_small, 2, 0, false},
     {"nhwc_split_dx", &Tuning::nhwc_split_dx, 2, 0, false},
+    {"cache_reuse", &Tuning::cache_reuse, 2, 0, false},
 };
 
 int stats_splits(const Dims& d, const IndexParams& ip, int cg) {
@@ -117,9 +118,9 @@ bns_status stats_range(const Dims& d, const IndexParams& ip, const void* x, floa
 
 bns_status reduce_range(const Dims& d, const void* x, const void* dy, const float* save_mean,
                         const float* save_invstd, float* dgamma, float* dbeta, Partial* ws, int c0, int cg,
-                        hipStream_t st) {
+                        bool x_again, hipStream_t st) {
     const int splits = reduce_splits(d, cg);
-    if (launch_reduce_partial(d, x, dy, save_mean, ws, splits, c0, cg, st) != hipSuccess) return BNS_EDEVICE;
+    if (launch_reduce_partial(d, x, dy, save_mean, ws, splits, c0, cg, x_again, st) != hipSuccess) return BNS_EDEVICE;
     return dev(launch_reduce_finalize(d, ws, splits, c0, cg, save_invstd, dgamma, dbeta, st));
 }
 
@@ -288,9 +289,10 @@ bns_status bns_backward_reduce(const bns_shape* shape, const void* x, const void
     if (!aligned16(x) || !aligned16(dy) || !aligned16(workspace)) return BNS_EINVAL;
     if (workspace_bytes < workspace_need(d)) return BNS_EWORKSPACE;
     if (nhwc(d))
-        return dev(launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, partials_of(workspace), dgamma, dbeta,
+        return dev(launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, partials_of(workspace), dgamma, dbeta, false,
                                       static_cast<hipStream_t>(stream)));
-    return reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, partials_of(workspace), 0, d.C,
+    // (the location set is not known here: dy is taken to be what the dx pass reads again)
+    return reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, partials_of(workspace), 0, d.C, false,
                         static_cast<hipStream_t>(stream));
 }
 
@@ -342,6 +344,9 @@ bns_status backward_impl(const bns_shape* shape, const bns_spec* spec, uint64_t 
     const IndexParams ip = make_index_params(*shape, *spec, seed);
     hipStream_t st = static_cast<hipStream_t>(stream);
     Partial* ws = partials_of(workspace);
+    // the dx pass reads x on the points of S only: worth keeping in cache when that is most of the tensor
+    const bool x_again = 2u * uint64_t(ip.shared.n_cnt) * uint64_t(ip.shared.h_cnt) * uint64_t(ip.shared.w_cnt) >=
+                         uint64_t(d.N) * uint64_t(d.HW);
     if (nhwc(d)) {
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
         hipError_t se = hipSuccess;
@@ -350,16 +355,19 @@ bns_status backward_impl(const bns_shape* shape, const bns_spec* spec, uint64_t 
             return dev(se);
         }
         t_last_path_backward = 1;
-        // Eq. 6 outside S needs none of the sums: when S is at most half of the rows, the reduction kernel writes
-        // dx there while it has dy in registers, and only the rows of S are left for after the sums
+        // Eq. 6 outside S needs none of the sums: the reduction kernel can write dx there while it has dy in
+        // registers, which leaves only the rows of S for after the sums.  That saves one read of dy from memory, and
+        // pays when S is at most half of the rows and dy is too large for the dx pass to find it in the memory-side
+        // cache (where the second read costs less than the slower kernel that the split makes of the reduction).
         const bns_box& sb = ip.shared;
         const uint64_t s_rows = uint64_t(sb.n_cnt) * uint64_t(sb.h_cnt) * uint64_t(sb.w_cnt);
         const int split = g_tuning.nhwc_split_dx;
-        if (split == 1 || (split == 0 && 2u * s_rows <= uint64_t(d.N) * uint64_t(d.HW))) {
+        if (split == 1 || (split == 0 && 2u * s_rows <= uint64_t(d.N) * uint64_t(d.HW) && !keep_for_next_pass(tensor_bytes(d)))) {
             t_last_path_backward = 4;
             return dev(launch_nhwc_backward_split(d, sb, x, dy, gamma, save_mean, save_invstd, ws, dgamma, dbeta, dx, st));
         }
-        if (launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, ws, dgamma, dbeta, st) != hipSuccess) return BNS_EDEVICE;
+        if (launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, ws, dgamma, dbeta, x_again, st) != hipSuccess)
+            return BNS_EDEVICE;
         return dev(launch_nhwc_dx(d, ip.shared, x, dy, gamma, save_mean, save_invstd, dgamma, dbeta, dx, st));
     }
     if (g_tuning.path != 1) {
@@ -385,7 +393,7 @@ bns_status backward_impl(const bns_shape* shape, const bns_spec* spec, uint64_t 
     const int G = channel_group(d);
     for (int c0 = 0; c0 < d.C; c0 += G) {
         const int cg = (d.C - c0 < G) ? d.C - c0 : G;
-        s = reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, ws, c0, cg, st);
+        s = reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, ws, c0, cg, x_again, st);
         if (s != BNS_OK) return s;
         s = dev(launch_dx(d, ip, x, dy, gamma, save_mean, save_invstd, dgamma, dbeta, dx, c0, cg, st));
         if (s != BNS_OK) return s;
@@ -543,7 +551,7 @@ bns_status bns_backward_mixed(const bns_shape* shape, const bns_spec* spec, uint
     if (nhwc(d)) {
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
         t_last_path_backward = 1;
-        if (launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, partials_of(workspace), dgamma, dbeta, st) !=
+        if (launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, partials_of(workspace), dgamma, dbeta, false, st) !=
             hipSuccess)
             return BNS_EDEVICE;
         return dev(launch_nhwc_dx_mixed(d, ip_s.shared, n_v, mix_beta, x, dy, gamma, save_invstd, dgamma, dbeta,
@@ -573,7 +581,7 @@ bns_status bns_backward_mixed(const bns_shape* shape, const bns_spec* spec, uint
         if (g_tuning.path == 2) return BNS_EUNSUPPORTED;
     }
     t_last_path_backward = 1;
-    s = reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, partials_of(workspace), 0, d.C, st);
+    s = reduce_range(d, x, dy, save_mean, save_invstd, dgamma, dbeta, partials_of(workspace), 0, d.C, false, st);
     if (s != BNS_OK) return s;
     const bns_box& b = ip_s.shared;
     DxSets sets;

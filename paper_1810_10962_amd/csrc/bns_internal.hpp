@@ -44,7 +44,9 @@ using TuneInt = std::atomic<int>;
 struct Tuning {
     TuneInt norm_unroll{0}, norm_nt{-1};    // accesses per thread; bit 0: non-temporal loads, bit 1: stores
     TuneInt dx_unroll{0}, dx_nt{-1};
-    TuneInt reduce_unroll{0}, reduce_nt{-1};
+    TuneInt reduce_unroll{0}, reduce_nt{-1};    // reduce_nt: bit 0 non-temporal loads of x, bit 1 of dy
+    TuneInt cache_reuse{0};                 // a first pass loads what the next pass reads again so that it stays in the
+                                            // memory-side cache: 1 always, 2 never, 0 when it fits (kKeepBytes)
     TuneInt path{0};                        // 0: fused kernels when a channel fits on chip, else streaming;
                                             // 1: streaming kernels only; 2: fused only (error if it cannot)
     TuneInt fused_variant{0};               // 1..7 forces a (block size, registers) variant of the fused kernels
@@ -65,6 +67,17 @@ struct Tuning {
 extern Tuning g_tuning;
 inline int tuned(int v, int dflt) { return v > 0 ? v : dflt; }
 inline int tuned_nt(int v, int dflt) { return v >= 0 ? v : dflt; }
+
+// Two passes over one tensor (statistics then Eq. 1; the sums of Eq. 5 then Eq. 6): the second pass finds in the
+// 256 MB memory-side cache what the first one loaded without the non-temporal hint, which for a copy-like pass is
+// worth about a quarter of its time (reads served there leave the memory to the writes).  Plain loads stream
+// some 10 % slower than non-temporal ones, so a first pass uses them only for what fits, with room to spare for
+// the other traffic of the two passes.
+constexpr size_t kKeepBytes = size_t(224) << 20;
+inline bool keep_for_next_pass(size_t bytes) {
+    const int o = g_tuning.cache_reuse;
+    return o == 1 || (o == 0 && bytes <= kKeepBytes);
+}
 
 // One (sum, sum) pair per channel and split.
 struct Partial {
@@ -89,8 +102,9 @@ hipError_t launch_normalize(const Dims& d, const void* x, const float* gamma, co
                             const float* mean, const float* invstd, void* y, int c0, int cg, hipStream_t st,
                             float var_eps = -1.f);
 // Backward sums of Eq. 5 over all m points: partial sums of dy and dy * (x - mean).
+// x_again: the dx pass reads every element of x again (S is everything), not only those of a small S
 hipError_t launch_reduce_partial(const Dims& d, const void* x, const void* dy, const float* mean,
-                                 Partial* partial, int splits, int c0, int cg, hipStream_t st);
+                                 Partial* partial, int splits, int c0, int cg, bool x_again, hipStream_t st);
 hipError_t launch_reduce_finalize(const Dims& d, const Partial* partial, int splits, int c0, int cg,
                                   const float* invstd, float* dgamma, float* dbeta, hipStream_t st);
 // Which 1/s terms an element receives in the dx pass.  Plain sampled BN: one set, weight 1/s,
@@ -166,8 +180,9 @@ hipError_t launch_nhwc_stats(const Dims& d, const bns_box& b, const void* x, Par
                              hipStream_t st);
 hipError_t launch_nhwc_normalize(const Dims& d, const void* x, const float* gamma, const float* beta, const float* mean,
                                  const float* invstd, void* y, hipStream_t st, float var_eps = -1.f);
+// x_again: as for launch_reduce_partial
 hipError_t launch_nhwc_reduce(const Dims& d, const void* x, const void* dy, const float* mean, const float* invstd,
-                              Partial* partial, float* dgamma, float* dbeta, hipStream_t st);
+                              Partial* partial, float* dgamma, float* dbeta, bool x_again, hipStream_t st);
 // Backward with dx split by the two branches of Eq. 6: the reduction kernel also writes dx outside S, a second
 // element-wise kernel takes the rows of S after the sums ((3 + 2r) e bytes per element instead of (4 + r) e).
 hipError_t launch_nhwc_backward_split(const Dims& d, const bns_box& b, const void* x, const void* dy, const float* gamma,

@@ -24,7 +24,9 @@ namespace bns {
 // S made of whole planes (FULL, NS, BS, VDN) with HW a multiple of V.
 // grid.x = cg * splits; block (c, k) reduces vectors [k * per_block, (k + 1) * per_block)
 // of the n_cnt * HW / V vectors of channel c.
-template <typename T, int V>
+// KEEP: the sampled planes fit the memory-side cache, and the normalization pass that follows reads them again:
+// plain loads leave them there, non-temporal ones (faster from memory) do not.
+template <typename T, int V, bool KEEP>
 __global__ __launch_bounds__(kBlock) void stats_partial_planes_kernel(
     const T* __restrict__ x, Partial* __restrict__ partial, IndexParams ip, int C, int HW,
     FastDiv hwv_div, int c0, int splits, uint32_t per_block) {
@@ -49,7 +51,8 @@ __global__ __launch_bounds__(kBlock) void stats_partial_planes_kernel(
         for (int u = 0; u < 4; ++u) {
             const uint32_t ju = j + u * kBlock;
             const uint32_t n = fdiv(ju, hwv_div);
-            v[u].load_nt(base + n * nstride + size_t(ju - n * hwv) * V);
+            const T* p = base + n * nstride + size_t(ju - n * hwv) * V;
+            if (KEEP) v[u].load(p); else v[u].load_nt(p);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u)
@@ -147,7 +150,7 @@ __global__ __launch_bounds__(kOneBlock) void stats_one_block_kernel(
                 const uint32_t j = j0 + u * kOneBlock;
                 if (j < tot) {
                     const uint32_t n = fdiv(j, hwv_div);
-                    v[u].load_nt(base + n * nstride + size_t(j - n * hwv) * V);
+                    v[u].load(base + n * nstride + size_t(j - n * hwv) * V);   // (few points, read again by Eq. 1: plain)
                 }
             }
 #pragma unroll
@@ -351,6 +354,8 @@ __global__ __launch_bounds__(kBlock) void normalize_kernel(
 // Backward reductions over all m points (Eq. 5): sum dy, sum dy * (x - mean)
 // ===========================================================================
 // grid.x = cg * splits, block (c, k) as in stats_partial_planes_kernel with S = everything.
+// NT: bit 0 non-temporal loads of x, bit 1 of dy.  What the dx pass reads again (dy; x too when S is everything)
+// is loaded plainly when it fits the memory-side cache, so that the dx pass finds it there.
 template <typename T, int V, int U, int NT>
 __global__ __launch_bounds__(kBlock) void reduce_partial_kernel(
     const T* __restrict__ x, const T* __restrict__ dy, const float* __restrict__ mean,
@@ -378,13 +383,8 @@ __global__ __launch_bounds__(kBlock) void reduce_partial_kernel(
             const uint32_t ju = j + u * kBlock;
             const uint32_t n = fdiv(ju, hwv_div);
             const size_t off = cbase + n * nstride + size_t(ju - n * hwv) * V;
-            if (NT & 1) {
-                g[u].load_nt(dy + off);
-                v[u].load_nt(x + off);
-            } else {
-                g[u].load(dy + off);
-                v[u].load(x + off);
-            }
+            if (NT & 2) g[u].load_nt(dy + off); else g[u].load(dy + off);
+            if (NT & 1) v[u].load_nt(x + off); else v[u].load(x + off);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -605,9 +605,14 @@ hipError_t launch_stats_partial(const Dims& d, const IndexParams& ip, const void
             const uint32_t hwv = uint32_t(d.HW / V);
             const uint32_t tot = uint32_t(b.n_cnt) * hwv;
             const uint32_t per_block = ceil_div(tot, uint32_t(splits));
-            BNS_LAUNCH((stats_partial_planes_kernel<T, V>), grid, dim3(kBlock), 0, st,
-                       static_cast<const T*>(x), partial, ip, d.C, d.HW, make_fastdiv(hwv), c0, splits,
-                       per_block);
+            if (keep_for_next_pass(size_t(tot) * V * sizeof(T) * size_t(cg)))
+                BNS_LAUNCH((stats_partial_planes_kernel<T, V, true>), grid, dim3(kBlock), 0, st,
+                           static_cast<const T*>(x), partial, ip, d.C, d.HW, make_fastdiv(hwv), c0, splits,
+                           per_block);
+            else
+                BNS_LAUNCH((stats_partial_planes_kernel<T, V, false>), grid, dim3(kBlock), 0, st,
+                           static_cast<const T*>(x), partial, ip, d.C, d.HW, make_fastdiv(hwv), c0, splits,
+                           per_block);
             return hipGetLastError();
         });
     }
@@ -709,11 +714,13 @@ hipError_t launch_normalize(const Dims& d, const void* x, const float* gamma, co
 }
 
 hipError_t launch_reduce_partial(const Dims& d, const void* x, const void* dy, const float* mean,
-                                 Partial* partial, int splits, int c0, int cg, hipStream_t st) {
+                                 Partial* partial, int splits, int c0, int cg, bool x_again, hipStream_t st) {
+    const size_t slab = size_t(d.N) * size_t(cg) * d.HW * (d.dtype == BNS_F32 ? 4 : 2);       // dy of this channel range
+    const int keep = !keep_for_next_pass(slab) ? 0 : (x_again && keep_for_next_pass(2 * slab)) ? 2 : 1;
     return dispatch(d, [&](auto t, auto vt) {
         using T = decltype(t);
         constexpr int V = decltype(vt)::value;
-        return dispatch_unroll_nt(tuned(g_tuning.reduce_unroll, 2), tuned_nt(g_tuning.reduce_nt, 1) & 1, [&](auto ut, auto nt) {
+        return dispatch_unroll_nt(tuned(g_tuning.reduce_unroll, 2), tuned_nt(g_tuning.reduce_nt, keep == 2 ? 0 : keep == 1 ? 1 : 3), [&](auto ut, auto nt) {
             constexpr int U = decltype(ut)::value;
             constexpr int NT = decltype(nt)::value;
             const uint32_t hwv = uint32_t(d.HW / V);

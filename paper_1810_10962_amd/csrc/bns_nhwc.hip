@@ -114,10 +114,11 @@ __device__ __forceinline__ void write_partials(float (&a)[V], float (&q)[V], flo
 // rows (a small S spread over the whole device) waits for memory once and a block with many rows keeps
 // two batches in flight.  Row indices past the end of the share are clamped to its last row and their
 // terms dropped, so every load is unconditional.  CONTIG: the rows of S are one contiguous run (Batch
-// Sampling, full BN, NS, the virtual set), so the sampled row needs no division.
+// Sampling, full BN, NS, the virtual set), so the sampled row needs no division.  KEEP: loads without the
+// non-temporal hint, so that the normalization pass finds the rows of S in the memory-side cache.
 constexpr int kStatRows = 8;
 
-template <typename T, int V, bool CONTIG>
+template <typename T, int V, bool CONTIG, bool KEEP>
 __global__ __launch_bounds__(kBlock) void nhwc_stats_partial_kernel(const T* __restrict__ x,
                                                                     Partial* __restrict__ partial, RowSet S, Tiling t) {
     __shared__ float lds[2 * kBlock * V];
@@ -142,8 +143,10 @@ __global__ __launch_bounds__(kBlock) void nhwc_stats_partial_kernel(const T* __r
         auto row_of = [&](uint32_t i) { return CONTIG ? first + i : sampled_row(S, i); };
         auto fetch = [&](Vec<T, V>(&v)[kStatRows], uint32_t i) {
 #pragma unroll
-            for (int u = 0; u < kStatRows; ++u)
-                v[u].load_nt(xc + size_t(row_of(min(i + uint32_t(u) * TY, i1 - 1u))) * t.C);
+            for (int u = 0; u < kStatRows; ++u) {
+                const T* p = xc + size_t(row_of(min(i + uint32_t(u) * TY, i1 - 1u))) * t.C;
+                if (KEEP) v[u].load(p); else v[u].load_nt(p);
+            }
         };
         auto add = [&](const Vec<T, V>(&v)[kStatRows], uint32_t i) {
             if (i + uint32_t(kStatRows - 1) * TY < i1) {         // every row of the batch belongs to the share
@@ -230,7 +233,9 @@ __device__ __forceinline__ bool row_in(const RowBox& b, uint32_t row) {
 // OUTSIDE: the kernel also writes dx on the rows that are NOT in S.  The second branch of Eq. 6, dx = gamma r dy,
 // needs none of the sums, and dy of those rows is in registers here anyway; what is left for after the sums are
 // the rows of S alone (nhwc_dx_rows_kernel).  Backward then has to move (3 + 2r) e bytes per element instead of (4 + r) e.
-template <typename T, int V, bool OUTSIDE>
+// KEEP: what the dx pass reads again is loaded without the non-temporal hint, so that it stays in the memory-side
+// cache: 1 = dy, 2 = dy and x (S is everything), 0 = neither (too large to stay, or dx is written here).
+template <typename T, int V, bool OUTSIDE, int KEEP>
 __device__ __forceinline__ void reduce_partial_body(const T* __restrict__ x, const T* __restrict__ dy,
                                                     const float* __restrict__ mean, Partial* __restrict__ partial,
                                                     const Tiling& t, uint32_t M, T* __restrict__ dx,
@@ -261,8 +266,8 @@ __device__ __forceinline__ void reduce_partial_body(const T* __restrict__ x, con
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 const size_t off = size_t(r + uint32_t(u) * TY) * t.C + col;
-                g[u].load_nt(dy + off);
-                v[u].load_nt(x + off);
+                if (KEEP >= 1) g[u].load(dy + off); else g[u].load_nt(dy + off);
+                if (KEEP == 2) v[u].load(x + off); else v[u].load_nt(x + off);
             }
 #pragma unroll
             for (int e = 0; e < V; ++e) {
@@ -284,8 +289,8 @@ __device__ __forceinline__ void reduce_partial_body(const T* __restrict__ x, con
         for (; r < r1; r += TY) {
             const size_t off = size_t(r) * t.C + col;
             Vec<T, V> g, v;
-            g.load_nt(dy + off);
-            v.load_nt(x + off);
+            if (KEEP >= 1) g.load(dy + off); else g.load_nt(dy + off);
+            if (KEEP == 2) v.load(x + off); else v.load_nt(x + off);
 #pragma unroll
             for (int e = 0; e < V; ++e) {
                 A[e] += double(g.f[e]);
@@ -306,12 +311,12 @@ __device__ __forceinline__ void reduce_partial_body(const T* __restrict__ x, con
     write_partials<V>(a, q, lds, t, l, partial);
 }
 
-template <typename T, int V>
+template <typename T, int V, int KEEP>
 __global__ __launch_bounds__(kBlock) void nhwc_reduce_partial_kernel(const T* __restrict__ x, const T* __restrict__ dy,
                                                                      const float* __restrict__ mean,
                                                                      Partial* __restrict__ partial, Tiling t, uint32_t M) {
     __shared__ float lds[2 * kBlock * V];
-    reduce_partial_body<T, V, false>(x, dy, mean, partial, t, M, nullptr, nullptr, nullptr, RowBox{}, lds);
+    reduce_partial_body<T, V, false, KEEP>(x, dy, mean, partial, t, M, nullptr, nullptr, nullptr, RowBox{}, lds);
 }
 
 template <typename T, int V>
@@ -321,7 +326,7 @@ __global__ __launch_bounds__(kBlock) void nhwc_reduce_outside_kernel(const T* __
                                                                      T* __restrict__ dx, const float* __restrict__ gamma,
                                                                      const float* __restrict__ invstd, RowBox B) {
     __shared__ float lds[2 * kBlock * V];
-    reduce_partial_body<T, V, true>(x, dy, mean, partial, t, M, dx, gamma, invstd, B, lds);
+    reduce_partial_body<T, V, true, 0>(x, dy, mean, partial, t, M, dx, gamma, invstd, B, lds);
 }
 
 // Finalize kernels: a block takes kFinCh neighbouring channels; thread (ch, kl) adds the partials
@@ -1010,10 +1015,16 @@ hipError_t dispatch_nhwc(const Dims& d, F&& f) {
 
 template <typename T, int V>
 hipError_t launch_stats_partial(const T* x, Partial* partial, const RowSet& S, const Tiling& t, hipStream_t st) {
-    if (S.contiguous)
-        BNS_LAUNCH((nhwc_stats_partial_kernel<T, V, true>), dim3(grid_of(t)), dim3(kBlock), 0, st, x, partial, S, t);
-    else
-        BNS_LAUNCH((nhwc_stats_partial_kernel<T, V, false>), dim3(grid_of(t)), dim3(kBlock), 0, st, x, partial, S, t);
+    const dim3 grid(grid_of(t)), block(kBlock);
+    // the normalization pass reads the rows of S again
+    const bool keep = keep_for_next_pass(size_t(S.rows) * size_t(t.C) * sizeof(T));
+    if (S.contiguous) {
+        if (keep) BNS_LAUNCH((nhwc_stats_partial_kernel<T, V, true, true>), grid, block, 0, st, x, partial, S, t);
+        else BNS_LAUNCH((nhwc_stats_partial_kernel<T, V, true, false>), grid, block, 0, st, x, partial, S, t);
+    } else {
+        if (keep) BNS_LAUNCH((nhwc_stats_partial_kernel<T, V, false, true>), grid, block, 0, st, x, partial, S, t);
+        else BNS_LAUNCH((nhwc_stats_partial_kernel<T, V, false, false>), grid, block, 0, st, x, partial, S, t);
+    }
     return hipGetLastError();
 }
 
@@ -1065,15 +1076,21 @@ hipError_t launch_nhwc_normalize(const Dims& d, const void* x, const float* gamm
 }
 
 hipError_t launch_nhwc_reduce(const Dims& d, const void* x, const void* dy, const float* mean, const float* invstd,
-                              Partial* partial, float* dgamma, float* dbeta, hipStream_t st) {
+                              Partial* partial, float* dgamma, float* dbeta, bool x_again, hipStream_t st) {
     const uint32_t M = uint32_t(d.N) * uint32_t(d.HW);
     const Tiling t = make_tiling(d, M);
     if (!fits_region(d, t)) return hipErrorInvalidValue;
+    const size_t bytes = size_t(M) * size_t(d.C) * (d.dtype == BNS_F32 ? 4 : 2);
+    const int keep = !keep_for_next_pass(bytes) ? 0 : (x_again && keep_for_next_pass(2 * bytes)) ? 2 : 1;
     return dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
         constexpr int V = decltype(vt)::value;
-        BNS_LAUNCH((nhwc_reduce_partial_kernel<T, V>), dim3(grid_of(t)), dim3(kBlock), 0, st,
-                   static_cast<const T*>(x), static_cast<const T*>(dy), mean, partial, t, M);
+        const dim3 grid(grid_of(t)), block(kBlock);
+        const T* xp = static_cast<const T*>(x);
+        const T* gp = static_cast<const T*>(dy);
+        if (keep == 2) BNS_LAUNCH((nhwc_reduce_partial_kernel<T, V, 2>), grid, block, 0, st, xp, gp, mean, partial, t, M);
+        else if (keep == 1) BNS_LAUNCH((nhwc_reduce_partial_kernel<T, V, 1>), grid, block, 0, st, xp, gp, mean, partial, t, M);
+        else BNS_LAUNCH((nhwc_reduce_partial_kernel<T, V, 0>), grid, block, 0, st, xp, gp, mean, partial, t, M);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         BNS_LAUNCH(nhwc_reduce_finalize_kernel, dim3(ceil_div_u(uint32_t(d.C), kFinCh)), dim3(kBlock), 0, st,

@@ -307,7 +307,7 @@ void host_functions() {
         ++g_failures, fprintf(stderr, "options\n");
     const char* names[] = {"path", "fused_variant", "fused_pipe", "fused_team", "fused_coop", "fused_keep_x", "fused_patch_mask", "split_statistics",
                            "splits_stats", "splits_reduce", "channel_group", "nhwc_blocks", "nhwc_ew_rows", "nhwc_small", "nhwc_split_dx",
-                           "norm_unroll", "dx_unroll", "reduce_unroll", "norm_nt", "dx_nt", "reduce_nt", "test_spin_limit",
+                           "norm_unroll", "dx_unroll", "reduce_unroll", "norm_nt", "dx_nt", "reduce_nt", "cache_reuse", "test_spin_limit",
                            "test_mute_exchange"};
     for (const char* n : names) {
         if (bns_get_option(n) != 0) ++g_failures, fprintf(stderr, "option %s not at its default\n", n);

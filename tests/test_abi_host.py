@@ -208,7 +208,7 @@ def test_options():
     ranges = {"path": 2, "fused_variant": 7, "fused_coop": 1, "fused_keep_x": 2, "fused_patch_mask": 2, "test_spin_limit": 1 << 21,
               "test_mute_exchange": 1, "split_statistics": 1, "nhwc_blocks": 8192, "nhwc_split_dx": 2,
               "nhwc_ew_rows": 1 << 20, "norm_unroll": 4, "dx_unroll": 4, "reduce_unroll": 4, "norm_nt": 4, "dx_nt": 4,
-              "reduce_nt": 2}
+              "reduce_nt": 4, "cache_reuse": 2}
     for name, hi in ranges.items():
         assert bns.bns_get_option(name) == 0, name
         for v in (1, hi):

@@ -193,8 +193,16 @@ def test_bit_identical_reruns_and_stage_calls():
     s = buf.results()
     for k in a:
         assert (a[k] == s[k]).all(), k
-    # (the whole-call backward wrote dx outside S from its reduction kernel; the stage calls cannot: same bits)
-    assert bns.bns_get_option("last_path_forward") == 1 and bns.bns_get_option("last_path_backward") == 4
+    assert bns.bns_get_option("last_path_forward") == 1 and bns.bns_get_option("last_path_backward") == 1
+    # the whole call with dx outside S written by its reduction kernel (the stage calls cannot): same bits again
+    bns.bns_set_option("nhwc_split_dx", 1)
+    try:
+        c = bns.run_workload(wl, inp)
+        assert bns.bns_get_option("last_path_backward") == 4
+    finally:
+        bns.bns_set_option("nhwc_split_dx", 0)
+    for k in a:
+        assert (a[k] == c[k]).all(), k
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -305,12 +313,12 @@ def test_small_tensors_take_one_launch_per_direction(kernel_choice):
     inp = workloads.make_inputs(wl)
     res = bns.run_workload(wl, inp)
     want = 3 if kernel_choice == "auto" else 1
-    want_b = 3 if kernel_choice == "auto" else 4                  # streaming: S is 16 of 196 rows, dx is split
+    want_b = 3 if kernel_choice == "auto" else 1
     assert bns.bns_get_option("last_path_forward") == want and bns.bns_get_option("last_path_backward") == want_b
     assert_parity(res, oracle_reference(wl, inp), wl, what="micro_a_fs nhwc", inp=inp)
     big = workloads.WORKLOADS["cifar_fs"].replace(layout="nhwc", N=16)
     bns.run_workload(big, workloads.make_inputs(big))
-    assert bns.bns_get_option("last_path_forward") == 1 and bns.bns_get_option("last_path_backward") == 4
+    assert bns.bns_get_option("last_path_forward") == 1 and bns.bns_get_option("last_path_backward") == 1
 
 
 MIXED_MODES = [

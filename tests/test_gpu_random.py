@@ -108,7 +108,7 @@ def test_random_configurations(chunk):
 # Launch-choice overrides (include/bns.h, bns_set_option): documented ranges, extremes included.
 OVERRIDES = {
     "norm_unroll": [0, 1, 2, 4], "dx_unroll": [0, 1, 2, 4], "reduce_unroll": [0, 1, 2, 4], "norm_nt": [0, 1, 2, 3, 4],
-    "dx_nt": [0, 1, 2, 3, 4], "reduce_nt": [0, 1, 2], "split_statistics": [0, 1], "splits_stats": [0, 1, 2, 7, 33, 64],
+    "dx_nt": [0, 1, 2, 3, 4], "reduce_nt": [0, 1, 2, 3, 4], "cache_reuse": [0, 1, 2], "split_statistics": [0, 1], "splits_stats": [0, 1, 2, 7, 33, 64],
     "splits_reduce": [0, 1, 3, 16, 64], "channel_group": [0, 1, 3, 16, 100], "nhwc_blocks": [0, 1, 7, 256, 3000, 8192],
     "nhwc_ew_rows": [0, 1, 2, 9, 64, 5000, 1 << 20], "nhwc_small": [0, 2], "nhwc_split_dx": [0, 1, 2], "fused_variant": [0, 0, 1, 2, 3, 4, 5, 6, 7],
     "fused_keep_x": [0, 1, 2], "fused_patch_mask": [0, 1, 2], "fused_coop": [0, 1], "path": [0, 0, 1, 2],
