@@ -14,6 +14,10 @@
 //   capped          `channel` with at most CAP loads in flight per thread
 //   sample-major    persistent blocks that each stream one contiguous run: the planes of G adjacent channels of
 //                   one sample
+//   two passes      a read-only pass over two tensors (what a reduction does), then a pass that reads one of them
+//                   again and writes a third (what the element-wise pass after it does); timed: the second pass.
+//                   The first pass loads the tensor that is read again either like everything else, with the
+//                   non-temporal hint, or plainly: plain loads leave it in the memory-side cache.
 //
 // Every pattern touches each element of the three tensors exactly once and stays inside the allocations (checked
 // on the host before the launch).
@@ -46,6 +50,22 @@ __global__ __launch_bounds__(256) void flat_kernel(const v4* __restrict__ g, con
                                                     size_t n) {
     const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
     if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(g + i) * 0.5f + __builtin_nontemporal_load(x + i), o + i);
+}
+
+// two passes: first pass (g plain or non-temporal, x non-temporal), second pass (g non-temporal -> o non-temporal)
+template <bool KEEP>
+__global__ __launch_bounds__(256) void sums_kernel(const v4* __restrict__ g, const v4* __restrict__ x, float* __restrict__ out,
+                                                   size_t n) {
+    const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n) return;
+    const v4 a = KEEP ? g[i] : __builtin_nontemporal_load(g + i);
+    const v4 b = __builtin_nontemporal_load(x + i);
+    if (a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w == 12345.678f) out[0] = 1.f;      // (never: keeps the loads)
+}
+__global__ __launch_bounds__(256) void scale_kernel(const v4* __restrict__ g, v4* __restrict__ o, size_t n) {
+    const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n) return;
+    __builtin_nontemporal_store(__builtin_nontemporal_load(g + i) * 2.f, o + i);
 }
 
 // layout: 0 real (sample stride `sstride` vectors), 1 channel-contiguous, 2 the real walk's arithmetic on the
@@ -231,5 +251,37 @@ int main() {
     run("sample-major, 16 teams of 64 blocks x 448 threads, 2 channels of one sample each", [&](int s) {
         hipLaunchKernelGGL((sample_major_kernel<448, 4, 2>), dim3(N * 16), dim3(448), 0, 0, G[s], X[s], O[s], 16);
     });
+
+    // two passes over n vectors (the whole fp32 tensor, and half of it: the same tensor in bf16)
+    float* flag = nullptr;
+    CK(hipMalloc(&flag, sizeof(float)));
+    for (size_t n : {kVectors, kVectors / 2})
+        for (int keep = 0; keep < 2; ++keep) {
+            std::vector<float> t1, t2;
+            const dim3 grid(unsigned((n + 255) / 256));
+            for (int it = 0; it < 30; ++it) {
+                const int s = it % kSets;
+                float ms1 = 0.f, ms2 = 0.f;
+                (void)hipEventRecord(e0, 0);
+                if (keep) hipLaunchKernelGGL(sums_kernel<true>, grid, dim3(256), 0, 0, G[s], X[s], flag, n);
+                else hipLaunchKernelGGL(sums_kernel<false>, grid, dim3(256), 0, 0, G[s], X[s], flag, n);
+                (void)hipEventRecord(e1, 0);
+                (void)hipEventSynchronize(e1);
+                (void)hipEventElapsedTime(&ms1, e0, e1);
+                (void)hipEventRecord(e0, 0);
+                hipLaunchKernelGGL(scale_kernel, grid, dim3(256), 0, 0, G[s], O[s], n);
+                (void)hipEventRecord(e1, 0);
+                (void)hipEventSynchronize(e1);
+                (void)hipEventElapsedTime(&ms2, e0, e1);
+                if (it >= 6) t1.push_back(ms1), t2.push_back(ms2);
+            }
+            CK(hipGetLastError());
+            std::sort(t1.begin(), t1.end());
+            std::sort(t2.begin(), t2.end());
+            printf("two passes over %5.1f MB, first pass loads it %-17s first %6.1f us, second (read it, write as much) %6.1f us  %5.0f GB/s\n",
+                   n * sizeof(v4) / 1e6, keep ? "plainly:" : "non-temporally:", t1[t1.size() / 2] * 1e3, t2[t2.size() / 2] * 1e3,
+                   2.0 * n * sizeof(v4) / t2[t2.size() / 2] / 1e6);
+            fflush(stdout);
+        }
     return 0;
 }
