@@ -36,8 +36,8 @@ constexpr int kMaxSplits = 64;  // upper bound on blocks that share one channel'
 // Launch-shape choices; 0 = the default for the storage type (see tuned()).  The benchmark
 // can override them through bns_set_option.  Defaults come from sweeps on MI355X at
 // 64x256x56x56: one 128-bit access per thread and non-temporal loads and stores stream
-// fastest (streamed data is not re-read, so keeping it out of L2 avoids write-backs of
-// lines nobody will hit).
+// fastest (keeping streamed data out of the caches avoids write-backs of lines nobody will
+// hit); the exception is data that the very next pass reads again, see keep_for_next_pass.
 // Every field is an atomic: bns_set_option may run while another thread launches work (that call then
 // sees the old or the new value of each field it reads, never a torn one).
 using TuneInt = std::atomic<int>;
