@@ -302,12 +302,12 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  *                    one group before the next                                   (1..C)
  *   "nhwc_blocks"    blocks that an N x H x W x C reduction launch aims for      (1..8192)
  *   "nhwc_ew_rows"   rows per thread in the N x H x W x C element-wise kernels   (1..2^20)
- *   "nhwc_split_dx"  N x H x W x C backward: the reduction kernel also writes dx on the rows outside S (Eq. 6 needs
- *                    no sum there), a second kernel the rows of S: 1 always, 2 never; 0: when S is at most half
- *                    of the rows and the tensor too large for "cache_reuse"
+ *   "nhwc_split_dx"  1: the N x H x W x C backward writes dx on the rows outside S from its reduction kernel (Eq. 6
+ *                    needs no sum there) and the rows of S from a kernel of their own; by default (and with 2)
+ *                    the reduction is followed by one dx kernel over all rows, which is faster on this device
  *   "cache_reuse"    streaming kernels: a first pass (statistics; the sums of Eq. 5) loads what the pass after it
  *                    (Eq. 1; Eq. 6) reads again without the non-temporal hint, so that it stays in the device's
- *                    memory-side cache: 1 always, 2 never; 0: when it fits there (224 MB).  Results do not
+ *                    memory-side cache: 1 all of it, 2 none; 0: as much as fits there (224 MB).  Results do not
  *                    depend on it.
  *   "nhwc_small"     2: small N x H x W x C tensors also take the streaming kernels (by default one launch
  *                    per direction does everything when a thread would walk at most 16 rows)

@@ -356,15 +356,12 @@ bns_status backward_impl(const bns_shape* shape, const bns_spec* spec, uint64_t 
         }
         t_last_path_backward = 1;
         // Eq. 6 outside S needs none of the sums: the reduction kernel can write dx there while it has dy in
-        // registers, which leaves only the rows of S for after the sums.  That saves one read of dy from memory, and
-        // pays when S is at most half of the rows and dy is too large for the dx pass to find it in the memory-side
-        // cache (where the second read costs less than the slower kernel that the split makes of the reduction).
-        const bns_box& sb = ip.shared;
-        const uint64_t s_rows = uint64_t(sb.n_cnt) * uint64_t(sb.h_cnt) * uint64_t(sb.w_cnt);
-        const int split = g_tuning.nhwc_split_dx;
-        if (split == 1 || (split == 0 && 2u * s_rows <= uint64_t(d.N) * uint64_t(d.HW) && !keep_for_next_pass(tensor_bytes(d)))) {
+        // registers, which leaves only the rows of S for after the sums and saves one read of dy from memory.  Only on
+        // request: the dx pass finds most of dy in the memory-side cache, and that second read costs less than the
+        // slower kernel that the split makes of the reduction (measured up to 128 x 256 x 56 x 56).
+        if (g_tuning.nhwc_split_dx == 1) {
             t_last_path_backward = 4;
-            return dev(launch_nhwc_backward_split(d, sb, x, dy, gamma, save_mean, save_invstd, ws, dgamma, dbeta, dx, st));
+            return dev(launch_nhwc_backward_split(d, ip.shared, x, dy, gamma, save_mean, save_invstd, ws, dgamma, dbeta, dx, st));
         }
         if (launch_nhwc_reduce(d, x, dy, save_mean, save_invstd, ws, dgamma, dbeta, x_again, st) != hipSuccess)
             return BNS_EDEVICE;

@@ -10,6 +10,9 @@
 // recover the channel of an access with one multiply-shift division.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <type_traits>
+
 #include "bns_device.hpp"
 #include "bns_internal.hpp"
 
@@ -360,7 +363,7 @@ template <typename T, int V, int U, int NT>
 __global__ __launch_bounds__(kBlock) void reduce_partial_kernel(
     const T* __restrict__ x, const T* __restrict__ dy, const float* __restrict__ mean,
     Partial* __restrict__ partial, int C, int HW, FastDiv hwv_div, int c0, int splits, uint32_t per_block,
-    uint32_t tot) {
+    uint32_t tot, int keep_channels) {
     __shared__ float lds[2 * (kBlock / kWave)];
     const int cl = blockIdx.x / splits;       // consecutive blocks: consecutive ranges of the same channel
     const int k = blockIdx.x - cl * splits;
@@ -375,6 +378,8 @@ __global__ __launch_bounds__(kBlock) void reduce_partial_kernel(
     float s1[U], s2[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) s1[u] = s2[u] = 0.f;
+    auto walk = [&](auto mask) {
+    constexpr int M = decltype(mask)::value;
     uint32_t j = j0 + threadIdx.x;
     for (; j + uint32_t(U - 1) * kBlock < j1; j += uint32_t(U) * kBlock) {
         Vec<T, V> g[U], v[U];
@@ -383,8 +388,8 @@ __global__ __launch_bounds__(kBlock) void reduce_partial_kernel(
             const uint32_t ju = j + u * kBlock;
             const uint32_t n = fdiv(ju, hwv_div);
             const size_t off = cbase + n * nstride + size_t(ju - n * hwv) * V;
-            if (NT & 2) g[u].load_nt(dy + off); else g[u].load(dy + off);
-            if (NT & 1) v[u].load_nt(x + off); else v[u].load(x + off);
+            if (M & 2) g[u].load_nt(dy + off); else g[u].load(dy + off);
+            if (M & 1) v[u].load_nt(x + off); else v[u].load(x + off);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -406,6 +411,11 @@ __global__ __launch_bounds__(kBlock) void reduce_partial_kernel(
             s2[0] = fmaf(g.f[i], v.f[i] - mu, s2[0]);
         }
     }
+    };
+    // the channels whose dy (and x) fit the memory-side cache take the loads that the mask asks for, the others
+    // the non-temporal ones (the same for the whole block)
+    if (NT == 3 || cl < keep_channels) walk(std::integral_constant<int, NT>());
+    else walk(std::integral_constant<int, 3>());
     float a = s1[0], q = s2[0];
 #pragma unroll
     for (int u = 1; u < U; ++u) {
@@ -715,8 +725,14 @@ hipError_t launch_normalize(const Dims& d, const void* x, const float* gamma, co
 
 hipError_t launch_reduce_partial(const Dims& d, const void* x, const void* dy, const float* mean,
                                  Partial* partial, int splits, int c0, int cg, bool x_again, hipStream_t st) {
-    const size_t slab = size_t(d.N) * size_t(cg) * d.HW * (d.dtype == BNS_F32 ? 4 : 2);       // dy of this channel range
-    const int keep = !keep_for_next_pass(slab) ? 0 : (x_again && keep_for_next_pass(2 * slab)) ? 2 : 1;
+    // dy of as many channels as fit stays in the memory-side cache for the dx pass (x too if that pass reads most of
+    // it again)
+    const size_t per_channel = size_t(d.N) * d.HW * (d.dtype == BNS_F32 ? 4 : 2);
+    const int reuse = g_tuning.cache_reuse;
+    const bool both = x_again;
+    const size_t fit = kKeepBytes / (per_channel * (both ? 2 : 1));
+    const int keep_channels = reuse == 2 ? 0 : reuse == 1 ? cg : int(std::min<size_t>(size_t(cg), fit));
+    const int keep = keep_channels == 0 ? 0 : both ? 2 : 1;
     return dispatch(d, [&](auto t, auto vt) {
         using T = decltype(t);
         constexpr int V = decltype(vt)::value;
@@ -729,7 +745,7 @@ hipError_t launch_reduce_partial(const Dims& d, const void* x, const void* dy, c
             const dim3 grid(uint32_t(cg) * uint32_t(splits));
             BNS_LAUNCH((reduce_partial_kernel<T, V, U, NT>), grid, dim3(kBlock), 0, st,
                        static_cast<const T*>(x), static_cast<const T*>(dy), mean, partial, d.C, d.HW,
-                       make_fastdiv(hwv), c0, splits, per_block, tot);
+                       make_fastdiv(hwv), c0, splits, per_block, tot, keep_channels);
             return hipGetLastError();
         });
     });

@@ -16,6 +16,7 @@
 // order in fp64, so results are bit-identical from run to run.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "bns_device.hpp"
@@ -234,13 +235,15 @@ __device__ __forceinline__ bool row_in(const RowBox& b, uint32_t row) {
 // needs none of the sums, and dy of those rows is in registers here anyway; what is left for after the sums are
 // the rows of S alone (nhwc_dx_rows_kernel).  Backward then has to move (3 + 2r) e bytes per element instead of (4 + r) e.
 // KEEP: what the dx pass reads again is loaded without the non-temporal hint, so that it stays in the memory-side
-// cache: 1 = dy, 2 = dy and x (S is everything), 0 = neither (too large to stay, or dx is written here).
+// cache: 1 = dy in the blocks of the first `keep_splits` row shares (as many as fit; the dx pass loads and stores
+// with the hint, so what is cached stays until it gets there), 2 = dy and x everywhere (S is most of the rows and
+// both fit), 0 = neither (dx is written here).
 template <typename T, int V, bool OUTSIDE, int KEEP>
 __device__ __forceinline__ void reduce_partial_body(const T* __restrict__ x, const T* __restrict__ dy,
                                                     const float* __restrict__ mean, Partial* __restrict__ partial,
                                                     const Tiling& t, uint32_t M, T* __restrict__ dx,
                                                     const float* __restrict__ gamma, const float* __restrict__ invstd,
-                                                    const RowBox& B, float* lds) {
+                                                    const RowBox& B, float* lds, uint32_t keep_splits) {
     const Lane l = lane_of(t);
     const uint32_t r0 = uint32_t(l.k) * t.rows_per_block;
     const uint32_t r1 = min(r0 + t.rows_per_block, M);
@@ -260,14 +263,16 @@ __device__ __forceinline__ void reduce_partial_body(const T* __restrict__ x, con
             for (int e = 0; e < V; ++e) sc[e] = gamma[l.cv * V + e] * invstd[l.cv * V + e];      // a = gamma r
         }
         const size_t col = size_t(l.cv) * V;
+        auto walk = [&](auto keep_dy, auto keep_x) {
+        constexpr bool KD = decltype(keep_dy)::value, KX = decltype(keep_x)::value;
         uint32_t r = r0 + uint32_t(l.ty);
         for (; r + TY < r1; r += 2u * TY) {
             Vec<T, V> g[2], v[2];
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 const size_t off = size_t(r + uint32_t(u) * TY) * t.C + col;
-                if (KEEP >= 1) g[u].load(dy + off); else g[u].load_nt(dy + off);
-                if (KEEP == 2) v[u].load(x + off); else v[u].load_nt(x + off);
+                if (KD) g[u].load(dy + off); else g[u].load_nt(dy + off);
+                if (KX) v[u].load(x + off); else v[u].load_nt(x + off);
             }
 #pragma unroll
             for (int e = 0; e < V; ++e) {
@@ -289,8 +294,8 @@ __device__ __forceinline__ void reduce_partial_body(const T* __restrict__ x, con
         for (; r < r1; r += TY) {
             const size_t off = size_t(r) * t.C + col;
             Vec<T, V> g, v;
-            if (KEEP >= 1) g.load(dy + off); else g.load_nt(dy + off);
-            if (KEEP == 2) v.load(x + off); else v.load_nt(x + off);
+            if (KD) g.load(dy + off); else g.load_nt(dy + off);
+            if (KX) v.load(x + off); else v.load_nt(x + off);
 #pragma unroll
             for (int e = 0; e < V; ++e) {
                 A[e] += double(g.f[e]);
@@ -301,6 +306,15 @@ __device__ __forceinline__ void reduce_partial_body(const T* __restrict__ x, con
                 for (int e = 0; e < V; ++e) g.f[e] *= sc[e];
                 g.store_nt(dx + off);
             }
+        }
+        };
+        if constexpr (KEEP == 2) {
+            walk(std::true_type(), std::true_type());
+        } else if constexpr (KEEP == 1) {
+            if (uint32_t(l.k) < keep_splits) walk(std::true_type(), std::false_type());      // (the same for the whole block)
+            else walk(std::false_type(), std::false_type());
+        } else {
+            walk(std::false_type(), std::false_type());
         }
 #pragma unroll
         for (int e = 0; e < V; ++e) {
@@ -314,9 +328,10 @@ __device__ __forceinline__ void reduce_partial_body(const T* __restrict__ x, con
 template <typename T, int V, int KEEP>
 __global__ __launch_bounds__(kBlock) void nhwc_reduce_partial_kernel(const T* __restrict__ x, const T* __restrict__ dy,
                                                                      const float* __restrict__ mean,
-                                                                     Partial* __restrict__ partial, Tiling t, uint32_t M) {
+                                                                     Partial* __restrict__ partial, Tiling t, uint32_t M,
+                                                                     uint32_t keep_splits) {
     __shared__ float lds[2 * kBlock * V];
-    reduce_partial_body<T, V, false, KEEP>(x, dy, mean, partial, t, M, nullptr, nullptr, nullptr, RowBox{}, lds);
+    reduce_partial_body<T, V, false, KEEP>(x, dy, mean, partial, t, M, nullptr, nullptr, nullptr, RowBox{}, lds, keep_splits);
 }
 
 template <typename T, int V>
@@ -326,7 +341,7 @@ __global__ __launch_bounds__(kBlock) void nhwc_reduce_outside_kernel(const T* __
                                                                      T* __restrict__ dx, const float* __restrict__ gamma,
                                                                      const float* __restrict__ invstd, RowBox B) {
     __shared__ float lds[2 * kBlock * V];
-    reduce_partial_body<T, V, true, 0>(x, dy, mean, partial, t, M, dx, gamma, invstd, B, lds);
+    reduce_partial_body<T, V, true, 0>(x, dy, mean, partial, t, M, dx, gamma, invstd, B, lds, 0u);
 }
 
 // Finalize kernels: a block takes kFinCh neighbouring channels; thread (ch, kl) adds the partials
@@ -1080,17 +1095,23 @@ hipError_t launch_nhwc_reduce(const Dims& d, const void* x, const void* dy, cons
     const uint32_t M = uint32_t(d.N) * uint32_t(d.HW);
     const Tiling t = make_tiling(d, M);
     if (!fits_region(d, t)) return hipErrorInvalidValue;
+    // dy of as many row shares as fit is left in the memory-side cache for the dx pass (x too when that pass reads
+    // most of it again and both fit)
     const size_t bytes = size_t(M) * size_t(d.C) * (d.dtype == BNS_F32 ? 4 : 2);
-    const int keep = !keep_for_next_pass(bytes) ? 0 : (x_again && keep_for_next_pass(2 * bytes)) ? 2 : 1;
+    const size_t share = size_t(t.rows_per_block) * size_t(d.C) * (d.dtype == BNS_F32 ? 4 : 2);
+    const int reuse = g_tuning.cache_reuse;
+    const uint32_t keep_splits =
+        reuse == 2 ? 0u : reuse == 1 ? uint32_t(t.splits) : uint32_t(std::min<size_t>(size_t(t.splits), kKeepBytes / share));
+    const int keep = keep_splits == 0u ? 0 : (x_again && keep_for_next_pass(2 * bytes)) ? 2 : 1;
     return dispatch_nhwc(d, [&](auto ty, auto vt) {
         using T = decltype(ty);
         constexpr int V = decltype(vt)::value;
         const dim3 grid(grid_of(t)), block(kBlock);
         const T* xp = static_cast<const T*>(x);
         const T* gp = static_cast<const T*>(dy);
-        if (keep == 2) BNS_LAUNCH((nhwc_reduce_partial_kernel<T, V, 2>), grid, block, 0, st, xp, gp, mean, partial, t, M);
-        else if (keep == 1) BNS_LAUNCH((nhwc_reduce_partial_kernel<T, V, 1>), grid, block, 0, st, xp, gp, mean, partial, t, M);
-        else BNS_LAUNCH((nhwc_reduce_partial_kernel<T, V, 0>), grid, block, 0, st, xp, gp, mean, partial, t, M);
+        if (keep == 2) BNS_LAUNCH((nhwc_reduce_partial_kernel<T, V, 2>), grid, block, 0, st, xp, gp, mean, partial, t, M, keep_splits);
+        else if (keep == 1) BNS_LAUNCH((nhwc_reduce_partial_kernel<T, V, 1>), grid, block, 0, st, xp, gp, mean, partial, t, M, keep_splits);
+        else BNS_LAUNCH((nhwc_reduce_partial_kernel<T, V, 0>), grid, block, 0, st, xp, gp, mean, partial, t, M, keep_splits);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         BNS_LAUNCH(nhwc_reduce_finalize_kernel, dim3(ceil_div_u(uint32_t(d.C), kFinCh)), dim3(kBlock), 0, st,
