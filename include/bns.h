@@ -313,8 +313,8 @@ bns_status bns_copy_reference(void* dst, const void* src, size_t bytes, void* st
  *                    per direction does everything when a thread would walk at most 16 rows)
  *   "norm_unroll", "dx_unroll", "reduce_unroll"   128-bit accesses per thread    (1, 2, 4)
  *   "norm_nt", "dx_nt"   non-temporal access mask + 1: bit 0 loads, bit 1 stores
- *   "reduce_nt"      the same for the backward reduction: bit 0 loads of x, bit 1 loads of dy (overrides "cache_reuse"
- *                    there)
+ *   "reduce_nt"      the same for the backward reduction: bit 0 loads of x, bit 1 loads of dy, for the channels
+ *                    that "cache_reuse" keeps (the others are loaded non-temporally)
  * Two more exist for the library's own tests only; they make results wrong on purpose and a caller has no
  * use for them:
  *   "test_spin_limit"    polls a block of a fused kernel waits for a team-mate's sums before it gives up
