@@ -221,3 +221,34 @@ def test_structured_values_do_not_bias_long_sums(layout):
     print(f"[gpu-case] structured scaled errors {errs}", flush=True)
     # dbeta is 65536 / 3 for every channel; a biased sum shows here first
     assert np.max(np.abs(res["dbeta"] / (N * H * W / 3.0) - 1)) <= 2e-6
+
+
+@pytest.mark.parametrize("layout", ["nchw", "nhwc"])
+@pytest.mark.parametrize("n_s", [8, 40])
+def test_results_do_not_depend_on_the_cache_hints(layout, n_s):
+    """The streaming kernels load part of what their next pass reads again without the non-temporal hint: as much
+    as fits the memory-side cache (here 224 MB of a 411 MB tensor; with n_s = 40 the dx pass reads most of x again
+    and x is kept as well), all of it, or nothing.  Only a hint bit differs, so every output has the same bits."""
+    wl = Workload(name="hints", N=64, C=512, H=56, W=56, mode=BS, n_s=n_s, dtype="f32", layout=layout, data_seed=21,
+                  sampling_seed=5, layer_id=2, epoch=3)
+    names = ("y", "dx", "save_mean", "save_invstd", "running_mean", "running_var", "dgamma", "dbeta")
+    first = None
+    try:
+        bns.bns_set_option("path", 1)
+        for reuse in (0, 1, 2):
+            print(f"[gpu-case] cache hints {layout} n_s={n_s} cache_reuse={reuse}", flush=True)
+            bns.bns_set_option("cache_reuse", reuse)
+            t = _device_case(wl)
+            assert bns.bns_get_option("last_path_forward") == 1 and bns.bns_get_option("last_path_backward") == 1
+            got = {k: t[k].clone() for k in names}
+            del t
+            if first is None:
+                first = got
+            else:
+                for k in names:
+                    assert torch.equal(first[k], got[k]), f"{k}: cache_reuse={reuse} changes the result"
+            del got
+            torch.cuda.empty_cache()
+    finally:
+        bns.bns_set_option("cache_reuse", 0)
+        bns.bns_set_option("path", 0)
