@@ -379,38 +379,38 @@ __global__ __launch_bounds__(kBlock) void reduce_partial_kernel(
 #pragma unroll
     for (int u = 0; u < U; ++u) s1[u] = s2[u] = 0.f;
     auto walk = [&](auto mask) {
-    constexpr int M = decltype(mask)::value;
-    uint32_t j = j0 + threadIdx.x;
-    for (; j + uint32_t(U - 1) * kBlock < j1; j += uint32_t(U) * kBlock) {
-        Vec<T, V> g[U], v[U];
+        constexpr int M = decltype(mask)::value;
+        uint32_t j = j0 + threadIdx.x;
+        for (; j + uint32_t(U - 1) * kBlock < j1; j += uint32_t(U) * kBlock) {
+            Vec<T, V> g[U], v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t ju = j + u * kBlock;
-            const uint32_t n = fdiv(ju, hwv_div);
-            const size_t off = cbase + n * nstride + size_t(ju - n * hwv) * V;
-            if (M & 2) g[u].load_nt(dy + off); else g[u].load(dy + off);
-            if (M & 1) v[u].load_nt(x + off); else v[u].load(x + off);
+            for (int u = 0; u < U; ++u) {
+                const uint32_t ju = j + u * kBlock;
+                const uint32_t n = fdiv(ju, hwv_div);
+                const size_t off = cbase + n * nstride + size_t(ju - n * hwv) * V;
+                if (M & 2) g[u].load_nt(dy + off); else g[u].load(dy + off);
+                if (M & 1) v[u].load_nt(x + off); else v[u].load(x + off);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    s1[u] += g[u].f[i];
+                    s2[u] = fmaf(g[u].f[i], v[u].f[i] - mu, s2[u]);
+                }
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (; j < j1; j += kBlock) {
+            const uint32_t n = fdiv(j, hwv_div);
+            const size_t off = cbase + n * nstride + size_t(j - n * hwv) * V;
+            Vec<T, V> g, v;
+            g.load(dy + off);
+            v.load(x + off);
 #pragma unroll
             for (int i = 0; i < V; ++i) {
-                s1[u] += g[u].f[i];
-                s2[u] = fmaf(g[u].f[i], v[u].f[i] - mu, s2[u]);
+                s1[0] += g.f[i];
+                s2[0] = fmaf(g.f[i], v.f[i] - mu, s2[0]);
             }
-    }
-    for (; j < j1; j += kBlock) {
-        const uint32_t n = fdiv(j, hwv_div);
-        const size_t off = cbase + n * nstride + size_t(j - n * hwv) * V;
-        Vec<T, V> g, v;
-        g.load(dy + off);
-        v.load(x + off);
-#pragma unroll
-        for (int i = 0; i < V; ++i) {
-            s1[0] += g.f[i];
-            s2[0] = fmaf(g.f[i], v.f[i] - mu, s2[0]);
         }
-    }
     };
     // the channels whose dy (and x) fit the memory-side cache take the loads that the mask asks for, the others
     // the non-temporal ones (the same for the whole block)

@@ -264,49 +264,49 @@ __device__ __forceinline__ void reduce_partial_body(const T* __restrict__ x, con
         }
         const size_t col = size_t(l.cv) * V;
         auto walk = [&](auto keep_dy, auto keep_x) {
-        constexpr bool KD = decltype(keep_dy)::value, KX = decltype(keep_x)::value;
-        uint32_t r = r0 + uint32_t(l.ty);
-        for (; r + TY < r1; r += 2u * TY) {
-            Vec<T, V> g[2], v[2];
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const size_t off = size_t(r + uint32_t(u) * TY) * t.C + col;
-                if (KD) g[u].load(dy + off); else g[u].load_nt(dy + off);
-                if (KX) v[u].load(x + off); else v[u].load_nt(x + off);
-            }
-#pragma unroll
-            for (int e = 0; e < V; ++e) {
-                A[e] += double(g[0].f[e] + g[1].f[e]);
-                Q[e] += double(fmaf(g[1].f[e], v[1].f[e] - mu[e], g[0].f[e] * (v[0].f[e] - mu[e])));
-            }
-            if (OUTSIDE) {
+            constexpr bool KD = decltype(keep_dy)::value, KX = decltype(keep_x)::value;
+            uint32_t r = r0 + uint32_t(l.ty);
+            for (; r + TY < r1; r += 2u * TY) {
+                Vec<T, V> g[2], v[2];
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
-                    const uint32_t row = r + uint32_t(u) * TY;
-                    if (!row_in(B, row)) {
+                    const size_t off = size_t(r + uint32_t(u) * TY) * t.C + col;
+                    if (KD) g[u].load(dy + off); else g[u].load_nt(dy + off);
+                    if (KX) v[u].load(x + off); else v[u].load_nt(x + off);
+                }
 #pragma unroll
-                        for (int e = 0; e < V; ++e) g[u].f[e] *= sc[e];
-                        g[u].store_nt(dx + size_t(row) * t.C + col);
+                for (int e = 0; e < V; ++e) {
+                    A[e] += double(g[0].f[e] + g[1].f[e]);
+                    Q[e] += double(fmaf(g[1].f[e], v[1].f[e] - mu[e], g[0].f[e] * (v[0].f[e] - mu[e])));
+                }
+                if (OUTSIDE) {
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        const uint32_t row = r + uint32_t(u) * TY;
+                        if (!row_in(B, row)) {
+#pragma unroll
+                            for (int e = 0; e < V; ++e) g[u].f[e] *= sc[e];
+                            g[u].store_nt(dx + size_t(row) * t.C + col);
+                        }
                     }
                 }
             }
-        }
-        for (; r < r1; r += TY) {
-            const size_t off = size_t(r) * t.C + col;
-            Vec<T, V> g, v;
-            if (KD) g.load(dy + off); else g.load_nt(dy + off);
-            if (KX) v.load(x + off); else v.load_nt(x + off);
+            for (; r < r1; r += TY) {
+                const size_t off = size_t(r) * t.C + col;
+                Vec<T, V> g, v;
+                if (KD) g.load(dy + off); else g.load_nt(dy + off);
+                if (KX) v.load(x + off); else v.load_nt(x + off);
 #pragma unroll
-            for (int e = 0; e < V; ++e) {
-                A[e] += double(g.f[e]);
-                Q[e] += double(g.f[e] * (v.f[e] - mu[e]));
-            }
-            if (OUTSIDE && !row_in(B, r)) {
+                for (int e = 0; e < V; ++e) {
+                    A[e] += double(g.f[e]);
+                    Q[e] += double(g.f[e] * (v.f[e] - mu[e]));
+                }
+                if (OUTSIDE && !row_in(B, r)) {
 #pragma unroll
-                for (int e = 0; e < V; ++e) g.f[e] *= sc[e];
-                g.store_nt(dx + off);
+                    for (int e = 0; e < V; ++e) g.f[e] *= sc[e];
+                    g.store_nt(dx + off);
+                }
             }
-        }
         };
         if constexpr (KEEP == 2) {
             walk(std::true_type(), std::true_type());
