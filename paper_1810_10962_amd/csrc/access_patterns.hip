@@ -14,6 +14,8 @@
 //   capped          `channel` with at most CAP loads in flight per thread
 //   sample-major    persistent blocks that each stream one contiguous run: the planes of G adjacent channels of
 //                   one sample
+//   read-only, write-only   flat passes that only load (both read tensors) or only store (the written one), with
+//                   and without the non-temporal hint: what the memory gives when reads and writes do not mix
 //   two passes      a read-only pass over two tensors (what a reduction does), then a pass that reads one of them
 //                   again and writes a third (what the element-wise pass after it does); timed: the second pass.
 //                   The first pass loads the tensor that is read again either like everything else, with the
@@ -50,6 +52,24 @@ __global__ __launch_bounds__(256) void flat_kernel(const v4* __restrict__ g, con
                                                     size_t n) {
     const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
     if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(g + i) * 0.5f + __builtin_nontemporal_load(x + i), o + i);
+}
+
+// read-only and write-only flat passes
+template <bool NTH>
+__global__ __launch_bounds__(256) void loads_kernel(const v4* __restrict__ g, const v4* __restrict__ x, float* __restrict__ out,
+                                                    size_t n) {
+    const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n) return;
+    const v4 a = NTH ? __builtin_nontemporal_load(g + i) : g[i];
+    const v4 b = NTH ? __builtin_nontemporal_load(x + i) : x[i];
+    if (a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w == 12345.678f) out[0] = 1.f;      // (never: keeps the loads)
+}
+template <bool NTH>
+__global__ __launch_bounds__(256) void stores_kernel(v4* __restrict__ o, size_t n, float s) {
+    const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n) return;
+    const v4 v = {s, s + 1.f, s + 2.f, float(threadIdx.x)};
+    if (NTH) __builtin_nontemporal_store(v, o + i); else o[i] = v;
 }
 
 // two passes: first pass (g plain or non-temporal, x non-temporal), second pass (g non-temporal -> o non-temporal)
@@ -252,9 +272,47 @@ int main() {
         hipLaunchKernelGGL((sample_major_kernel<448, 4, 2>), dim3(N * 16), dim3(448), 0, 0, G[s], X[s], O[s], 16);
     });
 
-    // two passes over n vectors (the whole fp32 tensor, and half of it: the same tensor in bf16)
     float* flag = nullptr;
     CK(hipMalloc(&flag, sizeof(float)));
+    {
+        // (run() prints bytes of three tensors over the time: scaled here to what these passes move)
+        auto timed = [&](const char* label, double tensors, auto launch) {
+            std::vector<float> ts;
+            for (int it = 0; it < 30; ++it) {
+                (void)hipEventRecord(e0, 0);
+                launch(it % kSets);
+                (void)hipEventRecord(e1, 0);
+                (void)hipEventSynchronize(e1);
+                float ms = 0.f;
+                (void)hipEventElapsedTime(&ms, e0, e1);
+                if (it >= 6) ts.push_back(ms);
+            }
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) {
+                printf("%-72s launch error %s\n", label, hipGetErrorString(e));
+                exit(1);
+            }
+            std::sort(ts.begin(), ts.end());
+            const float med = ts[ts.size() / 2];
+            printf("%-72s %7.1f us (fastest %6.1f)  %5.0f GB/s\n", label, med * 1e3, ts[0] * 1e3, tensors * bytes / med / 1e6);
+            fflush(stdout);
+        };
+        const dim3 grid(unsigned((kVectors + 255) / 256));
+        timed("read-only flat (x and dy), non-temporal loads", 2.0, [&](int s) {
+            hipLaunchKernelGGL(loads_kernel<true>, grid, dim3(256), 0, 0, G[s], X[s], flag, kVectors);
+        });
+        timed("read-only flat (x and dy), plain loads", 2.0, [&](int s) {
+            hipLaunchKernelGGL(loads_kernel<false>, grid, dim3(256), 0, 0, G[s], X[s], flag, kVectors);
+        });
+        timed("write-only flat (dx), non-temporal stores", 1.0, [&](int s) {
+            hipLaunchKernelGGL(stores_kernel<true>, grid, dim3(256), 0, 0, O[s], kVectors, float(s));
+        });
+        timed("write-only flat (dx), plain stores", 1.0, [&](int s) {
+            hipLaunchKernelGGL(stores_kernel<false>, grid, dim3(256), 0, 0, O[s], kVectors, float(s));
+        });
+    }
+
+    // two passes over n vectors (the whole fp32 tensor, and half of it: the same tensor in bf16)
     for (size_t n : {kVectors, kVectors / 2})
         for (int keep = 0; keep < 2; ++keep) {
             std::vector<float> t1, t2;
